@@ -1,0 +1,313 @@
+/*
+ * ogq_oracle.c -- plain CPU oracle for per-bucket optimal gradient quantization.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of what the
+ * GPU library must compute.  Only the test-suite, the smoke check and the benchmark's
+ * "cpu_baseline" leg may build, load or call it.  It shares no code, header, table or helper
+ * with the HIP implementation and neither side includes the other.
+ *
+ * Source: "Optimal Gradient Quantization Condition for Communication-Efficient Distributed
+ * Training" (Xu, Huo, Huang; arXiv 2002.11082).  Each function names the passage it follows.
+ * Arithmetic is double precision over the fp32 inputs, except the stochastic-rounding test,
+ * which decides an integer code and is therefore taken in fp32 exactly as the device takes it.
+ *
+ * Pins (see tests/test_oracle_*.py): Philox known-answer vectors; Q* against exhaustive
+ * minimisation of the discrete rounding error in exact rationals; s=3 global optimum; sweeps
+ * never increase the error and end coordinate-wise optimal; uniform data gives the midpoint
+ * (Remark after Theorem 1); endpoints are min/max (Corollary 1); BinGrad-b levels are the
+ * conditional means, reduce to Scaled SignSGD on +-paired data and converge to 1-D 2-means;
+ * random rounding is unbiased with variance (v-b_k)(b_{k+1}-v) by Monte Carlo; pack/unpack
+ * round trip and hand-placed bits; decode-average special cases.
+ * No function here is "parity unpinned".
+ *
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC ogq_oracle.c -o libogq_oracle.so -lm
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_BINGRAD_B = 0, ORACLE_ORQ = 1 };
+
+/* ------------------------------------------------------------------------------------------
+ * Counter-based random numbers: Philox4x32 with 10 rounds, as published by Salmon, Moraes,
+ * Dror and Shaw ("Parallel random numbers: as easy as 1, 2, 3", SC'11).  The paper does not
+ * name a generator; the build's problem statement fixes this one.
+ * ---------------------------------------------------------------------------------------- */
+void ogq_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t prod_a = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        uint64_t prod_b = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(prod_b >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)prod_b;
+        uint32_t n2 = (uint32_t)(prod_a >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)prod_a;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The uniform draw that belongs to the element with global index `index`:
+ * four consecutive elements share one Philox block; the block counter is index/4 (64-bit,
+ * split over the first two counter words), the key is the 64-bit seed, the element takes
+ * word index%4, and the top 24 bits of that word give u in [0,1) on a 2^-24 grid. */
+float ogq_oracle_uniform(uint64_t seed, uint64_t index)
+{
+    uint64_t block = index >> 2;
+    uint32_t ctr[4] = { (uint32_t)block, (uint32_t)(block >> 32), 0u, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t r[4];
+    ogq_oracle_philox4x32_10(ctr, key, r);
+    return (float)(r[index & 3u] >> 8) * 0x1p-24f;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * BinGrad-b (Section 3.2, the deterministic two-level scheme and its optimal condition).
+ * The threshold b0 starts at the bucket mean (the paper's stated implementation shortcut);
+ * b_{-1} and b_1 are the means of the elements below / not below b0; each further iteration
+ * moves b0 to the midpoint of the two levels (first relation of the optimal condition) and
+ * recomputes the conditional means.  An empty lower side (constant bucket) takes b_{-1}=b_1.
+ * Outputs: levels[0]=b_{-1}, levels[1]=b_1 rounded to fp32, *b0_out = the threshold of the
+ * partition that produced them (code = v >= b0).
+ * ---------------------------------------------------------------------------------------- */
+void ogq_oracle_bingrad_bucket(const float* g, size_t n, uint32_t iters, float levels[2], float* b0_out)
+{
+    double total = 0.0;
+    for (size_t i = 0; i < n; ++i) total += (double)g[i];
+    float b0 = (float)(total / (double)n);
+    double b_lo = 0.0, b_hi = 0.0;
+    for (uint32_t it = 0;; ++it) {
+        double sum_lo = 0.0, sum_hi = 0.0;
+        size_t n_lo = 0, n_hi = 0;
+        for (size_t i = 0; i < n; ++i) {
+            if (g[i] < b0) { sum_lo += (double)g[i]; ++n_lo; }
+            else           { sum_hi += (double)g[i]; ++n_hi; }
+        }
+        if (n_hi > 0) b_hi = sum_hi / (double)n_hi;
+        if (n_lo > 0) b_lo = sum_lo / (double)n_lo;
+        if (n_lo == 0) b_lo = b_hi;
+        if (n_hi == 0) b_hi = b_lo;
+        if (it == iters) break;
+        b0 = (float)((b_lo + b_hi) * 0.5);
+    }
+    levels[0] = (float)b_lo;
+    levels[1] = (float)b_hi;
+    *b0_out = b0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * ORQ: one solve of the optimal condition for the middle level of three (Theorem 1, in the
+ * simplified form of the second remark and its discrete version).
+ *
+ * With outer levels L < R fixed, the expected random-rounding error of the elements in [L,R],
+ *     D(b) = sum_{L<=v<=b} (v-L)(b-v) + sum_{b<v<=R} (v-b)(R-v),
+ * is continuous and piecewise linear in b with right-slope  S - (R-L) * #{b < v <= R},
+ * where S = sum_{L<=v<=R} (v-L) is the numerator of the remark's right-hand side.  The slope
+ * is non-decreasing in b, so D is minimal at the smallest data value b whose count
+ * #{b < v <= R} does not exceed T = S/(R-L): the discrete optimal condition read as
+ * "count above b_k equals the right-hand side", resolved to the exact minimiser.  When the
+ * slope is exactly zero on an interval every point of it is optimal; the lower end is taken.
+ *
+ * x[0..n) must be sorted ascending.  Returns the level value.
+ * ---------------------------------------------------------------------------------------- */
+float ogq_oracle_qstar(const float* x, size_t n, float L, float R)
+{
+    if (!(L < R)) return L;
+    double S = 0.0;
+    size_t count_le_R = 0;
+    for (size_t t = 0; t < n; ++t) {
+        if (x[t] <= R) {
+            ++count_le_R;
+            if (x[t] >= L) S += (double)x[t] - (double)L;
+        }
+    }
+    double T = S / ((double)R - (double)L);
+    double m = floor(T);                       /* how many elements may lie above b */
+    size_t rank;                               /* 1-based rank of b among the sorted bucket */
+    if (m >= (double)count_le_R) rank = 1;
+    else rank = count_le_R - (size_t)m;
+    if (rank < 1) rank = 1;
+    float b = x[rank - 1];
+    if (b < L) b = L;
+    return b;
+}
+
+static int cmp_float_asc(const void* pa, const void* pb)
+{
+    float a = *(const float*)pa, b = *(const float*)pb;
+    return (a > b) - (a < b);
+}
+
+/* Greedy recursive placement (Algorithm 1): the level in the middle of [l, r] is the solve
+ * between the two outer levels, then both halves are treated the same way.  The paper states
+ * it for s = 2^K + 1 levels, where (l+r)/2 is always an integer; for other s the middle index
+ * is rounded down.  The recursion ends when no index lies strictly between l and r. */
+static void orq_place(const float* x, size_t n, float* b, int l, int r)
+{
+    if (r - l < 2) return;
+    int mid = (l + r) / 2;
+    b[mid] = ogq_oracle_qstar(x, n, b[l], b[r]);
+    orq_place(x, n, b, l, mid);
+    orq_place(x, n, b, mid, r);
+}
+
+/* ORQ levels of one bucket: endpoints are the bucket minimum and maximum (Corollary 1), the
+ * interior comes from the greedy placement, and `sweeps` rounds of re-solving every interior
+ * level between its current neighbours (k ascending) move the greedy result towards a
+ * solution of the coupled condition of Theorem 1.  `s` levels are written, non-decreasing. */
+void ogq_oracle_orq_levels_bucket(const float* g, size_t n, uint32_t s, uint32_t sweeps, float* levels)
+{
+    float* x = (float*)malloc(n * sizeof(float));
+    memcpy(x, g, n * sizeof(float));
+    qsort(x, n, sizeof(float), cmp_float_asc);
+    levels[0] = x[0];
+    levels[s - 1] = x[n - 1];
+    for (uint32_t k = 1; k + 1 < s; ++k) levels[k] = x[0];
+    orq_place(x, n, levels, 0, (int)s - 1);
+    for (uint32_t sw = 0; sw < sweeps; ++sw)
+        for (uint32_t k = 1; k + 1 < s; ++k)
+            levels[k] = ogq_oracle_qstar(x, n, levels[k - 1], levels[k + 1]);
+    free(x);
+}
+
+/* Random rounding of one element (Section 3.1): v in [b_k, b_{k+1}] goes up to b_{k+1} with
+ * probability (v-b_k)/(b_{k+1}-b_k).  k is the last level not above v (at most s-2); the
+ * probability test is the division-free u*w < delta, in fp32, one rounding per operation. */
+uint32_t ogq_oracle_orq_encode_element(float v, const float* levels, uint32_t s, float u)
+{
+    uint32_t not_above = 0;
+    for (uint32_t k = 0; k < s; ++k) if (levels[k] <= v) ++not_above;
+    uint32_t k = not_above > 0 ? not_above - 1 : 0;
+    if (k > s - 2) k = s - 2;
+    float w = levels[k + 1] - levels[k];
+    float delta = v - levels[k];
+    float scaled = u * w;
+    return k + (scaled < delta ? 1u : 0u);
+}
+
+/* Bit-plane packing: element i sits in group i/64 at lane i%64; bit `lane` of 64-bit word
+ * group*bits + p is bit p of the element's code. */
+void ogq_oracle_pack(const uint8_t* codes, size_t n, uint32_t bits, uint64_t* words)
+{
+    size_t groups = (n + 63) / 64;
+    memset(words, 0, groups * bits * sizeof(uint64_t));
+    for (size_t i = 0; i < n; ++i)
+        for (uint32_t p = 0; p < bits; ++p)
+            if ((codes[i] >> p) & 1u) words[(i / 64) * bits + p] |= (uint64_t)1 << (i % 64);
+}
+
+void ogq_oracle_unpack(const uint64_t* words, size_t n, uint32_t bits, uint8_t* codes)
+{
+    for (size_t i = 0; i < n; ++i) {
+        uint32_t c = 0;
+        for (uint32_t p = 0; p < bits; ++p)
+            c |= (uint32_t)((words[(i / 64) * bits + p] >> (i % 64)) & 1u) << p;
+        codes[i] = (uint8_t)c;
+    }
+}
+
+/* Quantize a whole gradient bucket by bucket (bucket-based quantization, Section 5; the last
+ * bucket is shorter when bucket_size does not divide n).  Writes (n/bucket_size rounded up)
+ * * 2^bits level floats, one unpacked code per element, and, when thresholds != NULL and the
+ * scheme is BinGrad-b, one b0 per bucket.  Returns 0, or -1 on bad arguments. */
+int ogq_oracle_quantize_codes(const float* g, size_t n, uint32_t bucket_size, uint32_t bits,
+                              uint32_t scheme, uint32_t level_iters, uint64_t seed,
+                              uint64_t index_offset, float* levels, uint8_t* codes,
+                              float* thresholds)
+{
+    if (!g || !levels || !codes || bucket_size == 0 || bits == 0 || bits > 8) return -1;
+    if (scheme == ORACLE_BINGRAD_B && bits != 1) return -1;
+    if (scheme != ORACLE_BINGRAD_B && scheme != ORACLE_ORQ) return -1;
+    uint32_t s = 1u << bits;
+    long long num_buckets = (long long)((n + bucket_size - 1) / bucket_size);
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (long long b = 0; b < num_buckets; ++b) {
+        size_t begin = (size_t)b * bucket_size;
+        size_t len = n - begin < bucket_size ? n - begin : bucket_size;
+        const float* gb = g + begin;
+        float* lv = levels + (size_t)b * s;
+        if (scheme == ORACLE_BINGRAD_B) {
+            float b0;
+            ogq_oracle_bingrad_bucket(gb, len, level_iters, lv, &b0);
+            if (thresholds) thresholds[b] = b0;
+            for (size_t i = 0; i < len; ++i) codes[begin + i] = gb[i] >= b0 ? 1 : 0;
+        } else {
+            ogq_oracle_orq_levels_bucket(gb, len, s, level_iters, lv);
+            for (size_t i = 0; i < len; ++i) {
+                float u = ogq_oracle_uniform(seed, index_offset + begin + i);
+                codes[begin + i] = (uint8_t)ogq_oracle_orq_encode_element(gb[i], lv, s, u);
+            }
+        }
+    }
+    return 0;
+}
+
+/* Quantize + pack: what one worker sends (Algorithm 2, "compute levels / quantize / encode"). */
+int ogq_oracle_quantize(const float* g, size_t n, uint32_t bucket_size, uint32_t bits,
+                        uint32_t scheme, uint32_t level_iters, uint64_t seed,
+                        uint64_t index_offset, float* levels, uint64_t* words)
+{
+    if (!words) return -1;
+    uint8_t* codes = (uint8_t*)malloc(n ? n : 1);
+    int rc = ogq_oracle_quantize_codes(g, n, bucket_size, bits, scheme, level_iters, seed,
+                                       index_offset, levels, codes, NULL);
+    if (rc == 0) ogq_oracle_pack(codes, n, bits, words);
+    free(codes);
+    return rc;
+}
+
+/* Server side of Algorithm 2: decode every worker's stream with that worker's levels and
+ * average: out_i = (1/W) * sum_w levels_w[bucket(i)][code_{w,i}], summed in double. */
+int ogq_oracle_dequantize_average(const uint64_t* const* words, const float* const* levels,
+                                  uint32_t num_workers, size_t n, uint32_t bucket_size,
+                                  uint32_t bits, float* out)
+{
+    if (!words || !levels || !out || num_workers == 0 || bucket_size == 0 || bits == 0 || bits > 8)
+        return -1;
+    uint32_t s = 1u << bits;
+    long long nn = (long long)n;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (long long i = 0; i < nn; ++i) {
+        size_t bucket = (size_t)i / bucket_size;
+        double acc = 0.0;
+        for (uint32_t w = 0; w < num_workers; ++w) {
+            uint32_t c = 0;
+            for (uint32_t p = 0; p < bits; ++p)
+                c |= (uint32_t)((words[w][((size_t)i / 64) * bits + p] >> ((size_t)i % 64)) & 1u) << p;
+            acc += (double)levels[w][bucket * s + c];
+        }
+        out[i] = (float)(acc / (double)num_workers);
+    }
+    return 0;
+}
+
+int ogq_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void ogq_oracle_set_threads(int t)
+{
+#ifdef _OPENMP
+    if (t > 0) omp_set_num_threads(t);
+#else
+    (void)t;
+#endif
+}
