@@ -1,0 +1,712 @@
+// libogq: per-bucket optimal gradient quantization for MI355X (gfx950, wave64).
+//
+// Method: "Optimal Gradient Quantization Condition for Communication-Efficient Distributed
+// Training" (arXiv 2002.11082).  One wavefront owns one bucket from the HBM load to the packed
+// store, so the gradient is read exactly once:
+//   BinGrad-b (Section 3.2): fp64 wave reductions for the mean and the two conditional means,
+//     the code bit of 64 consecutive elements is the ballot of (v >= b0).
+//   ORQ (Theorem 1, its discrete remark, Corollary 1, Algorithm 1; random rounding of
+//     Section 3.1): every level solve is a range sum plus an exact rank selection over the
+//     register-resident bucket; Philox4x32-10 draws keyed by (seed, global element index).
+//   Decode-average (server step of Algorithm 2): the packed 64-bit words are used directly as
+//     lane masks of v_cndmask selects over the bucket's level table.
+//
+// Compile with -ffp-contract=off: the rounding decision of ORQ is specified op by op in fp32.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ogq.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+
+thread_local int g_last_hip_error = 0;
+
+// ----------------------------------------------------------------------------------------------
+// wave-level helpers
+// ----------------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, kWave);
+    return x;
+}
+
+__device__ __forceinline__ float wave_min(float x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x = fminf(x, __shfl_xor(x, off, kWave));
+    return x;
+}
+
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
+    return x;
+}
+
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+
+__device__ __forceinline__ float uniform_f32(float x)
+{
+    return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(x)));
+}
+
+__device__ __forceinline__ double uniform_f64(double x)
+{
+    uint64_t u = (uint64_t)__double_as_longlong(x);
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u);
+    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// ----------------------------------------------------------------------------------------------
+// BinGrad-b quantize.  Lane l register j holds bucket element 64*j + l, so a ballot over
+// register j is the packed code word j of the bucket.
+// ----------------------------------------------------------------------------------------------
+template <int E, bool FULL>
+__device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint32_t len, uint32_t iters,
+                                               float* __restrict__ levels2, uint64_t* __restrict__ words)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    float v[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        const uint32_t e = 64u * j + lane;
+        v[j] = (FULL || e < len) ? g[e] : 0.0f;
+    }
+
+    double part = 0.0;
+#pragma unroll
+    for (int j = 0; j < E; ++j) part += (double)v[j];
+    const double total = uniform_f64(wave_sum(part));
+    float b0 = (float)(total / (double)len);  // threshold starts at the bucket mean
+
+    double b_lo = 0.0, b_hi = 0.0;
+    uint64_t my_word = 0;
+    uint32_t prev_n_lo = 0xFFFFFFFFu;
+    for (uint32_t it = 0;; ++it) {
+        double s_lo = 0.0, s_hi = 0.0;
+        uint32_t n_lo = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            const bool valid = FULL || (64u * j + lane < len);
+            const bool lo = valid && (v[j] < b0);
+            const bool hi = valid && !lo;
+            const uint64_t hi_mask = __ballot(hi);
+            n_lo += (uint32_t)__popcll(__ballot(lo));
+            const double dv = (double)v[j];
+            s_lo += lo ? dv : 0.0;
+            s_hi += hi ? dv : 0.0;
+            if (lane == (uint32_t)j) my_word = hi_mask;
+        }
+        s_lo = uniform_f64(wave_sum(s_lo));
+        s_hi = uniform_f64(wave_sum(s_hi));
+        const uint32_t n_hi = len - n_lo;
+        if (n_hi > 0) b_hi = s_hi / (double)n_hi;
+        if (n_lo > 0) b_lo = s_lo / (double)n_lo;
+        if (n_lo == 0) b_lo = b_hi;  // constant bucket: both levels equal
+        if (n_hi == 0) b_hi = b_lo;
+        // Further threshold updates are identities once the partition repeats.
+        if (it == iters || n_lo == prev_n_lo) break;
+        prev_n_lo = n_lo;
+        b0 = (float)((b_lo + b_hi) * 0.5);
+    }
+
+    if (lane == 0) {
+        levels2[0] = (float)b_lo;
+        levels2[1] = (float)b_hi;
+    }
+    const uint32_t n_words = (len + 63u) / 64u;
+    if (lane < n_words) words[lane] = my_word;
+}
+
+template <int E>
+__global__ __launch_bounds__(kBlock) void bingrad_quantize_kernel(const float* __restrict__ grad, size_t n,
+                                                                  uint32_t bucket_size, uint32_t iters,
+                                                                  uint32_t num_buckets, float* __restrict__ levels,
+                                                                  uint64_t* __restrict__ codes)
+{
+    const uint32_t bucket = uniform_u32(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    if (bucket >= num_buckets) return;
+    const size_t begin = (size_t)bucket * bucket_size;
+    const size_t rest = n - begin;
+    const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
+    const float* g = grad + begin;
+    float* lv = levels + (size_t)bucket * 2;
+    uint64_t* w = codes + begin / 64;
+    if (len == 64u * E) bingrad_bucket<E, true>(g, len, iters, lv, w);
+    else bingrad_bucket<E, false>(g, len, iters, lv, w);
+}
+
+// ----------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter (c0, c1, 0, 0), key (k0, k1).
+// ----------------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1, uint32_t (&r)[4])
+{
+    uint32_t c2 = 0, c3 = 0;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t pa = (uint64_t)0xD2511F53u * c0;
+        const uint64_t pb = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)pb;
+        c3 = (uint32_t)pa;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    r[0] = c0; r[1] = c1; r[2] = c2; r[3] = c3;
+}
+
+// ----------------------------------------------------------------------------------------------
+// ORQ quantize.  Lane l holds, for chunk c, the four consecutive bucket elements
+// 256*c + 4*l + {0,1,2,3} (one 16-byte load), which are also the four elements that share one
+// Philox block.
+// ----------------------------------------------------------------------------------------------
+// Order-preserving map of fp32 onto unsigned integers (-0 sorts just below +0).
+__device__ __forceinline__ uint32_t float_to_key(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+}
+
+__device__ __forceinline__ float key_to_float(uint32_t k)
+{
+    const uint32_t u = (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
+    return __uint_as_float(u);
+}
+
+template <int C>
+struct OrqBucket {
+    float v[C][4];       // values; padding = +inf
+    uint32_t key[C][4];  // ordered keys; padding = 0xFFFFFFFF
+};
+
+// Value of 1-based rank `rank` among the bucket's elements: the largest key K with
+// #{key < K} < rank, built bit by bit from the top.
+template <int C>
+__device__ __forceinline__ float select_rank(const OrqBucket<C>& b, uint32_t rank)
+{
+    uint32_t prefix = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = prefix | (1u << bit);
+        uint32_t below = 0;
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) below += (uint32_t)__popcll(__ballot(b.key[c][k] < cand));
+        if (below < rank) prefix = cand;
+    }
+    return key_to_float(prefix);
+}
+
+// One solve of the discrete optimal condition for the level between L and R: with
+// S = sum_{L<=v<=R} (v - L) and T = S / (R - L), the level is the smallest bucket value b with
+// #{b < v <= R} <= T, i.e. the value of rank #{v <= R} - floor(T).
+template <int C>
+__device__ __forceinline__ float orq_solve(const OrqBucket<C>& b, float L, float R)
+{
+    if (!(L < R)) return L;
+    const double dL = (double)L;
+    double part = 0.0;
+    uint32_t count_le_R = 0;
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float x = b.v[c][k];
+            const bool le = x <= R;
+            count_le_R += (uint32_t)__popcll(__ballot(le));
+            part += (le && x >= L) ? ((double)x - dL) : 0.0;
+        }
+    const double S = uniform_f64(wave_sum(part));
+    const double T = S / ((double)R - dL);
+    const double m = floor(T);
+    uint32_t rank = (m >= (double)count_le_R) ? 1u : count_le_R - (uint32_t)m;
+    if (rank < 1u) rank = 1u;
+    float lvl = select_rank<C>(b, rank);
+    if (lvl < L) lvl = L;
+    return lvl;
+}
+
+// Order of the greedy solves (Algorithm 1): the level in the middle of [l, r] is solved from the
+// two outer levels, then both halves are treated the same way; the middle index is rounded down
+// when s is not of the form 2^K + 1.  Each step is packed as 3 bits of k, l, r.
+struct GreedyOrder {
+    uint64_t packed;
+    int count;
+};
+
+constexpr void greedy_visit(GreedyOrder& o, int l, int r)
+{
+    if (r - l < 2) return;
+    const int mid = (l + r) / 2;
+    o.packed |= (uint64_t)(mid | (l << 3) | (r << 6)) << (9 * o.count);
+    ++o.count;
+    greedy_visit(o, l, mid);
+    greedy_visit(o, mid, r);
+}
+
+template <int S>
+constexpr GreedyOrder greedy_order()
+{
+    GreedyOrder o{0, 0};
+    greedy_visit(o, 0, S - 1);
+    return o;
+}
+
+template <int S>
+__device__ __forceinline__ float pick_level(const float (&lv)[S], uint32_t i)
+{
+    float r = lv[0];
+#pragma unroll
+    for (int k = 1; k < S; ++k) r = (i == (uint32_t)k) ? lv[k] : r;
+    return r;
+}
+
+template <int C, int BITS>
+__global__ __launch_bounds__(kBlock) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
+                                                              uint32_t bucket_size, uint32_t sweeps,
+                                                              uint32_t num_buckets, uint64_t seed,
+                                                              uint64_t index_offset, float* __restrict__ levels,
+                                                              uint32_t* __restrict__ codes32)
+{
+    constexpr int S = 1 << BITS;
+    const uint32_t bucket = uniform_u32(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    if (bucket >= num_buckets) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const size_t begin = (size_t)bucket * bucket_size;
+    const size_t rest = n - begin;
+    const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
+    const float* g = grad + begin;
+
+    OrqBucket<C> b;
+    const float inf = __uint_as_float(0x7F800000u);
+    if (len == 256u * C) {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const float4 q = *reinterpret_cast<const float4*>(g + 256 * c + 4 * lane);
+            b.v[c][0] = q.x; b.v[c][1] = q.y; b.v[c][2] = q.z; b.v[c][3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t e = 256u * c + 4u * lane + k;
+                b.v[c][k] = e < len ? g[e] : inf;
+            }
+    }
+    float lo = inf, hi = -inf;
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t e = 256u * c + 4u * lane + k;
+            const bool valid = e < len;
+            b.key[c][k] = valid ? float_to_key(b.v[c][k]) : 0xFFFFFFFFu;
+            lo = fminf(lo, b.v[c][k]);
+            hi = fmaxf(hi, valid ? b.v[c][k] : -inf);
+        }
+
+    // Levels: ends are the bucket extremes (Corollary 1), interior by greedy recursion
+    // (Algorithm 1, middle index rounded down when s is not 2^K + 1), then re-solve sweeps.
+    float lv[S];
+    lv[0] = uniform_f32(wave_min(lo));
+    lv[S - 1] = uniform_f32(wave_max(hi));
+#pragma unroll
+    for (int k = 1; k < S - 1; ++k) lv[k] = lv[0];
+    if constexpr (S > 2) {
+        constexpr GreedyOrder order = greedy_order<S>();
+        const uint32_t steps = order.count + sweeps * (S - 2);
+        for (uint32_t t = 0; t < steps; ++t) {
+            uint32_t k, l, r;
+            if (t < (uint32_t)order.count) {
+                const uint32_t e = (uint32_t)(order.packed >> (9 * t));
+                k = e & 7u; l = (e >> 3) & 7u; r = (e >> 6) & 7u;
+            } else {
+                k = 1u + (t - order.count) % (S - 2);
+                l = k - 1u; r = k + 1u;
+            }
+            const float solved = orq_solve<C>(b, pick_level<S>(lv, l), pick_level<S>(lv, r));
+#pragma unroll
+            for (int i = 1; i < S - 1; ++i) lv[i] = (k == (uint32_t)i) ? solved : lv[i];
+        }
+    }
+
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < S; ++k) levels[(size_t)bucket * S + k] = lv[k];
+    }
+
+    // Encode + pack.
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint32_t padded_len = (len + 63u) & ~63u;
+    const size_t word0 = begin / 64;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const uint64_t block = (index_offset + begin + 256u * c + 4u * lane) >> 2;
+        uint32_t r[4];
+        philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), k0, k1, r);
+        uint32_t plane[BITS];
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) plane[p] = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float x = b.v[c][k];
+            const bool valid = 256u * c + 4u * lane + k < len;
+            // interval index: last level not above x, at most S-2
+            uint32_t idx = 0;
+            float base = lv[0], next = lv[1];
+#pragma unroll
+            for (int t = 1; t < S - 1; ++t) {
+                const bool ge = lv[t] <= x;
+                idx += ge ? 1u : 0u;
+                base = ge ? lv[t] : base;
+                next = ge ? lv[t + 1] : next;
+            }
+            const float w = next - base;
+            const float delta = x - base;
+            const float u = (float)(r[k] >> 8) * 0x1p-24f;
+            const float scaled = u * w;
+            uint32_t code = idx + (scaled < delta ? 1u : 0u);
+            code = valid ? code : 0u;
+#pragma unroll
+            for (int p = 0; p < BITS; ++p) plane[p] |= ((code >> p) & 1u) << (4u * (lane & 7u) + k);
+        }
+        // OR over the 8 lanes that make up one 32-bit half of a packed word.
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) {
+            uint32_t x = plane[p];
+            x |= __shfl_xor(x, 1, kWave);
+            x |= __shfl_xor(x, 2, kWave);
+            x |= __shfl_xor(x, 4, kWave);
+            const uint32_t first = 256u * c + 32u * (lane >> 3);  // first element of this half-word
+            if ((lane & 7u) == 0 && first < padded_len) {
+                const size_t word = (word0 + 4u * c + (lane >> 4)) * BITS + p;
+                codes32[word * 2 + ((lane >> 3) & 1u)] = x;
+            }
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Decode + average.  One wavefront decodes a segment of up to 16 packed words (1024 elements)
+// that lies inside one bucket; lane l owns element 64*j + l of word j, so the packed words are
+// the lane masks of the level selects.
+// ----------------------------------------------------------------------------------------------
+struct WorkerPtrs {
+    const uint64_t* codes[OGQ_MAX_WORKERS];
+    const float* levels[OGQ_MAX_WORKERS];
+};
+
+constexpr int kSegWords = 16;
+
+template <int BITS>
+__device__ __forceinline__ float select_level(const uint64_t* __restrict__ w, const float (&lv)[1 << BITS])
+{
+    bool bit[BITS];
+#pragma unroll
+    for (int p = 0; p < BITS; ++p) bit[p] = __builtin_amdgcn_inverse_ballot_w64(w[p]);
+    if constexpr (BITS == 1) {
+        return bit[0] ? lv[1] : lv[0];
+    } else if constexpr (BITS == 2) {
+        const float a = bit[0] ? lv[1] : lv[0];
+        const float b = bit[0] ? lv[3] : lv[2];
+        return bit[1] ? b : a;
+    } else {
+        const float a = bit[0] ? lv[1] : lv[0];
+        const float b = bit[0] ? lv[3] : lv[2];
+        const float c = bit[0] ? lv[5] : lv[4];
+        const float d = bit[0] ? lv[7] : lv[6];
+        const float ab = bit[1] ? b : a;
+        const float cd = bit[1] ? d : c;
+        return bit[2] ? cd : ab;
+    }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs ptrs, uint32_t num_workers, size_t n,
+                                                                    uint32_t bucket_size, uint32_t segs_per_bucket,
+                                                                    uint64_t num_segments, double inv_workers,
+                                                                    float* __restrict__ out)
+{
+    constexpr int S = 1 << BITS;
+    const uint64_t seg = (uint64_t)blockIdx.x * kWavesPerBlock + uniform_u32(threadIdx.x >> 6);
+    if (seg >= num_segments) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t bucket = seg / segs_per_bucket;
+    const uint32_t seg_in_bucket = (uint32_t)(seg - bucket * segs_per_bucket);
+    const size_t begin = (size_t)bucket * bucket_size + (size_t)seg_in_bucket * (kSegWords * 64);
+    if (begin >= n) return;
+    size_t end = begin + kSegWords * 64;
+    const size_t bucket_end = (size_t)(bucket + 1) * bucket_size;
+    if (end > bucket_end) end = bucket_end;
+    if (end > n) end = n;
+    const uint32_t len = (uint32_t)(end - begin);
+    const uint32_t n_words = uniform_u32((len + 63u) / 64u);
+    const size_t word0 = begin / 64;
+
+    double acc[kSegWords];
+#pragma unroll
+    for (int j = 0; j < kSegWords; ++j) acc[j] = 0.0;
+
+    for (uint32_t w = 0; w < num_workers; ++w) {
+        const float* __restrict__ lvp = ptrs.levels[w] + (size_t)bucket * S;
+        const uint64_t* __restrict__ cw = ptrs.codes[w] + word0 * BITS;
+        float lv[S];
+#pragma unroll
+        for (int k = 0; k < S; ++k) lv[k] = lvp[k];
+        if (n_words == kSegWords) {
+#pragma unroll
+            for (int j = 0; j < kSegWords; ++j) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+        } else {
+#pragma unroll
+            for (int j = 0; j < kSegWords; ++j)
+                if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kSegWords; ++j) {
+        const uint32_t e = 64u * j + lane;
+        if (e < len) out[begin + e] = (float)(acc[j] * inv_workers);
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Bandwidth probes.
+// ----------------------------------------------------------------------------------------------
+constexpr uint32_t kProbeBlocks = 256 * 8;
+
+__global__ __launch_bounds__(kBlock) void probe_read_kernel(const float4* __restrict__ src, size_t n4,
+                                                            float* __restrict__ sink)
+{
+    float acc = 0.f;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (size_t)gridDim.x * kBlock) {
+        const float4 q = src[i];
+        acc += (q.x + q.y) + (q.z + q.w);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+    if ((threadIdx.x & 63u) == 0) sink[blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)] = acc;
+}
+
+__global__ __launch_bounds__(kBlock) void probe_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                            size_t n4)
+{
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (size_t)gridDim.x * kBlock)
+        dst[i] = src[i];
+}
+
+// ----------------------------------------------------------------------------------------------
+// host side
+// ----------------------------------------------------------------------------------------------
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_params(const ogq_params_t* p, bool need_scheme)
+{
+    if (!p) return OGQ_ERR_NULL_POINTER;
+    if (p->bucket_size == 0 || p->bucket_size % 64 != 0 || p->bucket_size > OGQ_MAX_BUCKET_SIZE)
+        return OGQ_ERR_BUCKET_SIZE;
+    if (need_scheme) {
+        if (p->scheme == OGQ_BINGRAD_B) {
+            if (p->bits != 1) return OGQ_ERR_BITS;
+        } else if (p->scheme == OGQ_ORQ) {
+            if (p->bits < 1 || p->bits > 3) return OGQ_ERR_BITS;
+        } else {
+            return OGQ_ERR_SCHEME;
+        }
+        if (p->index_offset % 64 != 0) return OGQ_ERR_INDEX_OFFSET;
+    } else if (p->bits < 1 || p->bits > 3) {
+        return OGQ_ERR_BITS;
+    }
+    return OGQ_OK;
+}
+
+int finish_launch()
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return OGQ_ERR_LAUNCH;
+    }
+    return OGQ_OK;
+}
+
+template <int E>
+void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                    hipStream_t st)
+{
+    const uint32_t blocks = (nb + kWavesPerBlock - 1) / kWavesPerBlock;
+    hipLaunchKernelGGL(bingrad_quantize_kernel<E>, dim3(blocks), dim3(kBlock), 0, st, g, n, p->bucket_size,
+                       p->level_iters, nb, lv, static_cast<uint64_t*>(codes));
+}
+
+template <int C, int BITS>
+void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
+{
+    const uint32_t blocks = (nb + kWavesPerBlock - 1) / kWavesPerBlock;
+    hipLaunchKernelGGL((orq_quantize_kernel<C, BITS>), dim3(blocks), dim3(kBlock), 0, st, g, n, p->bucket_size,
+                       p->level_iters, nb, p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
+}
+
+template <int C>
+void launch_orq_bits(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                     hipStream_t st)
+{
+    switch (p->bits) {
+        case 1: launch_orq<C, 1>(g, n, p, nb, lv, codes, st); break;
+        case 2: launch_orq<C, 2>(g, n, p, nb, lv, codes, st); break;
+        default: launch_orq<C, 3>(g, n, p, nb, lv, codes, st); break;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ogq_num_buckets(size_t n, const ogq_params_t* p)
+{
+    if (!p || p->bucket_size == 0) return 0;
+    return n / p->bucket_size + (n % p->bucket_size != 0);
+}
+
+size_t ogq_levels_count(size_t n, const ogq_params_t* p)
+{
+    if (!p || p->bits > 31) return 0;
+    return ogq_num_buckets(n, p) << p->bits;
+}
+
+size_t ogq_codes_bytes(size_t n, const ogq_params_t* p)
+{
+    if (!p || p->bucket_size == 0) return 0;
+    return (n / 64 + (n % 64 != 0)) * p->bits * 8;
+}
+
+int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params, float* d_levels, void* d_codes,
+                 void* hip_stream)
+{
+    const int rc = check_params(params, true);
+    if (rc != OGQ_OK) return rc;
+    if (n == 0) return OGQ_OK;
+    if (!d_grad || !d_levels || !d_codes) return OGQ_ERR_NULL_POINTER;
+    if (!aligned(d_grad, 16) || !aligned(d_levels, 16) || !aligned(d_codes, 16)) return OGQ_ERR_ALIGNMENT;
+    const size_t nb64 = ogq_num_buckets(n, params);
+    if (nb64 >= (1ull << 31)) return OGQ_ERR_SIZE;
+    const uint32_t nb = (uint32_t)nb64;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const uint32_t d = params->bucket_size;
+    if (params->scheme == OGQ_BINGRAD_B) {
+        const uint32_t regs = d / 64;
+        if (regs <= 1) launch_bingrad<1>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (regs <= 2) launch_bingrad<2>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (regs <= 4) launch_bingrad<4>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (regs <= 8) launch_bingrad<8>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (regs <= 16) launch_bingrad<16>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (regs <= 32) launch_bingrad<32>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else launch_bingrad<64>(d_grad, n, params, nb, d_levels, d_codes, st);
+    } else {
+        const uint32_t chunks = (d + 255) / 256;
+        if (chunks <= 1) launch_orq_bits<1>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 2) launch_orq_bits<2>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 4) launch_orq_bits<4>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 8) launch_orq_bits<8>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else launch_orq_bits<16>(d_grad, n, params, nb, d_levels, d_codes, st);
+    }
+    return finish_launch();
+}
+
+int ogq_dequantize_average(const void* const* d_codes, const float* const* d_levels, uint32_t num_workers, size_t n,
+                           const ogq_params_t* params, float* d_out, void* hip_stream)
+{
+    const int rc = check_params(params, false);
+    if (rc != OGQ_OK) return rc;
+    if (num_workers == 0 || num_workers > OGQ_MAX_WORKERS) return OGQ_ERR_NUM_WORKERS;
+    if (n == 0) return OGQ_OK;
+    if (!d_codes || !d_levels || !d_out) return OGQ_ERR_NULL_POINTER;
+    if (!aligned(d_out, 16)) return OGQ_ERR_ALIGNMENT;
+    WorkerPtrs ptrs;
+    for (uint32_t w = 0; w < OGQ_MAX_WORKERS; ++w) {
+        ptrs.codes[w] = nullptr;
+        ptrs.levels[w] = nullptr;
+    }
+    for (uint32_t w = 0; w < num_workers; ++w) {
+        if (!d_codes[w] || !d_levels[w]) return OGQ_ERR_NULL_POINTER;
+        if (!aligned(d_codes[w], 16) || !aligned(d_levels[w], 16)) return OGQ_ERR_ALIGNMENT;
+        ptrs.codes[w] = static_cast<const uint64_t*>(d_codes[w]);
+        ptrs.levels[w] = d_levels[w];
+    }
+    const size_t nb = ogq_num_buckets(n, params);
+    if (nb >= (1ull << 31)) return OGQ_ERR_SIZE;
+    const uint32_t d = params->bucket_size;
+    const uint32_t segs = (d + kSegWords * 64 - 1) / (kSegWords * 64);
+    const uint64_t num_segments = (uint64_t)nb * segs;
+    const uint64_t blocks64 = (num_segments + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks64 >= (1ull << 31)) return OGQ_ERR_SIZE;
+    const dim3 grid((uint32_t)blocks64), block(kBlock);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const double inv = 1.0 / (double)num_workers;
+    switch (params->bits) {
+        case 1:
+            hipLaunchKernelGGL(dequantize_average_kernel<1>, grid, block, 0, st, ptrs, num_workers, n, d, segs,
+                               num_segments, inv, d_out);
+            break;
+        case 2:
+            hipLaunchKernelGGL(dequantize_average_kernel<2>, grid, block, 0, st, ptrs, num_workers, n, d, segs,
+                               num_segments, inv, d_out);
+            break;
+        default:
+            hipLaunchKernelGGL(dequantize_average_kernel<3>, grid, block, 0, st, ptrs, num_workers, n, d, segs,
+                               num_segments, inv, d_out);
+            break;
+    }
+    return finish_launch();
+}
+
+int ogq_probe_read(const float* d_src, size_t n, float* d_sink, void* hip_stream)
+{
+    if (!d_src || !d_sink) return OGQ_ERR_NULL_POINTER;
+    if (!aligned(d_src, 16)) return OGQ_ERR_ALIGNMENT;
+    if (n == 0) return OGQ_OK;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(kProbeBlocks), dim3(kBlock), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<const float4*>(d_src), n / 4, d_sink);
+    return finish_launch();
+}
+
+int ogq_probe_copy(const float* d_src, float* d_dst, size_t n, void* hip_stream)
+{
+    if (!d_src || !d_dst) return OGQ_ERR_NULL_POINTER;
+    if (!aligned(d_src, 16) || !aligned(d_dst, 16)) return OGQ_ERR_ALIGNMENT;
+    if (n == 0) return OGQ_OK;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(kProbeBlocks), dim3(kBlock), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<const float4*>(d_src), reinterpret_cast<float4*>(d_dst), n / 4);
+    return finish_launch();
+}
+
+const char* ogq_strerror(int status)
+{
+    switch (status) {
+        case OGQ_OK: return "ok";
+        case OGQ_ERR_NULL_POINTER: return "a required pointer is NULL";
+        case OGQ_ERR_BUCKET_SIZE: return "bucket_size must be a multiple of 64 in [64, 4096]";
+        case OGQ_ERR_BITS: return "bits not supported by the scheme (BinGrad-b: 1, ORQ: 1..3)";
+        case OGQ_ERR_SCHEME: return "unknown scheme";
+        case OGQ_ERR_NUM_WORKERS: return "num_workers must be in [1, 64]";
+        case OGQ_ERR_ALIGNMENT: return "device pointers must be 16-byte aligned";
+        case OGQ_ERR_INDEX_OFFSET: return "index_offset must be a multiple of 64";
+        case OGQ_ERR_LAUNCH: return "HIP kernel launch failed";
+        case OGQ_ERR_SIZE: return "n is too large for one call";
+        default: return "unknown status";
+    }
+}
+
+int ogq_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,190 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2002_11082_amd as ogq
+from paper_2002_11082_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _rng_bucket(rng, n, kind):
+    if kind == "normal":
+        return rng.normal(0, 1e-3, n).astype(np.float32)
+    if kind == "ints":
+        return rng.integers(-3, 4, n).astype(np.float32)
+    if kind == "heavy":
+        return (rng.standard_t(3, n) * 1e-2).astype(np.float32)
+    if kind == "shifted":
+        return rng.normal(5.0, 1e-3, n).astype(np.float32)
+    if kind == "const":
+        return np.full(n, -0.75, np.float32)
+    if kind == "zeros":
+        g = np.zeros(n, np.float32)
+        g[::7] = -0.0
+        return g
+    raise ValueError(kind)
+
+
+# ------------------------------------------------------------------------------------------------
+# small sizes: every element compared; several tiles and ragged tails
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d", [64, 128, 192, 512, 2048, 4096])
+@pytest.mark.parametrize("kind", ["normal", "ints", "heavy", "shifted", "const", "zeros"])
+def test_bingrad_small(d, kind):
+    rng = np.random.default_rng(d + len(kind))
+    for n in (1, 63, 64, 65, d - 1, d, d + 1, 5 * d + 37, 16 * d):
+        if n < 1:
+            continue
+        g = _rng_bucket(rng, n, kind)
+        for iters in (0, 1, 4):
+            parity.check_quantize(g, d, 1, ogq.BINGRAD_B, iters, tag=f"bingrad-{kind}-d{d}-n{n}-it{iters}")
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3])
+@pytest.mark.parametrize("d", [64, 256, 320, 2048, 4096])
+def test_orq_small(bits, d):
+    rng = np.random.default_rng(100 * bits + d)
+    for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
+        for n in (1, 2, 3, 65, d - 1, d, 3 * d + 129):
+            if n < 1:
+                continue
+            g = _rng_bucket(rng, n, kind)
+            for sweeps in (0, 2):
+                parity.check_quantize(g, d, bits, ogq.ORQ, sweeps, seed=1234 + n, tag=f"orq{bits}-{kind}-d{d}-n{n}")
+
+
+def test_orq_sweeps_and_offsets():
+    rng = np.random.default_rng(77)
+    g = _rng_bucket(rng, 8 * 1024 + 100, "heavy")
+    for sweeps in (0, 1, 3, 5):
+        parity.check_quantize(g, 1024, 3, ogq.ORQ, sweeps, seed=9, tag=f"orq-sweeps{sweeps}")
+    # shard with an index offset, including one above 2^34 (second counter word in use)
+    for off in (1024, 64 * 12345, (1 << 36) + 64):
+        parity.check_quantize(g, 1024, 2, ogq.ORQ, 2, seed=(1 << 40) + 17, index_offset=off, tag=f"orq-offset{off}")
+    # a shard reproduces the full vector's codes
+    params = ogq.make_params(1024, 2, ogq.ORQ, 2, 5, 0)
+    _, words_full, _ = parity.gpu_quantize(g, params)
+    params_s = ogq.make_params(1024, 2, ogq.ORQ, 2, 5, 4096)
+    _, words_shard, _ = parity.gpu_quantize(g[4096:], params_s)
+    assert np.array_equal(words_full[4096 // 64 * 2:], words_shard)
+
+
+def test_empty_input_is_a_noop():
+    p = ogq.make_params(512, 1, ogq.BINGRAD_B)
+    x = torch.zeros(4, device=DEV)
+    assert ogq.ogq_quantize_raw(x.data_ptr(), 0, p, x.data_ptr(), x.data_ptr()) == 0
+    assert ogq.ogq_dequantize_average_raw([x.data_ptr()], [x.data_ptr()], 0, p, x.data_ptr()) == 0
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------------
+# decode + average
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits,scheme", [(1, ogq.BINGRAD_B), (1, ogq.ORQ), (2, ogq.ORQ), (3, ogq.ORQ)])
+@pytest.mark.parametrize("d", [64, 192, 1024, 1536, 2048, 4096])
+def test_decode_average_small(bits, scheme, d):
+    rng = np.random.default_rng(bits * 1000 + d)
+    for n in (1, 65, d, 2 * d + 63, 7 * d + 1):
+        for W in (1, 2, 3, 8):
+            gs = [_rng_bucket(rng, n, "heavy" if w % 2 else "normal") for w in range(W)]
+            # oracle streams decoded by the oracle = expected; the same streams uploaded and decoded on the GPU
+            q = [oracle.quantize(g, d, bits, scheme, 1, seed=40 + w) for w, g in enumerate(gs)]
+            ref = oracle.dequantize_average([w for _, w in q], [l for l, _ in q], n, d, bits)
+            scale = parity.term_scale([l for l, _ in q], [w for _, w in q], n, d, bits)
+            dl = [torch.from_numpy(np.concatenate([l, np.zeros(4, np.float32)])).to(DEV) for l, _ in q]
+            dc = [torch.from_numpy(np.concatenate([w, np.zeros(2, np.uint64)]).view(np.int64)).to(DEV) for _, w in q]
+            params = ogq.make_params(d, bits, scheme)
+            out = ogq.ogq_dequantize_average(dc, dl, n, params)
+            torch.cuda.synchronize()
+            parity.check_average(out.cpu().numpy(), ref, scale, tag=f"avg-b{bits}-d{d}-n{n}-W{W}")
+
+
+def test_decode_average_many_identical_workers():
+    rng = np.random.default_rng(5)
+    n, d, bits = 5000, 512, 2
+    g = _rng_bucket(rng, n, "normal")
+    lv, w = oracle.quantize(g, d, bits, ogq.ORQ, 2, seed=3)
+    single = oracle.dequantize_average([w], [lv], n, d, bits)
+    dl = torch.from_numpy(np.concatenate([lv, np.zeros(4, np.float32)])).to(DEV)
+    dc = torch.from_numpy(np.concatenate([w, np.zeros(2, np.uint64)]).view(np.int64)).to(DEV)
+    for W in (1, 7, 64):
+        out = ogq.ogq_dequantize_average([dc] * W, [dl] * W, n, ogq.make_params(d, bits, ogq.ORQ))
+        torch.cuda.synchronize()
+        ref = oracle.dequantize_average([w] * W, [lv] * W, n, d, bits)
+        parity.check_average(out.cpu().numpy(), ref, np.abs(single).astype(np.float64), tag=f"avg-identical-W{W}")
+
+
+# ------------------------------------------------------------------------------------------------
+# the benchmark configurations at full size
+# ------------------------------------------------------------------------------------------------
+def _end_to_end(wl, g_list, sample_buckets):
+    n, d, bits = g_list[0].size, wl.bucket_size, wl.bits
+    dev_levels, dev_codes, lv_ref, w_ref = [], [], [], []
+    for w, g in enumerate(g_list):
+        lv, codes, rep = parity.check_quantize(g, d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w),
+                                               buckets=sample_buckets, tag=f"{wl.name}-w{w}")
+        dev_levels.append(lv)
+        dev_codes.append(codes)
+    params = ogq.make_params(d, bits, wl.scheme)
+    out = ogq.ogq_dequantize_average(dev_codes, dev_levels, n, params)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    # expected average on the sampled buckets, from oracle streams only
+    nb = (n + d - 1) // d
+    sel = range(nb) if sample_buckets is None else sorted(set(sample_buckets))
+    for b in sel:
+        lo, hi = b * d, min((b + 1) * d, n)
+        q = [oracle.quantize(g[lo:hi], d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w), lo)
+             for w, g in enumerate(g_list)]
+        ref = oracle.dequantize_average([x[1] for x in q], [x[0] for x in q], hi - lo, d, bits)
+        scale = parity.term_scale([x[0] for x in q], [x[1] for x in q], hi - lo, d, bits)
+        denom = np.maximum(np.abs(ref.astype(np.float64)), scale)
+        err = np.abs(out[lo:hi].astype(np.float64) - ref.astype(np.float64))
+        assert np.all(err <= parity.AVG_RTOL * denom), (wl.name, b, np.flatnonzero(err > parity.AVG_RTOL * denom)[:5])
+    print(f"[parity] {wl.name} decode-average checked on {len(list(sel))} buckets", flush=True)
+
+
+def _sample(nb, count, seed):
+    rng = np.random.default_rng(seed)
+    picks = set(rng.choice(nb, size=min(count, nb), replace=False).tolist())
+    picks |= {0, 1, nb - 2, nb - 1} & set(range(nb))
+    return sorted(picks)
+
+
+def test_cfg1_bingrad_1m_full_compare():
+    wl = synth.WORKLOADS["cfg1"]
+    _end_to_end(wl, [wl.gradient()], None)
+
+
+def test_cfg2_bingrad_resnet50_size():
+    wl = synth.WORKLOADS["cfg2"]
+    g = wl.gradient()
+    # every bucket's levels and codes are compared; the decode on a sample
+    parity.check_quantize(g, wl.bucket_size, wl.bits, wl.scheme, wl.level_iters, tag="cfg2-all")
+    _end_to_end(wl, [g], _sample(12500, 300, 1))
+
+
+def test_cfg3_orq2_mixture():
+    wl = synth.WORKLOADS["cfg3"]
+    g = wl.gradient()
+    _end_to_end(wl, [g], _sample(12500, 1500, 2))
+
+
+def test_cfg4_orq3_vgg19_shape():
+    wl = synth.WORKLOADS["cfg4"]
+    g = wl.gradient()
+    nb = (wl.n + wl.bucket_size - 1) // wl.bucket_size
+    _end_to_end(wl, [g], _sample(nb, 600, 3))
+
+
+def test_cfg5_eight_workers_decode_average():
+    wl = synth.WORKLOADS["cfg5"]
+    gs = [wl.gradient(w) for w in range(wl.workers)]
+    nb = (wl.n + wl.bucket_size - 1) // wl.bucket_size
+    _end_to_end(wl, gs, _sample(nb, 250, 5))
