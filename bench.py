@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-bucket quantization hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic gradient that is already resident in HBM:
+ogq_quantize (statistics, level solve, encode, bit-pack) followed by ogq_dequantize_average of
+the packed stream(s).  The default workload is the ResNet-50-sized BinGrad-b configuration
+(25.6 M fp32, bucket 2048); --workload picks another one.  Inputs rotate over several distinct
+buffers (>= 1 GB in total) so that the 256 MB last-level cache cannot serve repeats.
+
+Prints ONE JSON line.  `value` is the fp32-gradient throughput of the whole step (4*n*workers
+bytes per step / time per step); `roofline` prices the dominant kernel's algorithmic bytes per
+launch against the HBM peak using HIP-event timings taken inside the timed region;
+`cpu_baseline` is the plain CPU oracle timed on the host cores (a reported baseline only).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(n: int, bucket_size: int, bits: int, workers: int):
+    """Bytes the method must move per launch: quantize reads the gradient once and writes codes and
+    levels; decode-average reads every worker's codes and levels and writes the fp32 average."""
+    nb = (n + bucket_size - 1) // bucket_size
+    codes = ((n + 63) // 64) * bits * 8
+    levels = (nb << bits) * 4
+    return 4 * n + codes + levels, workers * (codes + levels) + 4 * n
+
+
+def read_traffic_note(kernel_key: str):
+    """Measured HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy
+    kernel of known size) as recorded in profiles/hbm_traffic.txt, or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel_key:
+            try:
+                return float(parts[1])
+            except ValueError:
+                return None
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--buffers", type=int, default=0, help="distinct input buffers (0 = enough for 1 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (simulated workers are buffers on that device); "
+              "--gpus N with N > 1 is not supported.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2002_11082_amd as ogq
+    from paper_2002_11082_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    ogq.lib()  # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = synth.WORKLOADS[args.workload]
+    n, d, bits, W = wl.n, wl.bucket_size, wl.bits, wl.workers
+    grad_bytes = 4 * n * W
+    n_buf = args.buffers or max(2, -(-(1 << 30) // grad_bytes) + 1)
+    if args.workload == "cfg2":
+        n_buf = max(n_buf, 10)
+
+    # ---- synthetic inputs, resident in HBM before anything is timed ------------------------------
+    # Buffer 0 is the workload's own seeded gradient(s); the others hold the same values rolled by a
+    # different amount (same distribution, different bytes at every address).
+    host = [wl.gradient(w) for w in range(W)]
+    grads = []  # grads[b][w]
+    for b in range(n_buf):
+        grads.append([torch.from_numpy(np.roll(h, 7919 * b) if b else h).to(dev) for h in host])
+    params = [ogq.make_params(d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w)) for w in range(W)]
+    n_levels = ogq.ogq_levels_count(n, params[0])
+    n_words = ogq.ogq_codes_bytes(n, params[0]) // 8
+    levels = [[torch.empty(n_levels + 4, dtype=torch.float32, device=dev) for _ in range(W)] for _ in range(n_buf)]
+    codes = [[torch.empty(n_words + 2, dtype=torch.int64, device=dev) for _ in range(W)] for _ in range(n_buf)]
+    outs = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(n_buf)]
+    dparams = ogq.make_params(d, bits, wl.scheme)
+
+    def step(i: int, ev=None):
+        b = i % n_buf
+        if ev:
+            ev[0].record()
+        for w in range(W):
+            ogq.ogq_quantize(grads[b][w], params[w], levels[b][w], codes[b][w])
+        if ev:
+            ev[1].record()
+        ogq.ogq_dequantize_average(codes[b], levels[b], n, dparams, outs[b])
+        if ev:
+            ev[2].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    q_ms = np.array([e[0].elapsed_time(e[1]) for e in events]) / W  # per quantize launch
+    a_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
+    q_bytes, a_bytes = algorithmic_bytes(n, d, bits, W)
+    q_avg, a_avg = float(q_ms.mean()), float(a_ms.mean())
+    q_gbs = q_bytes / (q_avg * 1e-3) / 1e9
+    a_gbs = a_bytes / (a_avg * 1e-3) / 1e9
+
+    # practical ceiling of this device: a pure streaming read of the same buffers
+    sink = torch.empty(ogq.binding.PROBE_SINK_FLOATS, dtype=torch.float32, device=dev)
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for i in range(5):
+        ogq.ogq_probe_read(grads[i % n_buf][0], sink)
+    reps = 40
+    pe[0].record()
+    for i in range(reps):
+        ogq.ogq_probe_read(grads[i % n_buf][0], sink)
+    pe[1].record()
+    torch.cuda.synchronize()
+    probe_gbs = 4 * n / (pe[0].elapsed_time(pe[1]) / reps * 1e-3) / 1e9
+
+    quant_name = "bingrad_quantize_kernel" if wl.scheme == synth.BINGRAD_B else "orq_quantize_kernel"
+    dominant_is_quant = q_avg * W >= a_avg
+    roof = {
+        "bound": "hbm", "kernel": quant_name if dominant_is_quant else "dequantize_average_kernel",
+        "achieved": round(q_gbs if dominant_is_quant else a_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round((q_gbs if dominant_is_quant else a_gbs) / HBM_PEAK_GBS, 4),
+        "traffic": read_traffic_note(f"{args.workload}:{quant_name if dominant_is_quant else 'dequantize_average_kernel'}"),
+        "algorithmic_bytes_per_launch": q_bytes if dominant_is_quant else a_bytes,
+        "avg_launch_us": round((q_avg if dominant_is_quant else a_avg) * 1e3, 2),
+    }
+    other = {
+        "kernel": "dequantize_average_kernel" if dominant_is_quant else quant_name,
+        "achieved": round(a_gbs if dominant_is_quant else q_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round((a_gbs if dominant_is_quant else q_gbs) / HBM_PEAK_GBS, 4),
+        "traffic": read_traffic_note(f"{args.workload}:{'dequantize_average_kernel' if dominant_is_quant else quant_name}"),
+        "algorithmic_bytes_per_launch": a_bytes if dominant_is_quant else q_bytes,
+        "avg_launch_us": round((a_avg if dominant_is_quant else q_avg) * 1e3, 2),
+    }
+
+    result = {
+        "metric": "quantize+pack GB/s of fp32 gradient (fraction of HBM peak); dequant-avg GB/s",
+        "value": round(grad_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s of fp32 gradient through quantize+pack+decode-average",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 data, f64 sums", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.description}", "n": n, "bucket_size": d, "bits": bits,
+                   "workers": W, "level_iters": wl.level_iters, "input_buffers": n_buf},
+        "elements_per_s": round(n * W / (ms_per_step * 1e-3), 1),
+        "quantize_gbs_fp32_in": round(4 * n / (q_avg * 1e-3) / 1e9, 1),
+        "dequant_avg_gbs_fp32_out": round(4 * n / (a_avg * 1e-3) / 1e9, 1),
+        "read_probe_gbs": round(probe_gbs, 1),
+        "roofline": roof,
+        "roofline_other_kernel": other,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.threads()
+        g0 = host  # the workload's own gradient(s)
+        # bounded sample: whole gradients for the small workloads, a prefix for the big ones
+        sample_n = n if wl.scheme == synth.BINGRAD_B else min(n, 4_194_304)
+        sample_n -= sample_n % d
+        t_cpu, reps_cpu = 0.0, 0
+        while t_cpu < args.cpu_seconds and reps_cpu < 50:
+            c0 = time.perf_counter()
+            q = [oracle.quantize(g0[w][:sample_n], d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w))
+                 for w in range(W)]
+            oracle.dequantize_average([x[1] for x in q], [x[0] for x in q], sample_n, d, bits)
+            t_cpu += time.perf_counter() - c0
+            reps_cpu += 1
+        result["cpu_baseline"] = {
+            "value": round(4 * sample_n * W * reps_cpu / t_cpu / 1e9, 3),
+            "unit": "GB/s of fp32 gradient through quantize+pack+decode-average",
+            "cores": threads, "kind": "oracle",
+            "sample": f"first {sample_n} elements of each worker's gradient of {wl.name}, {reps_cpu} repetitions, "
+                      f"{t_cpu:.1f} s, OpenMP over buckets",
+        }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
