@@ -28,25 +28,77 @@ thread_local int g_last_hip_error = 0;
 // ----------------------------------------------------------------------------------------------
 // wave-level helpers
 // ----------------------------------------------------------------------------------------------
+// Cross-lane moves within a row of 16 lanes (DPP): quad_perm [1,0,3,2], quad_perm [2,3,0,1],
+// row_half_mirror, row_mirror.  After the four steps of a butterfly every lane of a row holds the
+// row's result; the four rows are then combined through readlane.
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x)
+{
+    return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(x)));
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = dpp_u32<CTRL>((uint32_t)u), hi = dpp_u32<CTRL>((uint32_t)(u >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+__device__ __forceinline__ double readlane_f64(double x, int lane)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)u, lane);
+    const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(u >> 32), lane);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+__device__ __forceinline__ float readlane_f32(float x, int lane)
+{
+    return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), lane));
+}
+
+// Lane `lane` (compile-time constant) of `dst` takes the wave-uniform value `value`.
+__device__ __forceinline__ uint32_t writelane(uint32_t dst, uint32_t value, int lane)
+{
+    asm("v_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(value), "n"(lane));
+    return dst;
+}
+
+// Wave-wide sum; the result is wave-uniform.
 __device__ __forceinline__ double wave_sum(double x)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, kWave);
-    return x;
+    x += dpp_f64<kDppXor1>(x);
+    x += dpp_f64<kDppXor2>(x);
+    x += dpp_f64<kDppHalfMirror>(x);
+    x += dpp_f64<kDppMirror>(x);
+    return (readlane_f64(x, 0) + readlane_f64(x, 16)) + (readlane_f64(x, 32) + readlane_f64(x, 48));
 }
 
 __device__ __forceinline__ float wave_min(float x)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) x = fminf(x, __shfl_xor(x, off, kWave));
-    return x;
+    x = fminf(x, dpp_f32<kDppXor1>(x));
+    x = fminf(x, dpp_f32<kDppXor2>(x));
+    x = fminf(x, dpp_f32<kDppHalfMirror>(x));
+    x = fminf(x, dpp_f32<kDppMirror>(x));
+    return fminf(fminf(readlane_f32(x, 0), readlane_f32(x, 16)), fminf(readlane_f32(x, 32), readlane_f32(x, 48)));
 }
 
 __device__ __forceinline__ float wave_max(float x)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
-    return x;
+    x = fmaxf(x, dpp_f32<kDppXor1>(x));
+    x = fmaxf(x, dpp_f32<kDppXor2>(x));
+    x = fmaxf(x, dpp_f32<kDppHalfMirror>(x));
+    x = fmaxf(x, dpp_f32<kDppMirror>(x));
+    return fmaxf(fmaxf(readlane_f32(x, 0), readlane_f32(x, 16)), fmaxf(readlane_f32(x, 32), readlane_f32(x, 48)));
 }
 
 __device__ __forceinline__ uint32_t uniform_u32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -77,17 +129,17 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         const uint32_t e = 64u * j + lane;
-        v[j] = (FULL || e < len) ? g[e] : 0.0f;
+        v[j] = (FULL || e < len) ? __builtin_nontemporal_load(g + e) : 0.0f;  // read once: bypass the caches
     }
 
     double part = 0.0;
 #pragma unroll
     for (int j = 0; j < E; ++j) part += (double)v[j];
-    const double total = uniform_f64(wave_sum(part));
+    const double total = wave_sum(part);
     float b0 = (float)(total / (double)len);  // threshold starts at the bucket mean
 
     double b_lo = 0.0, b_hi = 0.0;
-    uint64_t my_word = 0;
+    uint32_t word_lo = 0, word_hi = 0;  // lane j ends up holding packed word j of the bucket
     uint32_t prev_n_lo = 0xFFFFFFFFu;
     for (uint32_t it = 0;; ++it) {
         double s_lo = 0.0, s_hi = 0.0;
@@ -96,16 +148,18 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
         for (int j = 0; j < E; ++j) {
             const bool valid = FULL || (64u * j + lane < len);
             const bool lo = valid && (v[j] < b0);
-            const bool hi = valid && !lo;
-            const uint64_t hi_mask = __ballot(hi);
-            n_lo += (uint32_t)__popcll(__ballot(lo));
-            const double dv = (double)v[j];
-            s_lo += lo ? dv : 0.0;
-            s_hi += hi ? dv : 0.0;
-            if (lane == (uint32_t)j) my_word = hi_mask;
+            const uint64_t lo_mask = __ballot(lo);
+            const uint64_t hi_mask = FULL ? ~lo_mask : __ballot(valid && !lo);
+            n_lo += (uint32_t)__popcll(lo_mask);
+            const float x_lo = lo ? v[j] : 0.0f;
+            const float x_hi = v[j] - x_lo;  // exact: one of the two is zero (padding holds 0)
+            s_lo += (double)x_lo;
+            s_hi += (double)x_hi;
+            word_lo = writelane(word_lo, (uint32_t)hi_mask, j);
+            word_hi = writelane(word_hi, (uint32_t)(hi_mask >> 32), j);
         }
-        s_lo = uniform_f64(wave_sum(s_lo));
-        s_hi = uniform_f64(wave_sum(s_hi));
+        s_lo = wave_sum(s_lo);
+        s_hi = wave_sum(s_hi);
         const uint32_t n_hi = len - n_lo;
         if (n_hi > 0) b_hi = s_hi / (double)n_hi;
         if (n_lo > 0) b_lo = s_lo / (double)n_lo;
@@ -122,11 +176,13 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
         levels2[1] = (float)b_hi;
     }
     const uint32_t n_words = (len + 63u) / 64u;
-    if (lane < n_words) words[lane] = my_word;
+    if (lane < n_words) words[lane] = ((uint64_t)word_hi << 32) | word_lo;
 }
 
+// At most 4 waves per SIMD: with more, all resident waves load and then compute in lock-step and
+// the tail of a launch that is only ~1.5 waves of workgroups deep is not overlapped.
 template <int E>
-__global__ __launch_bounds__(kBlock) void bingrad_quantize_kernel(const float* __restrict__ grad, size_t n,
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 4))) void bingrad_quantize_kernel(const float* __restrict__ grad, size_t n,
                                                                   uint32_t bucket_size, uint32_t iters,
                                                                   uint32_t num_buckets, float* __restrict__ levels,
                                                                   uint64_t* __restrict__ codes)
@@ -226,7 +282,7 @@ __device__ __forceinline__ float orq_solve(const OrqBucket<C>& b, float L, float
             count_le_R += (uint32_t)__popcll(__ballot(le));
             part += (le && x >= L) ? ((double)x - dL) : 0.0;
         }
-    const double S = uniform_f64(wave_sum(part));
+    const double S = wave_sum(part);
     const double T = S / ((double)R - dL);
     const double m = floor(T);
     uint32_t rank = (m >= (double)count_le_R) ? 1u : count_le_R - (uint32_t)m;
@@ -319,8 +375,8 @@ __global__ __launch_bounds__(kBlock) void orq_quantize_kernel(const float* __res
     // Levels: ends are the bucket extremes (Corollary 1), interior by greedy recursion
     // (Algorithm 1, middle index rounded down when s is not 2^K + 1), then re-solve sweeps.
     float lv[S];
-    lv[0] = uniform_f32(wave_min(lo));
-    lv[S - 1] = uniform_f32(wave_max(hi));
+    lv[0] = wave_min(lo);
+    lv[S - 1] = wave_max(hi);
 #pragma unroll
     for (int k = 1; k < S - 1; ++k) lv[k] = lv[0];
     if constexpr (S > 2) {
@@ -407,7 +463,7 @@ struct WorkerPtrs {
     const float* levels[OGQ_MAX_WORKERS];
 };
 
-constexpr int kSegWords = 16;
+constexpr int kSpanWords = 16;  // one wavefront decodes 16 packed word groups = 1024 elements
 
 template <int BITS>
 __device__ __forceinline__ float select_level(const uint64_t* __restrict__ w, const float (&lv)[1 << BITS])
@@ -432,52 +488,59 @@ __device__ __forceinline__ float select_level(const uint64_t* __restrict__ w, co
     }
 }
 
-template <int BITS>
+// ONE_BUCKET: the 16 word groups of a span lie in one bucket (bucket_size is a multiple of 1024),
+// so each worker's level table is fetched once per span; otherwise once per word group.
+template <int BITS, bool ONE_BUCKET>
 __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs ptrs, uint32_t num_workers, size_t n,
-                                                                    uint32_t bucket_size, uint32_t segs_per_bucket,
-                                                                    uint64_t num_segments, double inv_workers,
-                                                                    float* __restrict__ out)
+                                                                    uint32_t words_per_bucket, uint32_t total_words,
+                                                                    double inv_workers, float* __restrict__ out)
 {
     constexpr int S = 1 << BITS;
-    const uint64_t seg = (uint64_t)blockIdx.x * kWavesPerBlock + uniform_u32(threadIdx.x >> 6);
-    if (seg >= num_segments) return;
+    const uint32_t span = blockIdx.x * kWavesPerBlock + uniform_u32(threadIdx.x >> 6);
+    const uint32_t word0 = span * kSpanWords;
+    if (word0 >= total_words) return;
     const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t bucket = seg / segs_per_bucket;
-    const uint32_t seg_in_bucket = (uint32_t)(seg - bucket * segs_per_bucket);
-    const size_t begin = (size_t)bucket * bucket_size + (size_t)seg_in_bucket * (kSegWords * 64);
-    if (begin >= n) return;
-    size_t end = begin + kSegWords * 64;
-    const size_t bucket_end = (size_t)(bucket + 1) * bucket_size;
-    if (end > bucket_end) end = bucket_end;
-    if (end > n) end = n;
-    const uint32_t len = (uint32_t)(end - begin);
-    const uint32_t n_words = uniform_u32((len + 63u) / 64u);
-    const size_t word0 = begin / 64;
+    const uint32_t rest = total_words - word0;
+    const uint32_t n_words = rest < (uint32_t)kSpanWords ? rest : (uint32_t)kSpanWords;
 
-    double acc[kSegWords];
+    double acc[kSpanWords];
 #pragma unroll
-    for (int j = 0; j < kSegWords; ++j) acc[j] = 0.0;
+    for (int j = 0; j < kSpanWords; ++j) acc[j] = 0.0;
 
     for (uint32_t w = 0; w < num_workers; ++w) {
-        const float* __restrict__ lvp = ptrs.levels[w] + (size_t)bucket * S;
-        const uint64_t* __restrict__ cw = ptrs.codes[w] + word0 * BITS;
-        float lv[S];
+        const uint64_t* __restrict__ cw = ptrs.codes[w] + (size_t)word0 * BITS;
+        const float* __restrict__ table = ptrs.levels[w];
+        if constexpr (ONE_BUCKET) {
+            const float* __restrict__ lvp = table + (size_t)(word0 / words_per_bucket) * S;
+            float lv[S];
 #pragma unroll
-        for (int k = 0; k < S; ++k) lv[k] = lvp[k];
-        if (n_words == kSegWords) {
+            for (int k = 0; k < S; ++k) lv[k] = lvp[k];
+            if (n_words == (uint32_t)kSpanWords) {
 #pragma unroll
-            for (int j = 0; j < kSegWords; ++j) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+                for (int j = 0; j < kSpanWords; ++j) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+            } else {
+#pragma unroll
+                for (int j = 0; j < kSpanWords; ++j)
+                    if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+            }
         } else {
 #pragma unroll
-            for (int j = 0; j < kSegWords; ++j)
-                if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+            for (int j = 0; j < kSpanWords; ++j)
+                if ((uint32_t)j < n_words) {
+                    const float* __restrict__ lvp = table + (size_t)((word0 + j) / words_per_bucket) * S;
+                    float lv[S];
+#pragma unroll
+                    for (int k = 0; k < S; ++k) lv[k] = lvp[k];
+                    acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+                }
         }
     }
+    float* __restrict__ o = out + (size_t)word0 * 64 + lane;
+    const size_t first = (size_t)word0 * 64 + lane;
 #pragma unroll
-    for (int j = 0; j < kSegWords; ++j) {
-        const uint32_t e = 64u * j + lane;
-        if (e < len) out[begin + e] = (float)(acc[j] * inv_workers);
-    }
+    for (int j = 0; j < kSpanWords; ++j)
+        if ((uint32_t)j < n_words && first + 64u * j < n)
+            __builtin_nontemporal_store((float)(acc[j] * inv_workers), o + 64 * j);  // written once, never re-read here
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -646,27 +709,28 @@ int ogq_dequantize_average(const void* const* d_codes, const float* const* d_lev
     const size_t nb = ogq_num_buckets(n, params);
     if (nb >= (1ull << 31)) return OGQ_ERR_SIZE;
     const uint32_t d = params->bucket_size;
-    const uint32_t segs = (d + kSegWords * 64 - 1) / (kSegWords * 64);
-    const uint64_t num_segments = (uint64_t)nb * segs;
-    const uint64_t blocks64 = (num_segments + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (blocks64 >= (1ull << 31)) return OGQ_ERR_SIZE;
-    const dim3 grid((uint32_t)blocks64), block(kBlock);
+    const uint32_t total_words = (uint32_t)(n / 64 + (n % 64 != 0));
+    const uint32_t spans = (total_words + kSpanWords - 1) / kSpanWords;
+    const dim3 grid((spans + kWavesPerBlock - 1) / kWavesPerBlock), block(kBlock);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const double inv = 1.0 / (double)num_workers;
+    const uint32_t wpb = d / 64;
+    const bool one_bucket = d % (kSpanWords * 64) == 0;
+#define OGQ_LAUNCH_DEQUANT(BITS)                                                                                   \
+    do {                                                                                                           \
+        if (one_bucket)                                                                                            \
+            hipLaunchKernelGGL((dequantize_average_kernel<BITS, true>), grid, block, 0, st, ptrs, num_workers, n,  \
+                               wpb, total_words, inv, d_out);                                                      \
+        else                                                                                                       \
+            hipLaunchKernelGGL((dequantize_average_kernel<BITS, false>), grid, block, 0, st, ptrs, num_workers, n, \
+                               wpb, total_words, inv, d_out);                                                      \
+    } while (0)
     switch (params->bits) {
-        case 1:
-            hipLaunchKernelGGL(dequantize_average_kernel<1>, grid, block, 0, st, ptrs, num_workers, n, d, segs,
-                               num_segments, inv, d_out);
-            break;
-        case 2:
-            hipLaunchKernelGGL(dequantize_average_kernel<2>, grid, block, 0, st, ptrs, num_workers, n, d, segs,
-                               num_segments, inv, d_out);
-            break;
-        default:
-            hipLaunchKernelGGL(dequantize_average_kernel<3>, grid, block, 0, st, ptrs, num_workers, n, d, segs,
-                               num_segments, inv, d_out);
-            break;
+        case 1: OGQ_LAUNCH_DEQUANT(1); break;
+        case 2: OGQ_LAUNCH_DEQUANT(2); break;
+        default: OGQ_LAUNCH_DEQUANT(3); break;
     }
+#undef OGQ_LAUNCH_DEQUANT
     return finish_launch();
 }
 
