@@ -222,11 +222,19 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 
 // ----------------------------------------------------------------------------------------------
-// ORQ quantize.  Lane l holds, for chunk c, the four consecutive bucket elements
-// 256*c + 4*l + {0,1,2,3} (one 16-byte load), which are also the four elements that share one
-// Philox block.
+// ORQ quantize.  One wavefront (= one workgroup) owns one bucket.  Lane l holds, for chunk c, the
+// four consecutive bucket elements 256*c + 4*l + {0,1,2,3} (one 16-byte load), which are also the
+// four elements that share one Philox block.
+//
+// A level solve needs (a) counts and sums of the elements below a level and (b) the element of a
+// given rank.  The bucket is therefore grouped once, in LDS, by a monotone bin of the value (sign,
+// exponent and top mantissa bits, relative to the largest magnitude of the bucket; everything more
+// than 16 binades below that shares the two centre bins).  Per-bin counts and fp64 sums are
+// prefix-summed; after that a solve touches one bin: the bin holding the wanted rank is sorted
+// across the 64 lanes, and the counts and sums below the chosen element are added to the bin's
+// prefix.  All values of a regular bin share sign and exponent, so its fp64 sum is exact.
 // ----------------------------------------------------------------------------------------------
-// Order-preserving map of fp32 onto unsigned integers (-0 sorts just below +0).
+// Order-preserving map of fp32 onto unsigned integers.
 __device__ __forceinline__ uint32_t float_to_key(float f)
 {
     const uint32_t u = __float_as_uint(f);
@@ -237,59 +245,6 @@ __device__ __forceinline__ float key_to_float(uint32_t k)
 {
     const uint32_t u = (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
     return __uint_as_float(u);
-}
-
-template <int C>
-struct OrqBucket {
-    float v[C][4];       // values; padding = +inf
-    uint32_t key[C][4];  // ordered keys; padding = 0xFFFFFFFF
-};
-
-// Value of 1-based rank `rank` among the bucket's elements: the largest key K with
-// #{key < K} < rank, built bit by bit from the top.
-template <int C>
-__device__ __forceinline__ float select_rank(const OrqBucket<C>& b, uint32_t rank)
-{
-    uint32_t prefix = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = prefix | (1u << bit);
-        uint32_t below = 0;
-#pragma unroll
-        for (int c = 0; c < C; ++c)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) below += (uint32_t)__popcll(__ballot(b.key[c][k] < cand));
-        if (below < rank) prefix = cand;
-    }
-    return key_to_float(prefix);
-}
-
-// One solve of the discrete optimal condition for the level between L and R: with
-// S = sum_{L<=v<=R} (v - L) and T = S / (R - L), the level is the smallest bucket value b with
-// #{b < v <= R} <= T, i.e. the value of rank #{v <= R} - floor(T).
-template <int C>
-__device__ __forceinline__ float orq_solve(const OrqBucket<C>& b, float L, float R)
-{
-    if (!(L < R)) return L;
-    const double dL = (double)L;
-    double part = 0.0;
-    uint32_t count_le_R = 0;
-#pragma unroll
-    for (int c = 0; c < C; ++c)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float x = b.v[c][k];
-            const bool le = x <= R;
-            count_le_R += (uint32_t)__popcll(__ballot(le));
-            part += (le && x >= L) ? ((double)x - dL) : 0.0;
-        }
-    const double S = wave_sum(part);
-    const double T = S / ((double)R - dL);
-    const double m = floor(T);
-    uint32_t rank = (m >= (double)count_le_R) ? 1u : count_le_R - (uint32_t)m;
-    if (rank < 1u) rank = 1u;
-    float lvl = select_rank<C>(b, rank);
-    if (lvl < L) lvl = L;
-    return lvl;
 }
 
 // Order of the greedy solves (Algorithm 1): the level in the middle of [l, r] is solved from the
@@ -318,38 +273,216 @@ constexpr GreedyOrder greedy_order()
     return o;
 }
 
-template <int S>
-__device__ __forceinline__ float pick_level(const float (&lv)[S], uint32_t i)
+// LDS of one bucket: D = element capacity, B = number of bins.
+template <int D, int B>
+struct OrqLds {
+    uint32_t grouped[D];       // ordered keys grouped by bin (unsorted inside a bin)
+    uint32_t bin_start[B + 4]; // histogram, then exclusive prefix of the bin counts; [B] = length
+    double bin_sum[B];         // per-bin sum, then exclusive prefix of the bin sums
+    // per level k: value; #{v < value}; #{v <= value}; sum{v < value}; sum{v <= value}; the rank it
+    // was picked at (0 = not picked by rank)
+    double lvl_sum_lt[8];
+    double lvl_sum_le[8];
+    float lvl_value[8];
+    uint32_t lvl_count_lt[8];
+    uint32_t lvl_count_le[8];
+    uint32_t lvl_rank[8];
+};
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
 {
-    float r = lv[0];
+    x += dpp_u32<kDppXor1>(x);
+    x += dpp_u32<kDppXor2>(x);
+    x += dpp_u32<kDppHalfMirror>(x);
+    x += dpp_u32<kDppMirror>(x);
+    return (__builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16)) +
+           (__builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48));
+}
+
+__device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__device__ __forceinline__ uint32_t umax32(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
+{
+    x = umax32(x, dpp_u32<kDppXor1>(x));
+    x = umax32(x, dpp_u32<kDppXor2>(x));
+    x = umax32(x, dpp_u32<kDppHalfMirror>(x));
+    x = umax32(x, dpp_u32<kDppMirror>(x));
+    return umax32(umax32(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+                  umax32(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
+}
+
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) { return ~wave_max_u32(~x); }
+
+// Inclusive scans over the lanes in ascending lane order.
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t x, uint32_t lane)
+{
 #pragma unroll
-    for (int k = 1; k < S; ++k) r = (i == (uint32_t)k) ? lv[k] : r;
-    return r;
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t y = (uint32_t)__shfl_up((int)x, off, kWave);
+        x += (lane >= (uint32_t)off) ? y : 0u;
+    }
+    return x;
+}
+
+__device__ __forceinline__ double wave_inclusive_scan_f64(double x, uint32_t lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double y = __shfl_up(x, off, kWave);
+        x += (lane >= (uint32_t)off) ? y : 0.0;
+    }
+    return x;
+}
+
+// Ascending bitonic sort of one key per lane across the 64 lanes.
+constexpr int kDppRor8 = 0x128;  // rotate by 8 inside a row of 16 lanes = partner lane ^ 8
+
+template <int DIST>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t x)
+{
+    if constexpr (DIST == 1) return dpp_u32<kDppXor1>(x);
+    else if constexpr (DIST == 2) return dpp_u32<kDppXor2>(x);
+    else if constexpr (DIST == 8) return dpp_u32<kDppRor8>(x);
+    else return (uint32_t)__shfl_xor((int)x, DIST, kWave);
+}
+
+template <int K, int DIST>
+__device__ __forceinline__ uint32_t bitonic_step(uint32_t x, uint32_t lane)
+{
+    const uint32_t y = lane_xor<DIST>(x);
+    const bool ascending = (lane & (uint32_t)K) == 0;
+    const bool lower = (lane & (uint32_t)DIST) == 0;
+    const uint32_t mn = umin32(x, y), mx = umax32(x, y);
+    return (ascending == lower) ? mn : mx;
+}
+
+__device__ __forceinline__ uint32_t wave_sort_u32(uint32_t x, uint32_t lane)
+{
+    x = bitonic_step<2, 1>(x, lane);
+    x = bitonic_step<4, 2>(x, lane);   x = bitonic_step<4, 1>(x, lane);
+    x = bitonic_step<8, 4>(x, lane);   x = bitonic_step<8, 2>(x, lane);   x = bitonic_step<8, 1>(x, lane);
+    x = bitonic_step<16, 8>(x, lane);  x = bitonic_step<16, 4>(x, lane);  x = bitonic_step<16, 2>(x, lane);
+    x = bitonic_step<16, 1>(x, lane);
+    x = bitonic_step<32, 16>(x, lane); x = bitonic_step<32, 8>(x, lane);  x = bitonic_step<32, 4>(x, lane);
+    x = bitonic_step<32, 2>(x, lane);  x = bitonic_step<32, 1>(x, lane);
+    x = bitonic_step<64, 32>(x, lane); x = bitonic_step<64, 16>(x, lane); x = bitonic_step<64, 8>(x, lane);
+    x = bitonic_step<64, 4>(x, lane);  x = bitonic_step<64, 2>(x, lane);  x = bitonic_step<64, 1>(x, lane);
+    return x;
+}
+
+// The bucket element of a given rank, with the counts and sums of the bucket elements strictly
+// below it and not above it.
+struct Picked {
+    uint32_t key;
+    uint32_t count_lt, count_le;
+    double sum_lt, sum_le;
+};
+
+// rank is 1-based, 1 <= rank <= bucket length.  my_start[t] = bin_start[lane * PER + t].
+template <int D, int B>
+__device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint32_t (&my_start)[B / 64],
+                                            uint32_t rank, uint32_t lane)
+{
+    constexpr int PER = B / 64;
+    // the bin holding the rank: the last bin whose first position is below the rank
+    uint32_t starts_below = 0;
+#pragma unroll
+    for (int t = 0; t < PER; ++t) starts_below += (my_start[t] < rank) ? 1u : 0u;
+    const uint32_t bin = wave_sum_u32(starts_below) - 1u;  // bin_start[0] = 0 < rank: at least one
+    const uint32_t first = uniform_u32(lds.bin_start[bin]);
+    const uint32_t count = uniform_u32(lds.bin_start[bin + 1]) - first;
+    const double before = uniform_f64(lds.bin_sum[bin]);
+    const uint32_t r_in = rank - first;  // 1-based rank inside the bin
+
+    uint32_t key, c_lt, c_le;
+    double s_lt;
+    if (count <= 64u) {
+        const uint32_t mine = lane < count ? lds.grouped[first + lane] : 0xFFFFFFFFu;
+        const uint32_t sorted = wave_sort_u32(mine, lane);
+        key = __builtin_amdgcn_readlane(sorted, r_in - 1u);
+        const bool lt = sorted < key;
+        const bool le = (sorted <= key) && (lane < count);
+        c_lt = (uint32_t)__popcll(__ballot(lt));
+        c_le = (uint32_t)__popcll(__ballot(le));
+        s_lt = wave_sum(lt ? (double)key_to_float(sorted) : 0.0);
+    } else {
+        // a crowded bin (many equal or nearly equal values): bisection on the key over all its chunks
+        uint32_t prefix = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand = prefix | (1u << bit);
+            uint32_t below = 0;
+            for (uint32_t base = 0; base < count; base += 64u) {
+                const uint32_t i = base + lane;
+                const uint32_t k = i < count ? lds.grouped[first + i] : 0xFFFFFFFFu;
+                below += (uint32_t)__popcll(__ballot(k < cand));
+            }
+            if (below < r_in) prefix = cand;
+        }
+        key = prefix;
+        c_lt = 0;
+        c_le = 0;
+        double part = 0.0;
+        for (uint32_t base = 0; base < count; base += 64u) {
+            const uint32_t i = base + lane;
+            const uint32_t k = i < count ? lds.grouped[first + i] : 0xFFFFFFFFu;
+            const bool lt = k < key;
+            c_lt += (uint32_t)__popcll(__ballot(lt));
+            c_le += (uint32_t)__popcll(__ballot(k <= key && i < count));
+            part += lt ? (double)key_to_float(k) : 0.0;
+        }
+        s_lt = wave_sum(part);
+    }
+    Picked p;
+    p.key = key;
+    p.count_lt = first + c_lt;
+    p.count_le = first + c_le;
+    p.sum_lt = before + s_lt;
+    p.sum_le = p.sum_lt + (double)(c_le - c_lt) * (double)key_to_float(key);
+    return p;
+}
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Returns x unchanged but hides it from common-subexpression elimination, so that values derived
+// from the register-resident bucket are recomputed in each phase instead of being kept alive.
+__device__ __forceinline__ float recompute_from(float x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
 }
 
 template <int C, int BITS>
-__global__ __launch_bounds__(kBlock) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
-                                                              uint32_t bucket_size, uint32_t sweeps,
-                                                              uint32_t num_buckets, uint64_t seed,
-                                                              uint64_t index_offset, float* __restrict__ levels,
-                                                              uint32_t* __restrict__ codes32)
+__global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
+                                                             uint32_t bucket_size, uint32_t sweeps,
+                                                             uint32_t num_buckets, uint64_t seed,
+                                                             uint64_t index_offset, float* __restrict__ levels,
+                                                             uint32_t* __restrict__ codes32)
 {
     constexpr int S = 1 << BITS;
-    const uint32_t bucket = uniform_u32(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    constexpr int D = 256 * C;
+    constexpr int B = C >= 16 ? 512 : 256;    // bins
+    constexpr int PER = B / 64;               // bins per lane in the prefix step
+    constexpr int HALF = B / 2;               // bins per sign
+    constexpr int SHIFT = C >= 16 ? 19 : 20;  // magnitude bits dropped: keeps exponent + 4 (3) mantissa bits
+    __shared__ OrqLds<D, B> lds;
+
+    const uint32_t bucket = blockIdx.x;
     if (bucket >= num_buckets) return;
     const uint32_t lane = threadIdx.x & 63u;
     const size_t begin = (size_t)bucket * bucket_size;
     const size_t rest = n - begin;
     const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
     const float* g = grad + begin;
+    const bool full = len == (uint32_t)D;
 
-    OrqBucket<C> b;
-    const float inf = __uint_as_float(0x7F800000u);
-    if (len == 256u * C) {
+    // ---- load (read once: bypass the caches); padding holds +0 and is never binned or encoded ----
+    float v[C][4];
+    if (full) {
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            const float4 q = *reinterpret_cast<const float4*>(g + 256 * c + 4 * lane);
-            b.v[c][0] = q.x; b.v[c][1] = q.y; b.v[c][2] = q.z; b.v[c][3] = q.w;
+            const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + 256 * c + 4 * lane));
+            v[c][0] = q.x; v[c][1] = q.y; v[c][2] = q.z; v[c][3] = q.w;
         }
     } else {
 #pragma unroll
@@ -357,52 +490,193 @@ __global__ __launch_bounds__(kBlock) void orq_quantize_kernel(const float* __res
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t e = 256u * c + 4u * lane + k;
-                b.v[c][k] = e < len ? g[e] : inf;
+                v[c][k] = e < len ? g[e] : 0.0f;
             }
     }
-    float lo = inf, hi = -inf;
+
+    // ---- extremes ------------------------------------------------------------------------------
+    uint32_t key_min = 0xFFFFFFFFu, key_max = 0u, mag_max = 0u;
 #pragma unroll
     for (int c = 0; c < C; ++c)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const uint32_t e = 256u * c + 4u * lane + k;
-            const bool valid = e < len;
-            b.key[c][k] = valid ? float_to_key(b.v[c][k]) : 0xFFFFFFFFu;
-            lo = fminf(lo, b.v[c][k]);
-            hi = fmaxf(hi, valid ? b.v[c][k] : -inf);
+            const bool valid = full || (256u * c + 4u * lane + k < len);
+            const float x = v[c][k] + 0.0f;  // -0 -> +0
+            const uint32_t key = float_to_key(x);
+            key_min = umin32(key_min, valid ? key : 0xFFFFFFFFu);
+            key_max = umax32(key_max, valid ? key : 0u);
+            mag_max = umax32(mag_max, valid ? (__float_as_uint(x) & 0x7FFFFFFFu) : 0u);
         }
+    key_min = wave_min_u32(key_min);
+    key_max = wave_max_u32(key_max);
+    const uint32_t t_max = wave_max_u32(mag_max) >> SHIFT;
+    const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
 
-    // Levels: ends are the bucket extremes (Corollary 1), interior by greedy recursion
-    // (Algorithm 1, middle index rounded down when s is not 2^K + 1), then re-solve sweeps.
-    float lv[S];
-    lv[0] = wave_min(lo);
-    lv[S - 1] = wave_max(hi);
-#pragma unroll
-    for (int k = 1; k < S - 1; ++k) lv[k] = lv[0];
     if constexpr (S > 2) {
+        // ---- histogram (bin b counts into bin_start[b + 1]) and exact per-bin sums ---------------
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+            lds.bin_start[lane * PER + t + 1] = 0u;
+            lds.bin_sum[lane * PER + t] = 0.0;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        auto bin_of = [&](float x) -> uint32_t {
+            const uint32_t bits = __float_as_uint(x);
+            const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
+            const uint32_t u = t > t_low ? t - t_low : 0u;  // 0 .. HALF-1
+            return (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
+        };
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = full || (256u * c + 4u * lane + k < len);
+                const float x = recompute_from(v[c][k]) + 0.0f;
+                if (valid) {
+                    const uint32_t bin = bin_of(x);
+                    atomicAdd(&lds.bin_start[bin + 1], 1u);
+                    unsafeAtomicAdd(&lds.bin_sum[bin], (double)x);
+                }
+                if (k == 3) __builtin_amdgcn_sched_barrier(0);  // keep the live range of the temporaries to one chunk
+            }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- exclusive prefix over the bins (lane l owns bins l*PER .. l*PER+PER-1) --------------
+        uint32_t my_start[PER];
+        {
+            uint32_t cnt[PER];
+            double sum[PER];
+            uint32_t tot = 0;
+            double stot = 0.0;
+#pragma unroll
+            for (int t = 0; t < PER; ++t) {
+                cnt[t] = lds.bin_start[lane * PER + t + 1];
+                sum[t] = lds.bin_sum[lane * PER + t];
+                tot += cnt[t];
+                stot += sum[t];
+            }
+            uint32_t run = wave_inclusive_scan_u32(tot, lane) - tot;
+            double srun = wave_inclusive_scan_f64(stot, lane) - stot;
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int t = 0; t < PER; ++t) {
+                my_start[t] = run;
+                lds.bin_start[lane * PER + t + 1] = run;  // cursor of the scatter; ends as the next bin's start
+                lds.bin_sum[lane * PER + t] = srun;
+                run += cnt[t];
+                srun += sum[t];
+            }
+            if (lane == 63u) {
+                // the top level is only ever the right end of a solve
+                lds.lvl_count_le[S - 1] = run;
+                lds.lvl_sum_le[S - 1] = srun;
+                lds.lvl_count_lt[S - 1] = run;
+                lds.lvl_sum_lt[S - 1] = srun;
+            }
+        }
+        if (lane == 0u) {
+            lds.bin_start[0] = 0u;
+            // the bottom level is only ever the left end of a solve
+            lds.lvl_count_lt[0] = 0u;
+            lds.lvl_sum_lt[0] = 0.0;
+            lds.lvl_count_le[0] = 0u;
+            lds.lvl_sum_le[0] = 0.0;
+        }
+        if (lane < (uint32_t)S) {
+            lds.lvl_value[lane] = key_to_float(lane == (uint32_t)(S - 1) ? key_max : key_min);
+            lds.lvl_rank[lane] = 0u;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- scatter the keys into their bins: the returning add hands out the positions; afterwards
+        //      bin_start[b] is the first position of bin b and bin_start[B] the bucket length ----------
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = full || (256u * c + 4u * lane + k < len);
+                const float x = recompute_from(v[c][k]) + 0.0f;
+                if (valid) {
+                    const uint32_t pos = atomicAdd(&lds.bin_start[bin_of(x) + 1], 1u);
+                    lds.grouped[pos] = float_to_key(x);
+                }
+                if (k == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- level solves: greedy recursion (Algorithm 1), then re-solve sweeps ------------------
         constexpr GreedyOrder order = greedy_order<S>();
         const uint32_t steps = order.count + sweeps * (S - 2);
-        for (uint32_t t = 0; t < steps; ++t) {
+        for (uint32_t step = 0; step < steps; ++step) {
             uint32_t k, l, r;
-            if (t < (uint32_t)order.count) {
-                const uint32_t e = (uint32_t)(order.packed >> (9 * t));
+            if (step < (uint32_t)order.count) {
+                const uint32_t e = (uint32_t)(order.packed >> (9 * step));
                 k = e & 7u; l = (e >> 3) & 7u; r = (e >> 6) & 7u;
             } else {
-                k = 1u + (t - order.count) % (S - 2);
+                k = 1u + (step - order.count) % (S - 2);
                 l = k - 1u; r = k + 1u;
             }
-            const float solved = orq_solve<C>(b, pick_level<S>(lv, l), pick_level<S>(lv, r));
-#pragma unroll
-            for (int i = 1; i < S - 1; ++i) lv[i] = (k == (uint32_t)i) ? solved : lv[i];
+            const float L = uniform_f32(lds.lvl_value[l]);
+            const float R = uniform_f32(lds.lvl_value[r]);
+            const uint32_t cnt_lt_L = uniform_u32(lds.lvl_count_lt[l]);
+            const uint32_t cnt_le_R = uniform_u32(lds.lvl_count_le[r]);
+            const double sum_lt_L = uniform_f64(lds.lvl_sum_lt[l]);
+            const double sum_le_R = uniform_f64(lds.lvl_sum_le[r]);
+            bool copy_left = !(L < R);
+            Picked p;
+            uint32_t rank = 0;
+            if (!copy_left) {
+                // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
+                const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
+                const double T = Ssum / ((double)R - (double)L);
+                double m = floor(T);
+                if (!(m >= 0.0)) m = 0.0;
+                rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
+                rank = rank < 1u ? 1u : (rank > len ? len : rank);
+                if (rank == uniform_u32(lds.lvl_rank[k])) continue;  // same element as last time
+                p = pick_rank<D, B>(lds, my_start, rank, lane);
+                if (key_to_float(p.key) < L) copy_left = true;
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane == 0u) {
+                if (copy_left) {
+                    // the level coincides with the left end (L == R, or rounding put it below L)
+                    lds.lvl_value[k] = L;
+                    lds.lvl_count_lt[k] = cnt_lt_L;
+                    lds.lvl_sum_lt[k] = sum_lt_L;
+                    lds.lvl_count_le[k] = (L < R) ? uniform_u32(lds.lvl_count_le[l]) : cnt_le_R;
+                    lds.lvl_sum_le[k] = (L < R) ? uniform_f64(lds.lvl_sum_le[l]) : sum_le_R;
+                    lds.lvl_rank[k] = 0u;
+                } else {
+                    lds.lvl_value[k] = key_to_float(p.key);
+                    lds.lvl_count_lt[k] = p.count_lt;
+                    lds.lvl_count_le[k] = p.count_le;
+                    lds.lvl_sum_lt[k] = p.sum_lt;
+                    lds.lvl_sum_le[k] = p.sum_le;
+                    lds.lvl_rank[k] = rank;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     }
+
+    float lv[S];
+    lv[0] = key_to_float(key_min);
+    lv[S - 1] = key_to_float(key_max);
+#pragma unroll
+    for (int k = 1; k < S - 1; ++k) lv[k] = uniform_f32(lds.lvl_value[k]);
 
     if (lane == 0) {
 #pragma unroll
         for (int k = 0; k < S; ++k) levels[(size_t)bucket * S + k] = lv[k];
     }
 
-    // Encode + pack.
+    // ---- encode (random rounding, Section 3.1) + pack ----------------------------------------------
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t padded_len = (len + 63u) & ~63u;
     const size_t word0 = begin / 64;
@@ -416,8 +690,8 @@ __global__ __launch_bounds__(kBlock) void orq_quantize_kernel(const float* __res
         for (int p = 0; p < BITS; ++p) plane[p] = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float x = b.v[c][k];
-            const bool valid = 256u * c + 4u * lane + k < len;
+            const float x = v[c][k];
+            const bool valid = full || (256u * c + 4u * lane + k < len);
             // interval index: last level not above x, at most S-2
             uint32_t idx = 0;
             float base = lv[0], next = lv[1];
@@ -437,19 +711,20 @@ __global__ __launch_bounds__(kBlock) void orq_quantize_kernel(const float* __res
 #pragma unroll
             for (int p = 0; p < BITS; ++p) plane[p] |= ((code >> p) & 1u) << (4u * (lane & 7u) + k);
         }
-        // OR over the 8 lanes that make up one 32-bit half of a packed word.
+        // OR over the 8 lanes that make up one 32-bit half of a packed word
 #pragma unroll
         for (int p = 0; p < BITS; ++p) {
             uint32_t x = plane[p];
-            x |= __shfl_xor(x, 1, kWave);
-            x |= __shfl_xor(x, 2, kWave);
-            x |= __shfl_xor(x, 4, kWave);
-            const uint32_t first = 256u * c + 32u * (lane >> 3);  // first element of this half-word
+            x |= dpp_u32<kDppXor1>(x);
+            x |= dpp_u32<kDppXor2>(x);
+            x |= dpp_u32<kDppHalfMirror>(x);
+            const uint32_t first = 256u * c + 32u * (lane >> 3);  // first element of this half word
             if ((lane & 7u) == 0 && first < padded_len) {
                 const size_t word = (word0 + 4u * c + (lane >> 4)) * BITS + p;
                 codes32[word * 2 + ((lane >> 3) & 1u)] = x;
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -615,8 +890,7 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
 template <int C, int BITS>
 void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
-    const uint32_t blocks = (nb + kWavesPerBlock - 1) / kWavesPerBlock;
-    hipLaunchKernelGGL((orq_quantize_kernel<C, BITS>), dim3(blocks), dim3(kBlock), 0, st, g, n, p->bucket_size,
+    hipLaunchKernelGGL((orq_quantize_kernel<C, BITS>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
                        p->level_iters, nb, p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
 }
 
