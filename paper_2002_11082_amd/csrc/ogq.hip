@@ -276,9 +276,11 @@ constexpr GreedyOrder greedy_order()
 // LDS of one bucket: D = element capacity, B = number of bins.
 template <int D, int B>
 struct OrqLds {
-    uint32_t grouped[D];       // ordered keys grouped by bin (unsorted inside a bin)
-    uint32_t bin_start[B + 4]; // histogram, then exclusive prefix of the bin counts; [B] = length
-    double bin_sum[B];         // per-bin sum, then exclusive prefix of the bin sums
+    // fp32 bit patterns (-0 stored as +0) grouped by bin, unsorted inside a bin.  Position i lives at
+    // word i + i/32, so that the 64 lanes reading consecutive blocks of D/64 positions hit distinct banks.
+    uint32_t grouped[D + D / 32];
+    uint32_t bin_start[B + 4];  // histogram, then first position of each bin; [B] = bucket length
+    double block_prefix[64];    // fp64 sum of all positions before block l (block = D/64 positions)
     // per level k: value; #{v < value}; #{v <= value}; sum{v < value}; sum{v <= value}; the rank it
     // was picked at (0 = not picked by rank)
     double lvl_sum_lt[8];
@@ -288,6 +290,8 @@ struct OrqLds {
     uint32_t lvl_count_le[8];
     uint32_t lvl_rank[8];
 };
+
+__device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 5); }
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
 {
@@ -336,21 +340,40 @@ __device__ __forceinline__ double wave_inclusive_scan_f64(double x, uint32_t lan
 }
 
 // Ascending bitonic sort of one key per lane across the 64 lanes.
-constexpr int kDppRor8 = 0x128;  // rotate by 8 inside a row of 16 lanes = partner lane ^ 8
+constexpr int kDppRor8 = 0x128;   // rotate by 8 inside a row of 16 lanes: partner lane ^ 8
+constexpr int kDppRowShl4 = 0x104;  // lane i takes lane i + 4 of its row
+constexpr int kDppRowShr4 = 0x114;  // lane i takes lane i - 4 of its row
 
+// Value held by lane (lane ^ DIST).
 template <int DIST>
-__device__ __forceinline__ uint32_t lane_xor(uint32_t x)
+__device__ __forceinline__ uint32_t lane_xor(uint32_t x, uint32_t lane)
 {
-    if constexpr (DIST == 1) return dpp_u32<kDppXor1>(x);
-    else if constexpr (DIST == 2) return dpp_u32<kDppXor2>(x);
-    else if constexpr (DIST == 8) return dpp_u32<kDppRor8>(x);
-    else return (uint32_t)__shfl_xor((int)x, DIST, kWave);
+    if constexpr (DIST == 1) {
+        return dpp_u32<kDppXor1>(x);
+    } else if constexpr (DIST == 2) {
+        return dpp_u32<kDppXor2>(x);
+    } else if constexpr (DIST == 4) {
+        // banks (groups of 4 lanes) 0 and 2 of every row take the lane 4 above, banks 1 and 3 the lane 4 below
+        int y = __builtin_amdgcn_update_dpp((int)x, (int)x, kDppRowShl4, 0xF, 0x5, false);
+        y = __builtin_amdgcn_update_dpp(y, (int)x, kDppRowShr4, 0xF, 0xA, false);
+        return (uint32_t)y;
+    } else if constexpr (DIST == 8) {
+        return dpp_u32<kDppRor8>(x);
+    } else if constexpr (DIST == 16) {
+        // rows (0,1) and (2,3) trade places
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        return (lane & 16u) ? r[0] : r[1];
+    } else {
+        // the two halves of the wave trade places
+        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        return (lane & 32u) ? r[0] : r[1];
+    }
 }
 
 template <int K, int DIST>
 __device__ __forceinline__ uint32_t bitonic_step(uint32_t x, uint32_t lane)
 {
-    const uint32_t y = lane_xor<DIST>(x);
+    const uint32_t y = lane_xor<DIST>(x, lane);
     const bool ascending = (lane & (uint32_t)K) == 0;
     const bool lower = (lane & (uint32_t)DIST) == 0;
     const uint32_t mn = umin32(x, y), mx = umax32(x, y);
@@ -385,6 +408,7 @@ __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint3
                                             uint32_t rank, uint32_t lane)
 {
     constexpr int PER = B / 64;
+    constexpr uint32_t BLOCK = D / 64;  // positions per block of the fp64 prefix
     // the bin holding the rank: the last bin whose first position is below the rank
     uint32_t starts_below = 0;
 #pragma unroll
@@ -392,20 +416,26 @@ __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint3
     const uint32_t bin = wave_sum_u32(starts_below) - 1u;  // bin_start[0] = 0 < rank: at least one
     const uint32_t first = uniform_u32(lds.bin_start[bin]);
     const uint32_t count = uniform_u32(lds.bin_start[bin + 1]) - first;
-    const double before = uniform_f64(lds.bin_sum[bin]);
     const uint32_t r_in = rank - first;  // 1-based rank inside the bin
+
+    // sum of everything before the bin = prefix of its block + the block's positions before `first`
+    const uint32_t block = first / BLOCK;
+    const uint32_t block_first = block * BLOCK;
+    const double before_block = uniform_f64(lds.block_prefix[block]);
+    const float head = lane < first - block_first ? __uint_as_float(lds.grouped[skewed(block_first + lane)]) : 0.0f;
 
     uint32_t key, c_lt, c_le;
     double s_lt;
     if (count <= 64u) {
-        const uint32_t mine = lane < count ? lds.grouped[first + lane] : 0xFFFFFFFFu;
+        const uint32_t mine =
+            lane < count ? float_to_key(__uint_as_float(lds.grouped[skewed(first + lane)])) : 0xFFFFFFFFu;
         const uint32_t sorted = wave_sort_u32(mine, lane);
         key = __builtin_amdgcn_readlane(sorted, r_in - 1u);
         const bool lt = sorted < key;
         const bool le = (sorted <= key) && (lane < count);
         c_lt = (uint32_t)__popcll(__ballot(lt));
         c_le = (uint32_t)__popcll(__ballot(le));
-        s_lt = wave_sum(lt ? (double)key_to_float(sorted) : 0.0);
+        s_lt = wave_sum((double)head + (lt ? (double)key_to_float(sorted) : 0.0));
     } else {
         // a crowded bin (many equal or nearly equal values): bisection on the key over all its chunks
         uint32_t prefix = 0;
@@ -414,7 +444,7 @@ __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint3
             uint32_t below = 0;
             for (uint32_t base = 0; base < count; base += 64u) {
                 const uint32_t i = base + lane;
-                const uint32_t k = i < count ? lds.grouped[first + i] : 0xFFFFFFFFu;
+                const uint32_t k = i < count ? float_to_key(__uint_as_float(lds.grouped[skewed(first + i)])) : 0xFFFFFFFFu;
                 below += (uint32_t)__popcll(__ballot(k < cand));
             }
             if (below < r_in) prefix = cand;
@@ -422,14 +452,15 @@ __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint3
         key = prefix;
         c_lt = 0;
         c_le = 0;
-        double part = 0.0;
+        double part = (double)head;
         for (uint32_t base = 0; base < count; base += 64u) {
             const uint32_t i = base + lane;
-            const uint32_t k = i < count ? lds.grouped[first + i] : 0xFFFFFFFFu;
+            const float x = i < count ? __uint_as_float(lds.grouped[skewed(first + i)]) : 0.0f;
+            const uint32_t k = i < count ? float_to_key(x) : 0xFFFFFFFFu;
             const bool lt = k < key;
             c_lt += (uint32_t)__popcll(__ballot(lt));
             c_le += (uint32_t)__popcll(__ballot(k <= key && i < count));
-            part += lt ? (double)key_to_float(k) : 0.0;
+            part += lt ? (double)x : 0.0;
         }
         s_lt = wave_sum(part);
     }
@@ -437,7 +468,7 @@ __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint3
     p.key = key;
     p.count_lt = first + c_lt;
     p.count_le = first + c_le;
-    p.sum_lt = before + s_lt;
+    p.sum_lt = before_block + s_lt;
     p.sum_le = p.sum_lt + (double)(c_le - c_lt) * (double)key_to_float(key);
     return p;
 }
@@ -452,29 +483,28 @@ __device__ __forceinline__ float recompute_from(float x)
     return x;
 }
 
-template <int C, int BITS>
-__global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
-                                                             uint32_t bucket_size, uint32_t sweeps,
-                                                             uint32_t num_buckets, uint64_t seed,
-                                                             uint64_t index_offset, float* __restrict__ levels,
-                                                             uint32_t* __restrict__ codes32)
+template <int C>
+struct OrqShape {
+    static constexpr int D = 256 * C;               // element capacity of the wave
+    static constexpr int B = C >= 16 ? 512 : 256;   // bins
+    static constexpr int SHIFT = C >= 16 ? 19 : 20; // magnitude bits dropped: keeps exponent + 4 (3) mantissa bits
+};
+
+// FULL: the bucket has exactly 256*C elements (no padding, no per-element validity tests).
+template <int C, int BITS, bool FULL>
+__device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B>& lds, const float* __restrict__ g,
+                                           uint32_t len, size_t begin, uint32_t bucket, uint32_t sweeps, uint64_t seed,
+                                           uint64_t index_offset, float* __restrict__ levels,
+                                           uint32_t* __restrict__ codes32)
 {
     constexpr int S = 1 << BITS;
-    constexpr int D = 256 * C;
-    constexpr int B = C >= 16 ? 512 : 256;    // bins
-    constexpr int PER = B / 64;               // bins per lane in the prefix step
-    constexpr int HALF = B / 2;               // bins per sign
-    constexpr int SHIFT = C >= 16 ? 19 : 20;  // magnitude bits dropped: keeps exponent + 4 (3) mantissa bits
-    __shared__ OrqLds<D, B> lds;
-
-    const uint32_t bucket = blockIdx.x;
-    if (bucket >= num_buckets) return;
+    constexpr int D = OrqShape<C>::D;
+    constexpr int B = OrqShape<C>::B;
+    constexpr int PER = B / 64;   // bins per lane in the prefix step
+    constexpr int HALF = B / 2;   // bins per sign
+    constexpr int SHIFT = OrqShape<C>::SHIFT;
+    constexpr bool full = FULL;
     const uint32_t lane = threadIdx.x & 63u;
-    const size_t begin = (size_t)bucket * bucket_size;
-    const size_t rest = n - begin;
-    const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
-    const float* g = grad + begin;
-    const bool full = len == (uint32_t)D;
 
     // ---- load (read once: bypass the caches); padding holds +0 and is never binned or encoded ----
     float v[C][4];
@@ -513,71 +543,85 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
     const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
 
     if constexpr (S > 2) {
-        // ---- histogram (bin b counts into bin_start[b + 1]) and exact per-bin sums ---------------
+        // ---- histogram: the returning LDS add hands every element its position inside its bin ------
 #pragma unroll
-        for (int t = 0; t < PER; ++t) {
-            lds.bin_start[lane * PER + t + 1] = 0u;
-            lds.bin_sum[lane * PER + t] = 0.0;
-        }
+        for (int t = 0; t < PER; ++t) lds.bin_start[lane * PER + t] = 0u;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        auto bin_of = [&](float x) -> uint32_t {
-            const uint32_t bits = __float_as_uint(x);
-            const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
-            const uint32_t u = t > t_low ? t - t_low : 0u;  // 0 .. HALF-1
-            return (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
-        };
+        uint32_t slot[C][4];  // bin | position inside the bin << 16
 #pragma unroll
         for (int c = 0; c < C; ++c)
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const bool valid = full || (256u * c + 4u * lane + k < len);
-                const float x = recompute_from(v[c][k]) + 0.0f;
-                if (valid) {
-                    const uint32_t bin = bin_of(x);
-                    atomicAdd(&lds.bin_start[bin + 1], 1u);
-                    unsafeAtomicAdd(&lds.bin_sum[bin], (double)x);
-                }
-                if (k == 3) __builtin_amdgcn_sched_barrier(0);  // keep the live range of the temporaries to one chunk
+                const uint32_t bits = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
+                const uint32_t u = t > t_low ? t - t_low : 0u;  // 0 .. HALF-1
+                const uint32_t bin = (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
+                slot[c][k] = 0u;
+                if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
             }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
-        // ---- exclusive prefix over the bins (lane l owns bins l*PER .. l*PER+PER-1) --------------
+        // ---- exclusive prefix over the bin counts (lane l owns bins l*PER .. l*PER+PER-1) ------------
         uint32_t my_start[PER];
         {
             uint32_t cnt[PER];
-            double sum[PER];
             uint32_t tot = 0;
-            double stot = 0.0;
 #pragma unroll
             for (int t = 0; t < PER; ++t) {
-                cnt[t] = lds.bin_start[lane * PER + t + 1];
-                sum[t] = lds.bin_sum[lane * PER + t];
+                cnt[t] = lds.bin_start[lane * PER + t];
                 tot += cnt[t];
-                stot += sum[t];
             }
             uint32_t run = wave_inclusive_scan_u32(tot, lane) - tot;
-            double srun = wave_inclusive_scan_f64(stot, lane) - stot;
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int t = 0; t < PER; ++t) {
                 my_start[t] = run;
-                lds.bin_start[lane * PER + t + 1] = run;  // cursor of the scatter; ends as the next bin's start
-                lds.bin_sum[lane * PER + t] = srun;
+                lds.bin_start[lane * PER + t] = run;
                 run += cnt[t];
-                srun += sum[t];
             }
+            if (lane == 63u) lds.bin_start[B] = run;  // = len
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- scatter the values into their bins ---------------------------------------------------
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = full || (256u * c + 4u * lane + k < len);
+                if (valid) {
+                    const uint32_t bin = slot[c][k] & 0xFFFFu, pos = slot[c][k] >> 16;
+                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                }
+            }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- fp64 prefix of the grouped values at block granularity (lane l sums block l) ------------
+        {
+            constexpr uint32_t BLOCK = D / 64;
+            double part = 0.0;
+#pragma unroll
+            for (uint32_t i = 0; i < BLOCK; ++i) {
+                const uint32_t position = lane * BLOCK + i;
+                const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
+                part += (double)x;
+            }
+            const double incl = wave_inclusive_scan_f64(part, lane);
+            lds.block_prefix[lane] = incl - part;
             if (lane == 63u) {
                 // the top level is only ever the right end of a solve
-                lds.lvl_count_le[S - 1] = run;
-                lds.lvl_sum_le[S - 1] = srun;
-                lds.lvl_count_lt[S - 1] = run;
-                lds.lvl_sum_lt[S - 1] = srun;
+                lds.lvl_count_le[S - 1] = len;
+                lds.lvl_sum_le[S - 1] = incl;
+                lds.lvl_count_lt[S - 1] = len;
+                lds.lvl_sum_lt[S - 1] = incl;
             }
         }
         if (lane == 0u) {
-            lds.bin_start[0] = 0u;
             // the bottom level is only ever the left end of a solve
             lds.lvl_count_lt[0] = 0u;
             lds.lvl_sum_lt[0] = 0.0;
@@ -588,23 +632,6 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
             lds.lvl_value[lane] = key_to_float(lane == (uint32_t)(S - 1) ? key_max : key_min);
             lds.lvl_rank[lane] = 0u;
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-
-        // ---- scatter the keys into their bins: the returning add hands out the positions; afterwards
-        //      bin_start[b] is the first position of bin b and bin_start[B] the bucket length ----------
-#pragma unroll
-        for (int c = 0; c < C; ++c)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const bool valid = full || (256u * c + 4u * lane + k < len);
-                const float x = recompute_from(v[c][k]) + 0.0f;
-                if (valid) {
-                    const uint32_t pos = atomicAdd(&lds.bin_start[bin_of(x) + 1], 1u);
-                    lds.grouped[pos] = float_to_key(x);
-                }
-                if (k == 3) __builtin_amdgcn_sched_barrier(0);
-            }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
@@ -677,6 +704,9 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
     }
 
     // ---- encode (random rounding, Section 3.1) + pack ----------------------------------------------
+    // the selects below take the levels from vector registers (one copy per lane, made once)
+#pragma unroll
+    for (int k = 0; k < S; ++k) asm volatile("v_mov_b32 %0, %1" : "=v"(lv[k]) : "s"(lv[k]));
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t padded_len = (len + 63u) & ~63u;
     const size_t word0 = begin / 64;
@@ -726,6 +756,25 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+template <int C, int BITS>
+__global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
+                                                             uint32_t bucket_size, uint32_t sweeps,
+                                                             uint32_t num_buckets, uint64_t seed,
+                                                             uint64_t index_offset, float* __restrict__ levels,
+                                                             uint32_t* __restrict__ codes32)
+{
+    __shared__ OrqLds<OrqShape<C>::D, OrqShape<C>::B> lds;
+    const uint32_t bucket = blockIdx.x;
+    if (bucket >= num_buckets) return;
+    const size_t begin = (size_t)bucket * bucket_size;
+    const size_t rest = n - begin;
+    const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
+    if (len == (uint32_t)OrqShape<C>::D)
+        orq_bucket<C, BITS, true>(lds, grad + begin, len, begin, bucket, sweeps, seed, index_offset, levels, codes32);
+    else
+        orq_bucket<C, BITS, false>(lds, grad + begin, len, begin, bucket, sweeps, seed, index_offset, levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
