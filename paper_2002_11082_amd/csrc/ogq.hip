@@ -706,7 +706,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     // ---- encode (random rounding, Section 3.1) + pack ----------------------------------------------
     // the selects below take the levels from vector registers (one copy per lane, made once)
 #pragma unroll
-    for (int k = 0; k < S; ++k) asm volatile("v_mov_b32 %0, %1" : "=v"(lv[k]) : "s"(lv[k]));
+    for (int k = 0; k < S; ++k) asm("v_mov_b32 %0, %1" : "=v"(lv[k]) : "s"(lv[k]));
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t padded_len = (len + 63u) & ~63u;
     const size_t word0 = begin / 64;
@@ -812,6 +812,18 @@ __device__ __forceinline__ float select_level(const uint64_t* __restrict__ w, co
     }
 }
 
+// Loads one bucket's level table (wave-uniform address, scalar loads) into vector registers: the
+// selects take two vector sources and the packed word as their lane mask.
+template <int S>
+__device__ __forceinline__ void load_levels(const float* __restrict__ table, float (&lv)[S])
+{
+    float s[S];
+#pragma unroll
+    for (int k = 0; k < S; ++k) s[k] = table[k];
+#pragma unroll
+    for (int k = 0; k < S; ++k) asm("v_mov_b32 %0, %1" : "=v"(lv[k]) : "s"(s[k]));
+}
+
 // ONE_BUCKET: the 16 word groups of a span lie in one bucket (bucket_size is a multiple of 1024),
 // so each worker's level table is fetched once per span; otherwise once per word group.
 template <int BITS, bool ONE_BUCKET>
@@ -826,6 +838,8 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t rest = total_words - word0;
     const uint32_t n_words = rest < (uint32_t)kSpanWords ? rest : (uint32_t)kSpanWords;
+    // every element of the span exists: no per-word or per-element bounds tests
+    const bool whole = n_words == (uint32_t)kSpanWords && ((size_t)word0 + kSpanWords) * 64 <= n;
 
     double acc[kSpanWords];
 #pragma unroll
@@ -835,11 +849,9 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
         const uint64_t* __restrict__ cw = ptrs.codes[w] + (size_t)word0 * BITS;
         const float* __restrict__ table = ptrs.levels[w];
         if constexpr (ONE_BUCKET) {
-            const float* __restrict__ lvp = table + (size_t)(word0 / words_per_bucket) * S;
             float lv[S];
-#pragma unroll
-            for (int k = 0; k < S; ++k) lv[k] = lvp[k];
-            if (n_words == (uint32_t)kSpanWords) {
+            load_levels<S>(table + (size_t)(word0 / words_per_bucket) * S, lv);
+            if (whole) {
 #pragma unroll
                 for (int j = 0; j < kSpanWords; ++j) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
             } else {
@@ -851,20 +863,24 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
 #pragma unroll
             for (int j = 0; j < kSpanWords; ++j)
                 if ((uint32_t)j < n_words) {
-                    const float* __restrict__ lvp = table + (size_t)((word0 + j) / words_per_bucket) * S;
                     float lv[S];
-#pragma unroll
-                    for (int k = 0; k < S; ++k) lv[k] = lvp[k];
+                    load_levels<S>(table + (size_t)((word0 + j) / words_per_bucket) * S, lv);
                     acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
                 }
         }
     }
     float* __restrict__ o = out + (size_t)word0 * 64 + lane;
-    const size_t first = (size_t)word0 * 64 + lane;
+    if (whole) {
 #pragma unroll
-    for (int j = 0; j < kSpanWords; ++j)
-        if ((uint32_t)j < n_words && first + 64u * j < n)
+        for (int j = 0; j < kSpanWords; ++j)
             __builtin_nontemporal_store((float)(acc[j] * inv_workers), o + 64 * j);  // written once, never re-read here
+    } else {
+        const size_t first = (size_t)word0 * 64 + lane;
+#pragma unroll
+        for (int j = 0; j < kSpanWords; ++j)
+            if ((uint32_t)j < n_words && first + 64u * j < n)
+                __builtin_nontemporal_store((float)(acc[j] * inv_workers), o + 64 * j);
+    }
 }
 
 // ----------------------------------------------------------------------------------------------
