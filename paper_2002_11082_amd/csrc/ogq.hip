@@ -66,11 +66,14 @@ __device__ __forceinline__ float readlane_f32(float x, int lane)
     return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), lane));
 }
 
-// Lane `lane` (compile-time constant) of `dst` takes the wave-uniform value `value`.
+// v_writelane_b32 through the compiler's own intrinsic (the compiler then inserts the wait states the
+// instruction needs after a VALU write of its scalar source; hand-written asm would not get them).
+extern "C" __device__ uint32_t ogq_llvm_writelane(uint32_t value, uint32_t lane, uint32_t old) __asm("llvm.amdgcn.writelane.i32");
+
+// Lane `lane` of `dst` takes the wave-uniform value `value`; the other lanes keep theirs.
 __device__ __forceinline__ uint32_t writelane(uint32_t dst, uint32_t value, int lane)
 {
-    asm("v_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(value), "n"(lane));
-    return dst;
+    return ogq_llvm_writelane(value, (uint32_t)lane, dst);
 }
 
 // Wave-wide sum; the result is wave-uniform.
@@ -81,6 +84,16 @@ __device__ __forceinline__ double wave_sum(double x)
     x += dpp_f64<kDppHalfMirror>(x);
     x += dpp_f64<kDppMirror>(x);
     return (readlane_f64(x, 0) + readlane_f64(x, 16)) + (readlane_f64(x, 32) + readlane_f64(x, 48));
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
+{
+    x += dpp_u32<kDppXor1>(x);
+    x += dpp_u32<kDppXor2>(x);
+    x += dpp_u32<kDppHalfMirror>(x);
+    x += dpp_u32<kDppMirror>(x);
+    return (__builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16)) +
+           (__builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48));
 }
 
 __device__ __forceinline__ float wave_min(float x)
@@ -133,36 +146,59 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
     }
 
     double part = 0.0;
+    float mag = 0.0f;
 #pragma unroll
-    for (int j = 0; j < E; ++j) part += (double)v[j];
+    for (int j = 0; j < E; ++j) {
+        part += (double)v[j];
+        mag = fmaxf(mag, fabsf(v[j]));
+    }
     const double total = wave_sum(part);
     float b0 = (float)(total / (double)len);  // threshold starts at the bucket mean
+    // The upper sum is taken as total - lower sum.  Both are fp64 sums of at most 4096 fp32 values
+    // (error below 2^-53 * n^2 * max|v| each, and exact for any bucket whose values span fewer than
+    // ~18 binades), so the difference is trusted unless it is tiny against the largest element; such
+    // a bucket sums its upper side directly.
+    const float trust_above = 1e-3f * wave_max(mag);
 
     double b_lo = 0.0, b_hi = 0.0;
     uint32_t word_lo = 0, word_hi = 0;  // lane j ends up holding packed word j of the bucket
     uint32_t prev_n_lo = 0xFFFFFFFFu;
     for (uint32_t it = 0;; ++it) {
-        double s_lo = 0.0, s_hi = 0.0;
-        uint32_t n_lo = 0;
+        double s_lo = 0.0;
+        uint32_t below = 0;
 #pragma unroll
         for (int j = 0; j < E; ++j) {
             const bool valid = FULL || (64u * j + lane < len);
             const bool lo = valid && (v[j] < b0);
             const uint64_t lo_mask = __ballot(lo);
             const uint64_t hi_mask = FULL ? ~lo_mask : __ballot(valid && !lo);
-            n_lo += (uint32_t)__popcll(lo_mask);
-            const float x_lo = lo ? v[j] : 0.0f;
-            const float x_hi = v[j] - x_lo;  // exact: one of the two is zero (padding holds 0)
-            s_lo += (double)x_lo;
-            s_hi += (double)x_hi;
+            below += lo ? 1u : 0u;
+            s_lo += (double)(lo ? v[j] : 0.0f);
             word_lo = writelane(word_lo, (uint32_t)hi_mask, j);
             word_hi = writelane(word_hi, (uint32_t)(hi_mask >> 32), j);
         }
         s_lo = wave_sum(s_lo);
-        s_hi = wave_sum(s_hi);
+        const uint32_t n_lo = wave_sum_u32(below);
+        double s_hi = total - s_lo;
+        if (!(fabs(s_hi) >= (double)trust_above)) {
+            double direct = 0.0;
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                const bool valid = FULL || (64u * j + lane < len);
+                direct += (double)((valid && !(v[j] < b0)) ? v[j] : 0.0f);
+            }
+            s_hi = wave_sum(direct);
+        }
         const uint32_t n_hi = len - n_lo;
-        if (n_hi > 0) b_hi = s_hi / (double)n_hi;
-        if (n_lo > 0) b_lo = s_lo / (double)n_lo;
+        {
+            // both conditional means with one division sequence: lane 0 divides the lower side, the
+            // other lanes the upper side
+            const double num = lane == 0 ? s_lo : s_hi;
+            const uint32_t den = lane == 0 ? n_lo : n_hi;
+            const double quot = num / (double)(den > 0 ? den : 1u);
+            if (n_lo > 0) b_lo = readlane_f64(quot, 0);
+            if (n_hi > 0) b_hi = readlane_f64(quot, 1);
+        }
         if (n_lo == 0) b_lo = b_hi;  // constant bucket: both levels equal
         if (n_hi == 0) b_hi = b_lo;
         // Further threshold updates are identities once the partition repeats.
@@ -179,15 +215,18 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
     if (lane < n_words) words[lane] = ((uint64_t)word_hi << 32) | word_lo;
 }
 
-// At most 4 waves per SIMD: with more, all resident waves load and then compute in lock-step and
-// the tail of a launch that is only ~1.5 waves of workgroups deep is not overlapped.
+constexpr int kBinGradWaves = 2;  // buckets per workgroup
+
+// At most 4 waves per SIMD and small workgroups: with more, all resident waves load and then
+// compute in lock-step and the tail of a launch that is only ~1.5 waves of workgroups deep is not
+// overlapped.
 template <int E>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 4))) void bingrad_quantize_kernel(const float* __restrict__ grad, size_t n,
-                                                                  uint32_t bucket_size, uint32_t iters,
-                                                                  uint32_t num_buckets, float* __restrict__ levels,
-                                                                  uint64_t* __restrict__ codes)
+__global__ __launch_bounds__(kWave* kBinGradWaves)
+    __attribute__((amdgpu_waves_per_eu(E > 32 ? 2 : 4, 4))) void bingrad_quantize_kernel(
+    const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, uint32_t num_buckets,
+    float* __restrict__ levels, uint64_t* __restrict__ codes)
 {
-    const uint32_t bucket = uniform_u32(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const uint32_t bucket = uniform_u32(blockIdx.x * kBinGradWaves + (threadIdx.x >> 6));
     if (bucket >= num_buckets) return;
     const size_t begin = (size_t)bucket * bucket_size;
     const size_t rest = n - begin;
@@ -292,16 +331,6 @@ struct OrqLds {
 };
 
 __device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 5); }
-
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
-{
-    x += dpp_u32<kDppXor1>(x);
-    x += dpp_u32<kDppXor2>(x);
-    x += dpp_u32<kDppHalfMirror>(x);
-    x += dpp_u32<kDppMirror>(x);
-    return (__builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16)) +
-           (__builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48));
-}
 
 __device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __device__ __forceinline__ uint32_t umax32(uint32_t a, uint32_t b) { return a > b ? a : b; }
@@ -692,11 +721,12 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         }
     }
 
+    // every lane holds its own copy of the levels (the selects of the encoder take vector sources)
     float lv[S];
     lv[0] = key_to_float(key_min);
     lv[S - 1] = key_to_float(key_max);
 #pragma unroll
-    for (int k = 1; k < S - 1; ++k) lv[k] = uniform_f32(lds.lvl_value[k]);
+    for (int k = 1; k < S - 1; ++k) lv[k] = lds.lvl_value[k];
 
     if (lane == 0) {
 #pragma unroll
@@ -704,9 +734,6 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     }
 
     // ---- encode (random rounding, Section 3.1) + pack ----------------------------------------------
-    // the selects below take the levels from vector registers (one copy per lane, made once)
-#pragma unroll
-    for (int k = 0; k < S; ++k) asm("v_mov_b32 %0, %1" : "=v"(lv[k]) : "s"(lv[k]));
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t padded_len = (len + 63u) & ~63u;
     const size_t word0 = begin / 64;
@@ -947,8 +974,8 @@ template <int E>
 void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                     hipStream_t st)
 {
-    const uint32_t blocks = (nb + kWavesPerBlock - 1) / kWavesPerBlock;
-    hipLaunchKernelGGL(bingrad_quantize_kernel<E>, dim3(blocks), dim3(kBlock), 0, st, g, n, p->bucket_size,
+    const uint32_t blocks = (nb + kBinGradWaves - 1) / kBinGradWaves;
+    hipLaunchKernelGGL(bingrad_quantize_kernel<E>, dim3(blocks), dim3(kWave * kBinGradWaves), 0, st, g, n, p->bucket_size,
                        p->level_iters, nb, lv, static_cast<uint64_t*>(codes));
 }
 
