@@ -43,7 +43,8 @@ typedef enum {
     OGQ_ERR_ALIGNMENT = -6,     /* a device pointer is not 16-byte aligned */
     OGQ_ERR_INDEX_OFFSET = -7,  /* index_offset is not a multiple of 64 */
     OGQ_ERR_LAUNCH = -8,        /* the HIP runtime refused the launch (ogq_last_hip_error()) */
-    OGQ_ERR_SIZE = -9           /* n is too large for the 32-bit bucket grid (n/bucket_size >= 2^31) */
+    OGQ_ERR_SIZE = -9,          /* n is too large for the 32-bit bucket grid (n/bucket_size >= 2^31) */
+    OGQ_ERR_CLIP = -10          /* clip_factor is negative or not finite */
 } ogq_status_t;
 
 typedef enum {
@@ -72,6 +73,12 @@ typedef struct {
      * that belongs to global index index_offset + i, so a bucket-aligned shard reproduces the
      * codes of the full vector. */
     uint64_t index_offset;
+    /* Gradient clipping before quantization (Section 5, taken over from TernGrad): every bucket value
+     * becomes sign(v) * min(|v|, clip_factor * sigma), sigma^2 = population variance of the bucket about
+     * its mean (fp64), threshold rounded to fp32; levels and codes are those of the clipped bucket.
+     * 0 = off.  The paper uses 2.5 (and 1.7). */
+    float clip_factor;
+    uint32_t reserved;     /* must be 0 */
 } ogq_params_t;
 
 /* Sizes of the outputs of ogq_quantize for a gradient of n elements (pure host arithmetic).

@@ -56,9 +56,11 @@ def lib() -> ctypes.CDLL:
         L.ogq_oracle_pack.restype = None
         L.ogq_oracle_unpack.argtypes = [vp, sz, u32, vp]
         L.ogq_oracle_unpack.restype = None
-        L.ogq_oracle_quantize_codes.argtypes = [vp, sz, u32, u32, u32, u32, u64, u64, vp, vp, vp]
+        L.ogq_oracle_clip_bucket.argtypes = [vp, sz, ctypes.c_float, vp]
+        L.ogq_oracle_clip_bucket.restype = None
+        L.ogq_oracle_quantize_codes.argtypes = [vp, sz, u32, u32, u32, u32, u64, u64, ctypes.c_float, vp, vp, vp]
         L.ogq_oracle_quantize_codes.restype = ctypes.c_int
-        L.ogq_oracle_quantize.argtypes = [vp, sz, u32, u32, u32, u32, u64, u64, vp, vp]
+        L.ogq_oracle_quantize.argtypes = [vp, sz, u32, u32, u32, u32, u64, u64, ctypes.c_float, vp, vp]
         L.ogq_oracle_quantize.restype = ctypes.c_int
         L.ogq_oracle_dequantize_average.argtypes = [vp, vp, u32, sz, u32, u32, vp]
         L.ogq_oracle_dequantize_average.restype = ctypes.c_int
@@ -132,8 +134,15 @@ def unpack(words, n: int, bits: int) -> np.ndarray:
     return codes
 
 
+def clip_bucket(g, c: float) -> np.ndarray:
+    g = _f32(g)
+    out = np.zeros_like(g)
+    lib().ogq_oracle_clip_bucket(_ptr(g), g.size, float(c), _ptr(out))
+    return out
+
+
 def quantize_codes(g, bucket_size: int, bits: int, scheme: int, level_iters: int = 0, seed: int = 0,
-                   index_offset: int = 0):
+                   index_offset: int = 0, clip_factor: float = 0.0):
     """Returns (levels [num_buckets*2^bits] f32, codes [n] u8, thresholds [num_buckets] f32)."""
     g = _f32(g)
     n = g.size
@@ -142,14 +151,14 @@ def quantize_codes(g, bucket_size: int, bits: int, scheme: int, level_iters: int
     codes = np.zeros(n, dtype=np.uint8)
     thresholds = np.zeros(nb, dtype=np.float32)
     rc = lib().ogq_oracle_quantize_codes(_ptr(g), n, bucket_size, bits, scheme, level_iters, seed,
-                                         index_offset, _ptr(levels), _ptr(codes), _ptr(thresholds))
+                                         index_offset, float(clip_factor), _ptr(levels), _ptr(codes), _ptr(thresholds))
     if rc != 0:
         raise ValueError(f"oracle quantize_codes rejected its arguments (rc={rc})")
     return levels, codes, thresholds
 
 
 def quantize(g, bucket_size: int, bits: int, scheme: int, level_iters: int = 0, seed: int = 0,
-             index_offset: int = 0):
+             index_offset: int = 0, clip_factor: float = 0.0):
     """Returns (levels f32, packed code words u64)."""
     g = _f32(g)
     n = g.size
@@ -157,7 +166,7 @@ def quantize(g, bucket_size: int, bits: int, scheme: int, level_iters: int = 0, 
     levels = np.zeros(nb << bits, dtype=np.float32)
     words = np.zeros(((n + 63) // 64) * bits, dtype=np.uint64)
     rc = lib().ogq_oracle_quantize(_ptr(g), n, bucket_size, bits, scheme, level_iters, seed, index_offset,
-                                   _ptr(levels), _ptr(words))
+                                   float(clip_factor), _ptr(levels), _ptr(words))
     if rc != 0:
         raise ValueError(f"oracle quantize rejected its arguments (rc={rc})")
     return levels, words

@@ -17,7 +17,8 @@
  * (Remark after Theorem 1); endpoints are min/max (Corollary 1); BinGrad-b levels are the
  * conditional means, reduce to Scaled SignSGD on +-paired data and converge to 1-D 2-means;
  * random rounding is unbiased with variance (v-b_k)(b_{k+1}-v) by Monte Carlo; pack/unpack
- * round trip and hand-placed bits; decode-average special cases.
+ * round trip and hand-placed bits; decode-average special cases; clipping against a hand example,
+ * the library standard deviation and its limiting cases.
  * No function here is "parity unpinned".
  *
  * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC ogq_oracle.c -o libogq_oracle.so -lm
@@ -215,13 +216,41 @@ void ogq_oracle_unpack(const uint64_t* words, size_t n, uint32_t bits, uint8_t* 
     }
 }
 
+/* Gradient clipping before quantization (Section 5, the technique taken over from TernGrad):
+ * clip(v) = sign(v) * min(|v|, c * sigma), sigma^2 = variance of the bucket's elements about their
+ * mean (population variance, fp64), threshold rounded to fp32.  Applied per bucket, because every
+ * bucket is quantized on its own.  c <= 0 leaves the bucket unchanged. */
+void ogq_oracle_clip_bucket(const float* g, size_t n, float c, float* out)
+{
+    if (!(c > 0.0f)) {
+        for (size_t i = 0; i < n; ++i) out[i] = g[i];
+        return;
+    }
+    double sum = 0.0;
+    for (size_t i = 0; i < n; ++i) sum += (double)g[i];
+    double mean = sum / (double)n;
+    double ss = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        double dv = (double)g[i] - mean;
+        ss += dv * dv;
+    }
+    double sigma = sqrt(ss / (double)n);
+    float limit = (float)((double)c * sigma);
+    for (size_t i = 0; i < n; ++i) {
+        float v = g[i];
+        if (v > limit) v = limit;
+        if (v < -limit) v = -limit;
+        out[i] = v;
+    }
+}
+
 /* Quantize a whole gradient bucket by bucket (bucket-based quantization, Section 5; the last
  * bucket is shorter when bucket_size does not divide n).  Writes (n/bucket_size rounded up)
  * * 2^bits level floats, one unpacked code per element, and, when thresholds != NULL and the
  * scheme is BinGrad-b, one b0 per bucket.  Returns 0, or -1 on bad arguments. */
 int ogq_oracle_quantize_codes(const float* g, size_t n, uint32_t bucket_size, uint32_t bits,
                               uint32_t scheme, uint32_t level_iters, uint64_t seed,
-                              uint64_t index_offset, float* levels, uint8_t* codes,
+                              uint64_t index_offset, float clip_factor, float* levels, uint8_t* codes,
                               float* thresholds)
 {
     if (!g || !levels || !codes || bucket_size == 0 || bits == 0 || bits > 8) return -1;
@@ -235,7 +264,8 @@ int ogq_oracle_quantize_codes(const float* g, size_t n, uint32_t bucket_size, ui
     for (long long b = 0; b < num_buckets; ++b) {
         size_t begin = (size_t)b * bucket_size;
         size_t len = n - begin < bucket_size ? n - begin : bucket_size;
-        const float* gb = g + begin;
+        float* gb = (float*)malloc(len * sizeof(float));
+        ogq_oracle_clip_bucket(g + begin, len, clip_factor, gb);
         float* lv = levels + (size_t)b * s;
         if (scheme == ORACLE_BINGRAD_B) {
             float b0;
@@ -249,6 +279,7 @@ int ogq_oracle_quantize_codes(const float* g, size_t n, uint32_t bucket_size, ui
                 codes[begin + i] = (uint8_t)ogq_oracle_orq_encode_element(gb[i], lv, s, u);
             }
         }
+        free(gb);
     }
     return 0;
 }
@@ -256,12 +287,12 @@ int ogq_oracle_quantize_codes(const float* g, size_t n, uint32_t bucket_size, ui
 /* Quantize + pack: what one worker sends (Algorithm 2, "compute levels / quantize / encode"). */
 int ogq_oracle_quantize(const float* g, size_t n, uint32_t bucket_size, uint32_t bits,
                         uint32_t scheme, uint32_t level_iters, uint64_t seed,
-                        uint64_t index_offset, float* levels, uint64_t* words)
+                        uint64_t index_offset, float clip_factor, float* levels, uint64_t* words)
 {
     if (!words) return -1;
     uint8_t* codes = (uint8_t*)malloc(n ? n : 1);
     int rc = ogq_oracle_quantize_codes(g, n, bucket_size, bits, scheme, level_iters, seed,
-                                       index_offset, levels, codes, NULL);
+                                       index_offset, clip_factor, levels, codes, NULL);
     if (rc == 0) ogq_oracle_pack(codes, n, bits, words);
     free(codes);
     return rc;

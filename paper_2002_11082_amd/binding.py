@@ -23,6 +23,8 @@ class Params(ctypes.Structure):
         ("level_iters", ctypes.c_uint32),
         ("seed", ctypes.c_uint64),
         ("index_offset", ctypes.c_uint64),
+        ("clip_factor", ctypes.c_float),
+        ("reserved", ctypes.c_uint32),
     ]
 
 
@@ -66,8 +68,8 @@ def lib() -> ctypes.CDLL:
 
 
 def make_params(bucket_size: int, bits: int, scheme: int, level_iters: int = 0, seed: int = 0,
-                index_offset: int = 0) -> Params:
-    return Params(bucket_size, bits, scheme, level_iters, seed, index_offset)
+                index_offset: int = 0, clip_factor: float = 0.0) -> Params:
+    return Params(bucket_size, bits, scheme, level_iters, seed, index_offset, clip_factor, 0)
 
 
 def ogq_strerror(status: int) -> str:

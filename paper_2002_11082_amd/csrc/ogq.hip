@@ -114,6 +114,28 @@ __device__ __forceinline__ float wave_max(float x)
     return fmaxf(fmaxf(readlane_f32(x, 0), readlane_f32(x, 16)), fmaxf(readlane_f32(x, 32), readlane_f32(x, 48)));
 }
 
+// Gradient clipping of a register-resident bucket (Section 5): v <- sign(v) * min(|v|, c * sigma) with
+// sigma^2 the population variance about the bucket mean, both in fp64.  valid(j) tells whether
+// register j of this lane holds a bucket element.
+template <int N, class ValidFn>
+__device__ __forceinline__ void clip_in_registers(float (&v)[N], uint32_t len, float c, ValidFn valid)
+{
+    double part = 0.0;
+#pragma unroll
+    for (int j = 0; j < N; ++j) part += valid(j) ? (double)v[j] : 0.0;
+    const double mean = wave_sum(part) / (double)len;
+    part = 0.0;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const double dv = (double)v[j] - mean;
+        part += valid(j) ? dv * dv : 0.0;
+    }
+    const double sigma = sqrt(wave_sum(part) / (double)len);
+    const float limit = (float)((double)c * sigma);
+#pragma unroll
+    for (int j = 0; j < N; ++j) v[j] = fminf(fmaxf(v[j], -limit), limit);
+}
+
 __device__ __forceinline__ uint32_t uniform_u32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
 
 __device__ __forceinline__ float uniform_f32(float x)
@@ -133,8 +155,8 @@ __device__ __forceinline__ double uniform_f64(double x)
 // BinGrad-b quantize.  Lane l register j holds bucket element 64*j + l, so a ballot over
 // register j is the packed code word j of the bucket.
 // ----------------------------------------------------------------------------------------------
-template <int E, bool FULL>
-__device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint32_t len, uint32_t iters,
+template <int E, bool FULL, bool CLIP>
+__device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint32_t len, uint32_t iters, float clip,
                                                float* __restrict__ levels2, uint64_t* __restrict__ words)
 {
     const uint32_t lane = threadIdx.x & 63u;
@@ -144,6 +166,7 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
         const uint32_t e = 64u * j + lane;
         v[j] = (FULL || e < len) ? __builtin_nontemporal_load(g + e) : 0.0f;  // read once: bypass the caches
     }
+    if constexpr (CLIP) clip_in_registers<E>(v, len, clip, [&](int j) { return FULL || (64u * j + lane < len); });
 
     double part = 0.0;
     float mag = 0.0f;
@@ -220,10 +243,10 @@ constexpr int kBinGradWaves = 2;  // buckets per workgroup
 // At most 4 waves per SIMD and small workgroups: with more, all resident waves load and then
 // compute in lock-step and the tail of a launch that is only ~1.5 waves of workgroups deep is not
 // overlapped.
-template <int E>
+template <int E, bool CLIP>
 __global__ __launch_bounds__(kWave* kBinGradWaves)
     __attribute__((amdgpu_waves_per_eu(E > 32 ? 2 : 4, 4))) void bingrad_quantize_kernel(
-    const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, uint32_t num_buckets,
+    const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, float clip, uint32_t num_buckets,
     float* __restrict__ levels, uint64_t* __restrict__ codes)
 {
     const uint32_t bucket = uniform_u32(blockIdx.x * kBinGradWaves + (threadIdx.x >> 6));
@@ -234,8 +257,8 @@ __global__ __launch_bounds__(kWave* kBinGradWaves)
     const float* g = grad + begin;
     float* lv = levels + (size_t)bucket * 2;
     uint64_t* w = codes + begin / 64;
-    if (len == 64u * E) bingrad_bucket<E, true>(g, len, iters, lv, w);
-    else bingrad_bucket<E, false>(g, len, iters, lv, w);
+    if (len == 64u * E) bingrad_bucket<E, true, CLIP>(g, len, iters, clip, lv, w);
+    else bingrad_bucket<E, false, CLIP>(g, len, iters, clip, lv, w);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -520,10 +543,10 @@ struct OrqShape {
 };
 
 // FULL: the bucket has exactly 256*C elements (no padding, no per-element validity tests).
-template <int C, int BITS, bool FULL>
+template <int C, int BITS, bool FULL, bool CLIP>
 __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B>& lds, const float* __restrict__ g,
-                                           uint32_t len, size_t begin, uint32_t bucket, uint32_t sweeps, uint64_t seed,
-                                           uint64_t index_offset, float* __restrict__ levels,
+                                           uint32_t len, size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
+                                           uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
                                            uint32_t* __restrict__ codes32)
 {
     constexpr int S = 1 << BITS;
@@ -553,22 +576,26 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
             }
     }
 
+    if constexpr (CLIP) {
+        float(&flat)[4 * C] = reinterpret_cast<float(&)[4 * C]>(v);
+        clip_in_registers<4 * C>(flat, len, clip, [&](int j) { return full || (64u * (j & ~3) + 4u * lane + (j & 3) < len); });
+    }
+
     // ---- extremes ------------------------------------------------------------------------------
-    uint32_t key_min = 0xFFFFFFFFu, key_max = 0u, mag_max = 0u;
+    float lane_min = __uint_as_float(0x7F800000u), lane_max = __uint_as_float(0xFF800000u);
 #pragma unroll
     for (int c = 0; c < C; ++c)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const bool valid = full || (256u * c + 4u * lane + k < len);
-            const float x = v[c][k] + 0.0f;  // -0 -> +0
-            const uint32_t key = float_to_key(x);
-            key_min = umin32(key_min, valid ? key : 0xFFFFFFFFu);
-            key_max = umax32(key_max, valid ? key : 0u);
-            mag_max = umax32(mag_max, valid ? (__float_as_uint(x) & 0x7FFFFFFFu) : 0u);
+            lane_min = fminf(lane_min, valid ? v[c][k] : __uint_as_float(0x7F800000u));
+            lane_max = fmaxf(lane_max, valid ? v[c][k] : __uint_as_float(0xFF800000u));
         }
-    key_min = wave_min_u32(key_min);
-    key_max = wave_max_u32(key_max);
-    const uint32_t t_max = wave_max_u32(mag_max) >> SHIFT;
+    const float bucket_min = wave_min(lane_min) + 0.0f;  // -0 -> +0
+    const float bucket_max = wave_max(lane_max) + 0.0f;
+    const uint32_t key_min = float_to_key(bucket_min), key_max = float_to_key(bucket_max);
+    const uint32_t mag_max = umax32(__float_as_uint(bucket_min) & 0x7FFFFFFFu, __float_as_uint(bucket_max) & 0x7FFFFFFFu);
+    const uint32_t t_max = mag_max >> SHIFT;
     const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
 
     if constexpr (S > 2) {
@@ -785,9 +812,9 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     }
 }
 
-template <int C, int BITS>
+template <int C, int BITS, bool CLIP>
 __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
-                                                             uint32_t bucket_size, uint32_t sweeps,
+                                                             uint32_t bucket_size, uint32_t sweeps, float clip,
                                                              uint32_t num_buckets, uint64_t seed,
                                                              uint64_t index_offset, float* __restrict__ levels,
                                                              uint32_t* __restrict__ codes32)
@@ -799,9 +826,9 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
     const size_t rest = n - begin;
     const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
     if (len == (uint32_t)OrqShape<C>::D)
-        orq_bucket<C, BITS, true>(lds, grad + begin, len, begin, bucket, sweeps, seed, index_offset, levels, codes32);
+        orq_bucket<C, BITS, true, CLIP>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
     else
-        orq_bucket<C, BITS, false>(lds, grad + begin, len, begin, bucket, sweeps, seed, index_offset, levels, codes32);
+        orq_bucket<C, BITS, false, CLIP>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -954,6 +981,7 @@ int check_params(const ogq_params_t* p, bool need_scheme)
             return OGQ_ERR_SCHEME;
         }
         if (p->index_offset % 64 != 0) return OGQ_ERR_INDEX_OFFSET;
+        if (!(p->clip_factor >= 0.0f) || !(p->clip_factor <= 3.0e38f)) return OGQ_ERR_CLIP;
     } else if (p->bits < 1 || p->bits > 3) {
         return OGQ_ERR_BITS;
     }
@@ -975,15 +1003,25 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
                     hipStream_t st)
 {
     const uint32_t blocks = (nb + kBinGradWaves - 1) / kBinGradWaves;
-    hipLaunchKernelGGL(bingrad_quantize_kernel<E>, dim3(blocks), dim3(kWave * kBinGradWaves), 0, st, g, n, p->bucket_size,
-                       p->level_iters, nb, lv, static_cast<uint64_t*>(codes));
+    if (p->clip_factor > 0.0f)
+        hipLaunchKernelGGL((bingrad_quantize_kernel<E, true>), dim3(blocks), dim3(kWave * kBinGradWaves), 0, st, g, n,
+                           p->bucket_size, p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
+    else
+        hipLaunchKernelGGL((bingrad_quantize_kernel<E, false>), dim3(blocks), dim3(kWave * kBinGradWaves), 0, st, g, n,
+                           p->bucket_size, p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
 }
 
 template <int C, int BITS>
 void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
-    hipLaunchKernelGGL((orq_quantize_kernel<C, BITS>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
-                       p->level_iters, nb, p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
+    if (p->clip_factor > 0.0f)
+        hipLaunchKernelGGL((orq_quantize_kernel<C, BITS, true>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+                           p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
+                           static_cast<uint32_t*>(codes));
+    else
+        hipLaunchKernelGGL((orq_quantize_kernel<C, BITS, false>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+                           p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
+                           static_cast<uint32_t*>(codes));
 }
 
 template <int C>
@@ -1133,6 +1171,7 @@ const char* ogq_strerror(int status)
         case OGQ_ERR_INDEX_OFFSET: return "index_offset must be a multiple of 64";
         case OGQ_ERR_LAUNCH: return "HIP kernel launch failed";
         case OGQ_ERR_SIZE: return "n is too large for one call";
+        case OGQ_ERR_CLIP: return "clip_factor must be finite and not negative";
         default: return "unknown status";
     }
 }

@@ -37,15 +37,15 @@ def gpu_quantize(g: np.ndarray, params, device="cuda:0"):
 
 
 def check_quantize(g: np.ndarray, bucket_size: int, bits: int, scheme: int, level_iters: int = 0, seed: int = 0,
-                   index_offset: int = 0, buckets=None, tag: str = ""):
+                   index_offset: int = 0, buckets=None, tag: str = "", clip_factor: float = 0.0):
     """Quantize g on the GPU and with the oracle and compare.  `buckets`: optional list of bucket
     indices to check (sampled comparison at full sizes); None = every bucket.
     Returns (device levels, device codes, report dict)."""
     n = g.size
     s = 1 << bits
-    params = ogq.make_params(bucket_size, bits, scheme, level_iters, seed, index_offset)
+    params = ogq.make_params(bucket_size, bits, scheme, level_iters, seed, index_offset, clip_factor)
     print(f"[parity] {tag} n={n} d={bucket_size} bits={bits} scheme={scheme} iters={level_iters} seed={seed} "
-          f"offset={index_offset}", flush=True)
+          f"offset={index_offset} clip={clip_factor}", flush=True)
     lv_gpu, words_gpu, dev = gpu_quantize(g, params)
     nb = (n + bucket_size - 1) // bucket_size
     assert lv_gpu.size == nb * s and words_gpu.size == ((n + 63) // 64) * bits
@@ -57,12 +57,13 @@ def check_quantize(g: np.ndarray, bucket_size: int, bits: int, scheme: int, leve
 
     if buckets is None:
         lv_ref, codes_ref, thr_ref = oracle.quantize_codes(g, bucket_size, bits, scheme, level_iters, seed,
-                                                           index_offset)
+                                                           index_offset, clip_factor)
         sel = np.arange(nb)
         lv_g = lv_gpu.reshape(nb, s)
         lv_r = lv_ref.reshape(nb, s)
         cg, cr = codes_gpu, codes_ref
-        gv = g
+        gv = g if clip_factor == 0 else np.concatenate(
+            [oracle.clip_bucket(g[i:i + bucket_size], clip_factor) for i in range(0, n, bucket_size)])
         thr = np.repeat(thr_ref, bucket_size)[:n]
         lvl_ok_elem = None
     else:
@@ -72,11 +73,11 @@ def check_quantize(g: np.ndarray, bucket_size: int, bits: int, scheme: int, leve
         for i, b in enumerate(sel):
             lo, hi = b * bucket_size, min((b + 1) * bucket_size, n)
             l, c, t = oracle.quantize_codes(g[lo:hi], bucket_size, bits, scheme, level_iters, seed,
-                                            index_offset + lo)
+                                            index_offset + lo, clip_factor)
             lv_r[i] = l
             parts_c.append(c)
             parts_g.append(codes_gpu[lo:hi])
-            parts_v.append(g[lo:hi])
+            parts_v.append(g[lo:hi] if clip_factor == 0 else oracle.clip_bucket(g[lo:hi], clip_factor))
             parts_t.append(np.full(hi - lo, t[0], np.float32))
         lv_g = lv_gpu.reshape(nb, s)[sel]
         cr, cg = np.concatenate(parts_c), np.concatenate(parts_g)

@@ -36,8 +36,9 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_params_struct_layout_matches_the_header():
-    assert ctypes.sizeof(ogq.Params) == 32
+    assert ctypes.sizeof(ogq.Params) == 40
     assert ogq.Params.seed.offset == 16 and ogq.Params.index_offset.offset == 24
+    assert ogq.Params.clip_factor.offset == 32
 
 
 def test_size_queries(lib):
@@ -75,6 +76,8 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert q(A, 100, ogq.make_params(2048, 0, ogq.ORQ), A, A) == -3
     assert q(A, 100, ogq.make_params(2048, 2, 7), A, A) == -4
     assert q(A, 100, ogq.make_params(2048, 2, ogq.ORQ, index_offset=5), A, A) == -7
+    assert q(A, 100, ogq.make_params(2048, 2, ogq.ORQ, clip_factor=-1.0), A, A) == -10
+    assert q(A, 100, ogq.make_params(2048, 2, ogq.ORQ, clip_factor=float('nan')), A, A) == -10
     d = ogq.ogq_dequantize_average_raw
     assert d([A], [A], 0, ok, A) == 0
     assert d([], [], 100, ok, A) == -5
@@ -83,7 +86,7 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert d([A], [A], 100, ok, 0) == -1
     assert d([A + 8], [A], 100, ok, A) == -6
     assert d([A], [A], 100, ogq.make_params(2048, 5, ogq.ORQ), A) == -3
-    for code in range(-9, 1):
+    for code in range(-10, 1):
         assert ogq.ogq_strerror(code)
     assert lib.ogq_quantize(A, 100, None, A, A, None) == -1
 

@@ -75,6 +75,18 @@ def test_orq_sweeps_and_offsets():
     assert np.array_equal(words_full[4096 // 64 * 2:], words_shard)
 
 
+@pytest.mark.parametrize("clip", [1.0, 1.7, 2.5])
+def test_clipping_before_quantization(clip):
+    rng = np.random.default_rng(int(clip * 10))
+    for kind in ("normal", "heavy", "shifted", "const", "ints"):
+        for d, n in ((64, 200), (512, 5 * 512 + 77), (2048, 3 * 2048), (4096, 4096 + 5)):
+            g = _rng_bucket(rng, n, kind)
+            parity.check_quantize(g, d, 1, ogq.BINGRAD_B, 1, clip_factor=clip, tag=f"clip{clip}-bingrad-{kind}-d{d}")
+            for bits in (2, 3):
+                parity.check_quantize(g, d, bits, ogq.ORQ, 2, seed=11, clip_factor=clip,
+                                      tag=f"clip{clip}-orq{bits}-{kind}-d{d}")
+
+
 def test_empty_input_is_a_noop():
     p = ogq.make_params(512, 1, ogq.BINGRAD_B)
     x = torch.zeros(4, device=DEV)
