@@ -54,7 +54,11 @@ typedef enum {
     /* ORQ: s = 2^bits levels placed by the optimal condition of Theorem 1 (greedy recursion of
      * Algorithm 1 followed by re-solve sweeps), unbiased random rounding (Section 3.1).
      * bits in 1..3. */
-    OGQ_ORQ = 1
+    OGQ_ORQ = 1,
+    /* ORQ with the paper's level counts s = 2^K + 1 (Algorithm 1's initialisation: 3, 5 or 9 levels);
+     * bits = K + 1 in 2..4 is the width of a level index.  With level_iters = 0 the levels are those of
+     * Algorithm 1 as printed.  Encoding and packing as for OGQ_ORQ. */
+    OGQ_ORQ_PAPER = 3
 } ogq_scheme_t;
 
 #define OGQ_MAX_WORKERS 64u
@@ -62,7 +66,7 @@ typedef enum {
 
 typedef struct {
     uint32_t bucket_size;  /* elements per bucket: a multiple of 64 in [64, 4096] */
-    uint32_t bits;         /* code width; s = 1 << bits levels per bucket */
+    uint32_t bits;         /* width of a level index; levels per bucket: see ogq_levels_per_bucket */
     uint32_t scheme;       /* ogq_scheme_t */
     /* BINGRAD_B: number of threshold updates b0 <- (b_{-1} + b_1)/2 after the start b0 = bucket
      * mean (0 = the paper's shortcut).  ORQ: number of sweeps that re-solve every interior level
@@ -82,10 +86,12 @@ typedef struct {
 } ogq_params_t;
 
 /* Sizes of the outputs of ogq_quantize for a gradient of n elements (pure host arithmetic).
- *   num_buckets  = ceil(n / bucket_size)
- *   levels_count = num_buckets << bits            fp32 values
- *   codes_bytes  = ceil(n / 64) * bits * 8        bytes
- * They return 0 when params is NULL or bucket_size is 0. */
+ *   levels_per_bucket = 2 (BINGRAD_B), 2^bits (ORQ), 2^(bits-1) + 1 (ORQ_PAPER)
+ *   num_buckets       = ceil(n / bucket_size)
+ *   levels_count      = num_buckets * levels_per_bucket    fp32 values
+ *   codes_bytes       = ceil(n / 64) * bits * 8            bytes
+ * They return 0 when params is NULL, bucket_size is 0 or scheme / bits do not go together. */
+size_t ogq_levels_per_bucket(const ogq_params_t* params);
 size_t ogq_num_buckets(size_t n, const ogq_params_t* params);
 size_t ogq_levels_count(size_t n, const ogq_params_t* params);
 size_t ogq_codes_bytes(size_t n, const ogq_params_t* params);
@@ -95,7 +101,7 @@ size_t ogq_codes_bytes(size_t n, const ogq_params_t* params);
  *
  *   d_grad    in   n fp32, device, read once.
  *   d_levels  out  levels_count fp32, device; bucket b owns entries
- *                  [b << bits, (b+1) << bits), non-decreasing.
+ *                  [b * levels_per_bucket, (b+1) * levels_per_bucket), non-decreasing.
  *                  BINGRAD_B: {b_{-1}, b_1} = means of the elements below / not below the
  *                  threshold b0 (b0 = fp32 bucket mean, then level_iters midpoint updates);
  *                  a constant bucket gives two equal levels.
@@ -116,15 +122,15 @@ int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params,
                  float* d_levels, void* d_codes, void* hip_stream);
 
 /* Decode num_workers packed streams and average them (server step of Algorithm 2):
- *   d_out[i] = (1/num_workers) * sum_w d_levels[w][(i / bucket_size) << bits | index_w(i)]
+ *   d_out[i] = (1/num_workers) * sum_w d_levels[w][(i / bucket_size) * levels_per_bucket + index_w(i)]
  * accumulated in fp64 and rounded once to fp32.
  *
  *   d_codes   in   HOST array of num_workers DEVICE pointers, each to codes_bytes bytes as
  *                  written by ogq_quantize.
  *   d_levels  in   HOST array of num_workers DEVICE pointers, each to levels_count fp32.
  *   d_out     out  n fp32, device; must not overlap any input.
- * All workers share n and params (bucket_size, bits); their level tables differ.  Only
- * bucket_size and bits of params are read.  The host arrays are copied during the call and may
+ * All workers share n and params; their level tables differ.  Only bucket_size, bits and scheme of
+ * params are read.  The host arrays are copied during the call and may
  * be reused as soon as it returns. */
 int ogq_dequantize_average(const void* const* d_codes, const float* const* d_levels,
                            uint32_t num_workers, size_t n, const ogq_params_t* params,

@@ -19,6 +19,7 @@ _LIB = os.path.join(_HERE, "libogq_oracle.so")
 
 BINGRAD_B = 0
 ORQ = 1
+ORQ_PAPER = 3
 
 
 def build(force: bool = False) -> str:
@@ -62,7 +63,9 @@ def lib() -> ctypes.CDLL:
         L.ogq_oracle_quantize_codes.restype = ctypes.c_int
         L.ogq_oracle_quantize.argtypes = [vp, sz, u32, u32, u32, u32, u64, u64, ctypes.c_float, vp, vp]
         L.ogq_oracle_quantize.restype = ctypes.c_int
-        L.ogq_oracle_dequantize_average.argtypes = [vp, vp, u32, sz, u32, u32, vp]
+        L.ogq_oracle_dequantize_average.argtypes = [vp, vp, u32, sz, u32, u32, u32, vp]
+        L.ogq_oracle_levels_per_bucket.argtypes = [u32, u32]
+        L.ogq_oracle_levels_per_bucket.restype = u32
         L.ogq_oracle_dequantize_average.restype = ctypes.c_int
         L.ogq_oracle_threads.argtypes = []
         L.ogq_oracle_threads.restype = ctypes.c_int
@@ -134,6 +137,13 @@ def unpack(words, n: int, bits: int) -> np.ndarray:
     return codes
 
 
+def levels_per_bucket(scheme: int, bits: int) -> int:
+    s = int(lib().ogq_oracle_levels_per_bucket(scheme, bits))
+    if s == 0:
+        raise ValueError(f"bad scheme/bits combination ({scheme}, {bits})")
+    return s
+
+
 def clip_bucket(g, c: float) -> np.ndarray:
     g = _f32(g)
     out = np.zeros_like(g)
@@ -143,11 +153,11 @@ def clip_bucket(g, c: float) -> np.ndarray:
 
 def quantize_codes(g, bucket_size: int, bits: int, scheme: int, level_iters: int = 0, seed: int = 0,
                    index_offset: int = 0, clip_factor: float = 0.0):
-    """Returns (levels [num_buckets*2^bits] f32, codes [n] u8, thresholds [num_buckets] f32)."""
+    """Returns (levels [num_buckets*levels_per_bucket] f32, codes [n] u8, thresholds [num_buckets] f32)."""
     g = _f32(g)
     n = g.size
     nb = (n + bucket_size - 1) // bucket_size
-    levels = np.zeros(nb << bits, dtype=np.float32)
+    levels = np.zeros(nb * levels_per_bucket(scheme, bits), dtype=np.float32)
     codes = np.zeros(n, dtype=np.uint8)
     thresholds = np.zeros(nb, dtype=np.float32)
     rc = lib().ogq_oracle_quantize_codes(_ptr(g), n, bucket_size, bits, scheme, level_iters, seed,
@@ -163,7 +173,7 @@ def quantize(g, bucket_size: int, bits: int, scheme: int, level_iters: int = 0, 
     g = _f32(g)
     n = g.size
     nb = (n + bucket_size - 1) // bucket_size
-    levels = np.zeros(nb << bits, dtype=np.float32)
+    levels = np.zeros(nb * levels_per_bucket(scheme, bits), dtype=np.float32)
     words = np.zeros(((n + 63) // 64) * bits, dtype=np.uint64)
     rc = lib().ogq_oracle_quantize(_ptr(g), n, bucket_size, bits, scheme, level_iters, seed, index_offset,
                                    float(clip_factor), _ptr(levels), _ptr(words))
@@ -172,8 +182,10 @@ def quantize(g, bucket_size: int, bits: int, scheme: int, level_iters: int = 0, 
     return levels, words
 
 
-def dequantize_average(words_list, levels_list, n: int, bucket_size: int, bits: int) -> np.ndarray:
+def dequantize_average(words_list, levels_list, n: int, bucket_size: int, bits: int, stride: int = 0) -> np.ndarray:
+    """stride = levels per bucket (default 2^bits)."""
     W = len(words_list)
+    stride = stride or (1 << bits)
     assert W == len(levels_list) and W > 0
     ws = [np.ascontiguousarray(w, dtype=np.uint64) for w in words_list]
     ls = [_f32(l) for l in levels_list]
@@ -181,7 +193,7 @@ def dequantize_average(words_list, levels_list, n: int, bucket_size: int, bits: 
     lp = (ctypes.c_void_p * W)(*[_ptr(l) for l in ls])
     out = np.zeros(n, dtype=np.float32)
     rc = lib().ogq_oracle_dequantize_average(ctypes.addressof(wp), ctypes.addressof(lp), W, n, bucket_size,
-                                             bits, _ptr(out))
+                                             bits, stride, _ptr(out))
     if rc != 0:
         raise ValueError(f"oracle dequantize_average rejected its arguments (rc={rc})")
     return out

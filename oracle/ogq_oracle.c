@@ -32,7 +32,17 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_BINGRAD_B = 0, ORACLE_ORQ = 1 };
+enum { ORACLE_BINGRAD_B = 0, ORACLE_ORQ = 1, ORACLE_ORQ_PAPER = 3 };
+
+/* Levels per bucket: BinGrad-b 2; ORQ 2^bits; ORQ with the paper's level counts s = 2^K + 1
+ * (Algorithm 1: 3, 5, 9 levels), whose indices need bits = K + 1 bits.  0 = bad combination. */
+uint32_t ogq_oracle_levels_per_bucket(uint32_t scheme, uint32_t bits)
+{
+    if (scheme == ORACLE_BINGRAD_B) return bits == 1 ? 2u : 0u;
+    if (scheme == ORACLE_ORQ) return (bits >= 1 && bits <= 8) ? 1u << bits : 0u;
+    if (scheme == ORACLE_ORQ_PAPER) return (bits >= 2 && bits <= 8) ? (1u << (bits - 1)) + 1u : 0u;
+    return 0u;
+}
 
 /* ------------------------------------------------------------------------------------------
  * Counter-based random numbers: Philox4x32 with 10 rounds, as published by Salmon, Moraes,
@@ -254,9 +264,8 @@ int ogq_oracle_quantize_codes(const float* g, size_t n, uint32_t bucket_size, ui
                               float* thresholds)
 {
     if (!g || !levels || !codes || bucket_size == 0 || bits == 0 || bits > 8) return -1;
-    if (scheme == ORACLE_BINGRAD_B && bits != 1) return -1;
-    if (scheme != ORACLE_BINGRAD_B && scheme != ORACLE_ORQ) return -1;
-    uint32_t s = 1u << bits;
+    uint32_t s = ogq_oracle_levels_per_bucket(scheme, bits);
+    if (s == 0) return -1;
     long long num_buckets = (long long)((n + bucket_size - 1) / bucket_size);
 #ifdef _OPENMP
 #pragma omp parallel for schedule(static)
@@ -302,11 +311,12 @@ int ogq_oracle_quantize(const float* g, size_t n, uint32_t bucket_size, uint32_t
  * average: out_i = (1/W) * sum_w levels_w[bucket(i)][code_{w,i}], summed in double. */
 int ogq_oracle_dequantize_average(const uint64_t* const* words, const float* const* levels,
                                   uint32_t num_workers, size_t n, uint32_t bucket_size,
-                                  uint32_t bits, float* out)
+                                  uint32_t bits, uint32_t levels_per_bucket, float* out)
 {
     if (!words || !levels || !out || num_workers == 0 || bucket_size == 0 || bits == 0 || bits > 8)
         return -1;
-    uint32_t s = 1u << bits;
+    if (levels_per_bucket == 0 || levels_per_bucket > (1u << bits)) return -1;
+    uint32_t s = levels_per_bucket;
     long long nn = (long long)n;
 #ifdef _OPENMP
 #pragma omp parallel for schedule(static)

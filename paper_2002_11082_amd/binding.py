@@ -10,6 +10,7 @@ LIB_PATH = os.path.join(_PKG, "libogq.so")
 
 BINGRAD_B = 0
 ORQ = 1
+ORQ_PAPER = 3
 MAX_WORKERS = 64
 PROBE_SINK_FLOATS = 8192
 
@@ -47,6 +48,8 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH)
         sz, vp, u32 = ctypes.c_size_t, ctypes.c_void_p, ctypes.c_uint32
         pp = ctypes.POINTER(Params)
+        L.ogq_levels_per_bucket.argtypes = [pp]
+        L.ogq_levels_per_bucket.restype = sz
         for name in ("ogq_num_buckets", "ogq_levels_count", "ogq_codes_bytes"):
             f = getattr(L, name)
             f.argtypes = [sz, pp]
@@ -79,6 +82,10 @@ def ogq_strerror(status: int) -> str:
 def _check(status: int) -> None:
     if status != 0:
         raise OgqError(status, ogq_strerror(status))
+
+
+def ogq_levels_per_bucket(params: Params) -> int:
+    return lib().ogq_levels_per_bucket(ctypes.byref(params))
 
 
 def ogq_num_buckets(n: int, params: Params) -> int:

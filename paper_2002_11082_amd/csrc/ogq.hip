@@ -311,9 +311,9 @@ __device__ __forceinline__ float key_to_float(uint32_t k)
 
 // Order of the greedy solves (Algorithm 1): the level in the middle of [l, r] is solved from the
 // two outer levels, then both halves are treated the same way; the middle index is rounded down
-// when s is not of the form 2^K + 1.  Each step is packed as 3 bits of k, l, r.
+// when s is not of the form 2^K + 1.  Each step is packed as 4 bits of k, l, r; five steps per word.
 struct GreedyOrder {
-    uint64_t packed;
+    uint64_t packed[2];
     int count;
 };
 
@@ -321,7 +321,7 @@ constexpr void greedy_visit(GreedyOrder& o, int l, int r)
 {
     if (r - l < 2) return;
     const int mid = (l + r) / 2;
-    o.packed |= (uint64_t)(mid | (l << 3) | (r << 6)) << (9 * o.count);
+    o.packed[o.count / 5] |= (uint64_t)(mid | (l << 4) | (r << 8)) << (12 * (o.count % 5));
     ++o.count;
     greedy_visit(o, l, mid);
     greedy_visit(o, mid, r);
@@ -330,7 +330,7 @@ constexpr void greedy_visit(GreedyOrder& o, int l, int r)
 template <int S>
 constexpr GreedyOrder greedy_order()
 {
-    GreedyOrder o{0, 0};
+    GreedyOrder o{{0, 0}, 0};
     greedy_visit(o, 0, S - 1);
     return o;
 }
@@ -345,12 +345,12 @@ struct OrqLds {
     double block_prefix[64];    // fp64 sum of all positions before block l (block = D/64 positions)
     // per level k: value; #{v < value}; #{v <= value}; sum{v < value}; sum{v <= value}; the rank it
     // was picked at (0 = not picked by rank)
-    double lvl_sum_lt[8];
-    double lvl_sum_le[8];
-    float lvl_value[8];
-    uint32_t lvl_count_lt[8];
-    uint32_t lvl_count_le[8];
-    uint32_t lvl_rank[8];
+    double lvl_sum_lt[10];
+    double lvl_sum_le[10];
+    float lvl_value[10];
+    uint32_t lvl_count_lt[10];
+    uint32_t lvl_count_le[10];
+    uint32_t lvl_rank[10];
 };
 
 __device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 5); }
@@ -543,13 +543,14 @@ struct OrqShape {
 };
 
 // FULL: the bucket has exactly 256*C elements (no padding, no per-element validity tests).
-template <int C, int BITS, bool FULL, bool CLIP>
+// S levels per bucket, BITS bits per level index (S = 2^BITS, or 2^(BITS-1) + 1 for the paper's counts).
+template <int C, int S, int BITS, bool FULL, bool CLIP>
 __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B>& lds, const float* __restrict__ g,
                                            uint32_t len, size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
                                            uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
                                            uint32_t* __restrict__ codes32)
 {
-    constexpr int S = 1 << BITS;
+    static_assert(S >= 2 && S <= 9 && S <= (1 << BITS), "level count does not fit the index width");
     constexpr int D = OrqShape<C>::D;
     constexpr int B = OrqShape<C>::B;
     constexpr int PER = B / 64;   // bins per lane in the prefix step
@@ -697,8 +698,9 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         for (uint32_t step = 0; step < steps; ++step) {
             uint32_t k, l, r;
             if (step < (uint32_t)order.count) {
-                const uint32_t e = (uint32_t)(order.packed >> (9 * step));
-                k = e & 7u; l = (e >> 3) & 7u; r = (e >> 6) & 7u;
+                const uint32_t e = step < 5u ? (uint32_t)(order.packed[0] >> (12 * step))
+                                             : (uint32_t)(order.packed[1] >> (12 * (step - 5u)));
+                k = e & 15u; l = (e >> 4) & 15u; r = (e >> 8) & 15u;
             } else {
                 k = 1u + (step - order.count) % (S - 2);
                 l = k - 1u; r = k + 1u;
@@ -812,7 +814,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     }
 }
 
-template <int C, int BITS, bool CLIP>
+template <int C, int S, int BITS, bool CLIP>
 __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
                                                              uint32_t bucket_size, uint32_t sweeps, float clip,
                                                              uint32_t num_buckets, uint64_t seed,
@@ -826,9 +828,9 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
     const size_t rest = n - begin;
     const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
     if (len == (uint32_t)OrqShape<C>::D)
-        orq_bucket<C, BITS, true, CLIP>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+        orq_bucket<C, S, BITS, true, CLIP>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
     else
-        orq_bucket<C, BITS, false, CLIP>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+        orq_bucket<C, S, BITS, false, CLIP>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -843,26 +845,33 @@ struct WorkerPtrs {
 
 constexpr int kSpanWords = 16;  // one wavefront decodes 16 packed word groups = 1024 elements
 
+// Level selected by the packed words of one 64-element group: the words are the lane masks of the
+// selects.  S = 2^BITS levels: a full binary tree; S = 2^(BITS-1) + 1 levels (the paper's counts):
+// the top bit alone means the last level.
 template <int BITS>
-__device__ __forceinline__ float select_level(const uint64_t* __restrict__ w, const float (&lv)[1 << BITS])
+__device__ __forceinline__ float select_tree(const bool (&bit)[4], const float* lv)
 {
-    bool bit[BITS];
+    if constexpr (BITS == 0) {
+        return lv[0];
+    } else {
+        const float lo = select_tree<BITS - 1>(bit, lv);
+        const float hi = select_tree<BITS - 1>(bit, lv + (1 << (BITS - 1)));
+        return bit[BITS - 1] ? hi : lo;
+    }
+}
+
+template <int BITS, int S>
+__device__ __forceinline__ float select_level(const uint64_t* __restrict__ w, const float (&lv)[S])
+{
+    bool bit[4] = {false, false, false, false};
 #pragma unroll
     for (int p = 0; p < BITS; ++p) bit[p] = __builtin_amdgcn_inverse_ballot_w64(w[p]);
-    if constexpr (BITS == 1) {
-        return bit[0] ? lv[1] : lv[0];
-    } else if constexpr (BITS == 2) {
-        const float a = bit[0] ? lv[1] : lv[0];
-        const float b = bit[0] ? lv[3] : lv[2];
-        return bit[1] ? b : a;
+    if constexpr (S == (1 << BITS)) {
+        return select_tree<BITS>(bit, lv);
     } else {
-        const float a = bit[0] ? lv[1] : lv[0];
-        const float b = bit[0] ? lv[3] : lv[2];
-        const float c = bit[0] ? lv[5] : lv[4];
-        const float d = bit[0] ? lv[7] : lv[6];
-        const float ab = bit[1] ? b : a;
-        const float cd = bit[1] ? d : c;
-        return bit[2] ? cd : ab;
+        static_assert(S == (1 << (BITS - 1)) + 1, "level count");
+        const float low = select_tree<BITS - 1>(bit, lv);
+        return bit[BITS - 1] ? lv[S - 1] : low;
     }
 }
 
@@ -880,12 +889,11 @@ __device__ __forceinline__ void load_levels(const float* __restrict__ table, flo
 
 // ONE_BUCKET: the 16 word groups of a span lie in one bucket (bucket_size is a multiple of 1024),
 // so each worker's level table is fetched once per span; otherwise once per word group.
-template <int BITS, bool ONE_BUCKET>
+template <int BITS, int S, bool ONE_BUCKET>
 __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs ptrs, uint32_t num_workers, size_t n,
                                                                     uint32_t words_per_bucket, uint32_t total_words,
                                                                     double inv_workers, float* __restrict__ out)
 {
-    constexpr int S = 1 << BITS;
     const uint32_t span = blockIdx.x * kWavesPerBlock + uniform_u32(threadIdx.x >> 6);
     const uint32_t word0 = span * kSpanWords;
     if (word0 >= total_words) return;
@@ -907,11 +915,11 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
             load_levels<S>(table + (size_t)(word0 / words_per_bucket) * S, lv);
             if (whole) {
 #pragma unroll
-                for (int j = 0; j < kSpanWords; ++j) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+                for (int j = 0; j < kSpanWords; ++j) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
             } else {
 #pragma unroll
                 for (int j = 0; j < kSpanWords; ++j)
-                    if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+                    if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
             }
         } else {
 #pragma unroll
@@ -919,7 +927,7 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
                 if ((uint32_t)j < n_words) {
                     float lv[S];
                     load_levels<S>(table + (size_t)((word0 + j) / words_per_bucket) * S, lv);
-                    acc[j] += (double)select_level<BITS>(cw + j * BITS, lv);
+                    acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
                 }
         }
     }
@@ -965,25 +973,27 @@ __global__ __launch_bounds__(kBlock) void probe_copy_kernel(const float4* __rest
 // ----------------------------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------------------------
+// Levels per bucket, 0 for a scheme / bits combination that does not exist.
+uint32_t levels_per_bucket(uint32_t scheme, uint32_t bits)
+{
+    if (scheme == OGQ_BINGRAD_B) return bits == 1 ? 2u : 0u;
+    if (scheme == OGQ_ORQ) return (bits >= 1 && bits <= 3) ? 1u << bits : 0u;
+    if (scheme == OGQ_ORQ_PAPER) return (bits >= 2 && bits <= 4) ? (1u << (bits - 1)) + 1u : 0u;
+    return 0u;
+}
+
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-int check_params(const ogq_params_t* p, bool need_scheme)
+int check_params(const ogq_params_t* p, bool quantize)
 {
     if (!p) return OGQ_ERR_NULL_POINTER;
     if (p->bucket_size == 0 || p->bucket_size % 64 != 0 || p->bucket_size > OGQ_MAX_BUCKET_SIZE)
         return OGQ_ERR_BUCKET_SIZE;
-    if (need_scheme) {
-        if (p->scheme == OGQ_BINGRAD_B) {
-            if (p->bits != 1) return OGQ_ERR_BITS;
-        } else if (p->scheme == OGQ_ORQ) {
-            if (p->bits < 1 || p->bits > 3) return OGQ_ERR_BITS;
-        } else {
-            return OGQ_ERR_SCHEME;
-        }
+    if (p->scheme != OGQ_BINGRAD_B && p->scheme != OGQ_ORQ && p->scheme != OGQ_ORQ_PAPER) return OGQ_ERR_SCHEME;
+    if (levels_per_bucket(p->scheme, p->bits) == 0) return OGQ_ERR_BITS;
+    if (quantize) {
         if (p->index_offset % 64 != 0) return OGQ_ERR_INDEX_OFFSET;
         if (!(p->clip_factor >= 0.0f) || !(p->clip_factor <= 3.0e38f)) return OGQ_ERR_CLIP;
-    } else if (p->bits < 1 || p->bits > 3) {
-        return OGQ_ERR_BITS;
     }
     return OGQ_OK;
 }
@@ -1011,27 +1021,35 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
                            p->bucket_size, p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
 }
 
-template <int C, int BITS>
+template <int C, int S, int BITS>
 void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
     if (p->clip_factor > 0.0f)
-        hipLaunchKernelGGL((orq_quantize_kernel<C, BITS, true>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, true>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
                            p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
                            static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((orq_quantize_kernel<C, BITS, false>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, false>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
                            p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
                            static_cast<uint32_t*>(codes));
 }
 
 template <int C>
-void launch_orq_bits(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
-                     hipStream_t st)
+void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                       hipStream_t st)
 {
-    switch (p->bits) {
-        case 1: launch_orq<C, 1>(g, n, p, nb, lv, codes, st); break;
-        case 2: launch_orq<C, 2>(g, n, p, nb, lv, codes, st); break;
-        default: launch_orq<C, 3>(g, n, p, nb, lv, codes, st); break;
+    if (p->scheme == OGQ_ORQ) {
+        switch (p->bits) {
+            case 1: launch_orq<C, 2, 1>(g, n, p, nb, lv, codes, st); break;
+            case 2: launch_orq<C, 4, 2>(g, n, p, nb, lv, codes, st); break;
+            default: launch_orq<C, 8, 3>(g, n, p, nb, lv, codes, st); break;
+        }
+    } else {  // OGQ_ORQ_PAPER: 2^(bits-1) + 1 levels
+        switch (p->bits) {
+            case 2: launch_orq<C, 3, 2>(g, n, p, nb, lv, codes, st); break;
+            case 3: launch_orq<C, 5, 3>(g, n, p, nb, lv, codes, st); break;
+            default: launch_orq<C, 9, 4>(g, n, p, nb, lv, codes, st); break;
+        }
     }
 }
 
@@ -1045,15 +1063,17 @@ size_t ogq_num_buckets(size_t n, const ogq_params_t* p)
     return n / p->bucket_size + (n % p->bucket_size != 0);
 }
 
+size_t ogq_levels_per_bucket(const ogq_params_t* p) { return p ? levels_per_bucket(p->scheme, p->bits) : 0; }
+
 size_t ogq_levels_count(size_t n, const ogq_params_t* p)
 {
-    if (!p || p->bits > 31) return 0;
-    return ogq_num_buckets(n, p) << p->bits;
+    if (!p) return 0;
+    return ogq_num_buckets(n, p) * levels_per_bucket(p->scheme, p->bits);
 }
 
 size_t ogq_codes_bytes(size_t n, const ogq_params_t* p)
 {
-    if (!p || p->bucket_size == 0) return 0;
+    if (!p || p->bucket_size == 0 || levels_per_bucket(p->scheme, p->bits) == 0) return 0;
     return (n / 64 + (n % 64 != 0)) * p->bits * 8;
 }
 
@@ -1081,11 +1101,11 @@ int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params, floa
         else launch_bingrad<64>(d_grad, n, params, nb, d_levels, d_codes, st);
     } else {
         const uint32_t chunks = (d + 255) / 256;
-        if (chunks <= 1) launch_orq_bits<1>(d_grad, n, params, nb, d_levels, d_codes, st);
-        else if (chunks <= 2) launch_orq_bits<2>(d_grad, n, params, nb, d_levels, d_codes, st);
-        else if (chunks <= 4) launch_orq_bits<4>(d_grad, n, params, nb, d_levels, d_codes, st);
-        else if (chunks <= 8) launch_orq_bits<8>(d_grad, n, params, nb, d_levels, d_codes, st);
-        else launch_orq_bits<16>(d_grad, n, params, nb, d_levels, d_codes, st);
+        if (chunks <= 1) launch_orq_levels<1>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 2) launch_orq_levels<2>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 4) launch_orq_levels<4>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 8) launch_orq_levels<8>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else launch_orq_levels<16>(d_grad, n, params, nb, d_levels, d_codes, st);
     }
     return finish_launch();
 }
@@ -1120,19 +1140,22 @@ int ogq_dequantize_average(const void* const* d_codes, const float* const* d_lev
     const double inv = 1.0 / (double)num_workers;
     const uint32_t wpb = d / 64;
     const bool one_bucket = d % (kSpanWords * 64) == 0;
-#define OGQ_LAUNCH_DEQUANT(BITS)                                                                                   \
-    do {                                                                                                           \
-        if (one_bucket)                                                                                            \
-            hipLaunchKernelGGL((dequantize_average_kernel<BITS, true>), grid, block, 0, st, ptrs, num_workers, n,  \
-                               wpb, total_words, inv, d_out);                                                      \
-        else                                                                                                       \
-            hipLaunchKernelGGL((dequantize_average_kernel<BITS, false>), grid, block, 0, st, ptrs, num_workers, n, \
-                               wpb, total_words, inv, d_out);                                                      \
+#define OGQ_LAUNCH_DEQUANT(BITS, S)                                                                                   \
+    do {                                                                                                              \
+        if (one_bucket)                                                                                               \
+            hipLaunchKernelGGL((dequantize_average_kernel<BITS, S, true>), grid, block, 0, st, ptrs, num_workers, n,  \
+                               wpb, total_words, inv, d_out);                                                         \
+        else                                                                                                          \
+            hipLaunchKernelGGL((dequantize_average_kernel<BITS, S, false>), grid, block, 0, st, ptrs, num_workers, n, \
+                               wpb, total_words, inv, d_out);                                                         \
     } while (0)
-    switch (params->bits) {
-        case 1: OGQ_LAUNCH_DEQUANT(1); break;
-        case 2: OGQ_LAUNCH_DEQUANT(2); break;
-        default: OGQ_LAUNCH_DEQUANT(3); break;
+    switch (levels_per_bucket(params->scheme, params->bits)) {
+        case 2: OGQ_LAUNCH_DEQUANT(1, 2); break;
+        case 4: OGQ_LAUNCH_DEQUANT(2, 4); break;
+        case 8: OGQ_LAUNCH_DEQUANT(3, 8); break;
+        case 3: OGQ_LAUNCH_DEQUANT(2, 3); break;
+        case 5: OGQ_LAUNCH_DEQUANT(3, 5); break;
+        default: OGQ_LAUNCH_DEQUANT(4, 9); break;
     }
 #undef OGQ_LAUNCH_DEQUANT
     return finish_launch();
@@ -1164,7 +1187,7 @@ const char* ogq_strerror(int status)
         case OGQ_OK: return "ok";
         case OGQ_ERR_NULL_POINTER: return "a required pointer is NULL";
         case OGQ_ERR_BUCKET_SIZE: return "bucket_size must be a multiple of 64 in [64, 4096]";
-        case OGQ_ERR_BITS: return "bits not supported by the scheme (BinGrad-b: 1, ORQ: 1..3)";
+        case OGQ_ERR_BITS: return "bits not supported by the scheme (BinGrad-b: 1, ORQ: 1..3, ORQ_PAPER: 2..4)";
         case OGQ_ERR_SCHEME: return "unknown scheme";
         case OGQ_ERR_NUM_WORKERS: return "num_workers must be in [1, 64]";
         case OGQ_ERR_ALIGNMENT: return "device pointers must be 16-byte aligned";

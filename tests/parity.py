@@ -42,8 +42,9 @@ def check_quantize(g: np.ndarray, bucket_size: int, bits: int, scheme: int, leve
     indices to check (sampled comparison at full sizes); None = every bucket.
     Returns (device levels, device codes, report dict)."""
     n = g.size
-    s = 1 << bits
     params = ogq.make_params(bucket_size, bits, scheme, level_iters, seed, index_offset, clip_factor)
+    s = ogq.ogq_levels_per_bucket(params)
+    assert s == oracle.levels_per_bucket(scheme, bits)
     print(f"[parity] {tag} n={n} d={bucket_size} bits={bits} scheme={scheme} iters={level_iters} seed={seed} "
           f"offset={index_offset} clip={clip_factor}", flush=True)
     lv_gpu, words_gpu, dev = gpu_quantize(g, params)
@@ -107,11 +108,11 @@ def check_quantize(g: np.ndarray, bucket_size: int, bits: int, scheme: int, leve
     return dev[0], dev[1], report
 
 
-def term_scale(levels_list, codes_list, n, bucket_size, bits):
+def term_scale(levels_list, codes_list, n, bucket_size, bits, stride=0):
     """mean over workers of |decoded term| per element (denominator of the averaging tolerance)."""
     acc = np.zeros(n, np.float64)
     for lv, w in zip(levels_list, codes_list):
-        acc += np.abs(oracle.dequantize_average([w], [lv], n, bucket_size, bits).astype(np.float64))
+        acc += np.abs(oracle.dequantize_average([w], [lv], n, bucket_size, bits, stride).astype(np.float64))
     return acc / len(levels_list)
 
 

@@ -54,6 +54,15 @@ def test_size_queries(lib):
     assert ogq.ogq_num_buckets(61_100_000, p) == 29_834
     assert ogq.ogq_codes_bytes(65, p) == 2 * 2 * 8
     assert ogq.ogq_num_buckets(0, p) == 0 and ogq.ogq_codes_bytes(0, p) == 0
+    # the paper's level counts 3 / 5 / 9 need 2 / 3 / 4 index bits
+    for bits, s in ((2, 3), (3, 5), (4, 9)):
+        p = ogq.make_params(2048, bits, ogq.ORQ_PAPER)
+        assert ogq.ogq_levels_per_bucket(p) == s
+        assert ogq.ogq_levels_count(25_600_000, p) == 12_500 * s
+        assert ogq.ogq_codes_bytes(25_600_000, p) == 400_000 * bits * 8
+    assert ogq.ogq_levels_per_bucket(ogq.make_params(2048, 1, ogq.ORQ_PAPER)) == 0
+    assert ogq.ogq_levels_per_bucket(ogq.make_params(2048, 3, ogq.ORQ)) == 8
+    assert ogq.ogq_levels_per_bucket(ogq.make_params(2048, 1, ogq.BINGRAD_B)) == 2
     # one bit per element is the paper's x32 compression (level floats not counted)
     p = ogq.make_params(512, 1, ogq.BINGRAD_B)
     assert 4 * 1_048_576 / ogq.ogq_codes_bytes(1_048_576, p) == 32
@@ -75,6 +84,8 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert q(A, 100, ogq.make_params(2048, 4, ogq.ORQ), A, A) == -3
     assert q(A, 100, ogq.make_params(2048, 0, ogq.ORQ), A, A) == -3
     assert q(A, 100, ogq.make_params(2048, 2, 7), A, A) == -4
+    assert q(A, 100, ogq.make_params(2048, 1, ogq.ORQ_PAPER), A, A) == -3
+    assert q(A, 100, ogq.make_params(2048, 5, ogq.ORQ_PAPER), A, A) == -3
     assert q(A, 100, ogq.make_params(2048, 2, ogq.ORQ, index_offset=5), A, A) == -7
     assert q(A, 100, ogq.make_params(2048, 2, ogq.ORQ, clip_factor=-1.0), A, A) == -10
     assert q(A, 100, ogq.make_params(2048, 2, ogq.ORQ, clip_factor=float('nan')), A, A) == -10

@@ -59,6 +59,38 @@ def test_orq_small(bits, d):
                 parity.check_quantize(g, d, bits, ogq.ORQ, sweeps, seed=1234 + n, tag=f"orq{bits}-{kind}-d{d}-n{n}")
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("d", [64, 512, 2048, 4096])
+def test_orq_paper_level_counts_small(bits, d):
+    # s = 3, 5, 9 levels; zero sweeps is Algorithm 1 as printed
+    rng = np.random.default_rng(7 * bits + d)
+    for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
+        for n in (1, 2, 65, d - 1, d, 3 * d + 129):
+            g = _rng_bucket(rng, n, kind)
+            for sweeps in (0, 1):
+                parity.check_quantize(g, d, bits, ogq.ORQ_PAPER, sweeps, seed=99 + n,
+                                      tag=f"orqpaper{bits}-{kind}-d{d}-n{n}-sw{sweeps}")
+
+
+def test_orq_paper_five_levels_resnet50_size_sampled():
+    # ORQ-5 as in the paper's tables (bucket 2048, no clipping; and bucket 512 with clipping 2.5 as on ImageNet)
+    wl = synth.WORKLOADS["cfg3"]
+    g = wl.gradient()
+    for d, clip in ((2048, 0.0), (512, 2.5)):
+        nb = (g.size + d - 1) // d
+        lv, codes, rep = parity.check_quantize(g, d, 3, ogq.ORQ_PAPER, 0, seed=8, buckets=_sample(nb, 400, d),
+                                               clip_factor=clip, tag=f"orq5-d{d}-clip{clip}")
+        params = ogq.make_params(d, 3, ogq.ORQ_PAPER)
+        out = ogq.ogq_dequantize_average([codes], [lv], g.size, params)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy()
+        for b in _sample(nb, 60, 1):
+            lo, hi = b * d, min((b + 1) * d, g.size)
+            l, w = oracle.quantize(g[lo:hi], d, 3, ogq.ORQ_PAPER, 0, 8, lo, clip)
+            ref = oracle.dequantize_average([w], [l], hi - lo, d, 3, 5)
+            assert np.array_equal(out[lo:hi], ref)
+
+
 def test_orq_sweeps_and_offsets():
     rng = np.random.default_rng(77)
     g = _rng_bucket(rng, 8 * 1024 + 100, "heavy")
@@ -98,17 +130,19 @@ def test_empty_input_is_a_noop():
 # ------------------------------------------------------------------------------------------------
 # decode + average
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("bits,scheme", [(1, ogq.BINGRAD_B), (1, ogq.ORQ), (2, ogq.ORQ), (3, ogq.ORQ)])
+@pytest.mark.parametrize("bits,scheme", [(1, ogq.BINGRAD_B), (1, ogq.ORQ), (2, ogq.ORQ), (3, ogq.ORQ),
+                                         (2, ogq.ORQ_PAPER), (3, ogq.ORQ_PAPER), (4, ogq.ORQ_PAPER)])
 @pytest.mark.parametrize("d", [64, 192, 1024, 1536, 2048, 4096])
 def test_decode_average_small(bits, scheme, d):
     rng = np.random.default_rng(bits * 1000 + d)
+    stride = oracle.levels_per_bucket(scheme, bits)
     for n in (1, 65, d, 2 * d + 63, 7 * d + 1):
         for W in (1, 2, 3, 8):
             gs = [_rng_bucket(rng, n, "heavy" if w % 2 else "normal") for w in range(W)]
             # oracle streams decoded by the oracle = expected; the same streams uploaded and decoded on the GPU
             q = [oracle.quantize(g, d, bits, scheme, 1, seed=40 + w) for w, g in enumerate(gs)]
-            ref = oracle.dequantize_average([w for _, w in q], [l for l, _ in q], n, d, bits)
-            scale = parity.term_scale([l for l, _ in q], [w for _, w in q], n, d, bits)
+            ref = oracle.dequantize_average([w for _, w in q], [l for l, _ in q], n, d, bits, stride)
+            scale = parity.term_scale([l for l, _ in q], [w for _, w in q], n, d, bits, stride)
             dl = [torch.from_numpy(np.concatenate([l, np.zeros(4, np.float32)])).to(DEV) for l, _ in q]
             dc = [torch.from_numpy(np.concatenate([w, np.zeros(2, np.uint64)]).view(np.int64)).to(DEV) for _, w in q]
             params = ogq.make_params(d, bits, scheme)

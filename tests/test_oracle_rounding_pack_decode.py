@@ -159,3 +159,40 @@ def test_table1_sizes_used_by_the_benchmark_configs(golden_dir):
     for model, millions, ms in rows:
         t = 32 * float(millions) * 1e6 / 10e9 * 1e3
         assert abs(t - float(ms)) < (3.0 if model == "GoogLeNet" else 0.6)
+
+
+def test_paper_level_counts_three_five_nine():
+    # s = 2^K + 1 levels (Algorithm 1's initialisation) coded with K + 1 bits; zero sweeps = the algorithm as printed
+    rng = np.random.default_rng(21)
+    g = (rng.standard_t(3, 3 * 256 + 40) * 1e-3).astype(np.float32)
+    for bits, s in ((2, 3), (3, 5), (4, 9)):
+        assert oracle.levels_per_bucket(oracle.ORQ_PAPER, bits) == s
+        lv, codes, _ = oracle.quantize_codes(g, 256, bits, oracle.ORQ_PAPER, 0, seed=4)
+        assert lv.size == 4 * s and codes.max() == s - 1 and codes.min() == 0
+        for b in range(4):
+            seg = g[256 * b:256 * (b + 1)]
+            assert np.array_equal(lv[s * b:s * (b + 1)], oracle.orq_levels_bucket(seg, s, 0))
+        dec = lv.reshape(4, s)[np.arange(g.size) // 256, codes]
+        # each element decodes to one of its two neighbouring levels
+        table = lv.reshape(4, s)[np.arange(g.size) // 256]
+        below = np.max(np.where(table <= g[:, None], table, -np.inf), axis=1)
+        above = np.min(np.where(table >= g[:, None], table, np.inf), axis=1)
+        assert np.all((dec == below) | (dec == above))
+        words = oracle.pack(codes, bits)
+        out = oracle.dequantize_average([words], [lv], g.size, 256, bits, stride=s)
+        assert np.array_equal(out, dec)
+
+
+def test_three_level_rounding_is_unbiased():
+    rng = np.random.default_rng(22)
+    g = rng.normal(0, 1e-3, 128).astype(np.float32)
+    acc = np.zeros(g.size)
+    trials = 600
+    for t in range(trials):
+        lv, codes, _ = oracle.quantize_codes(g, 128, 2, oracle.ORQ_PAPER, 0, seed=5000 + t)
+        acc += lv[codes].astype(np.float64)
+    lo = np.array([lv[lv <= v].max() for v in g], np.float64)
+    hi = np.array([lv[lv >= v].min() for v in g], np.float64)
+    var = (g - lo) * (hi - g)
+    z = (acc / trials - g)[var > 0] / np.sqrt(var[var > 0] / trials)
+    assert np.abs(z).max() < 5.0
