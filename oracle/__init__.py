@@ -19,6 +19,7 @@ _LIB = os.path.join(_HERE, "libogq_oracle.so")
 
 BINGRAD_B = 0
 ORQ = 1
+BINGRAD_PB = 2
 ORQ_PAPER = 3
 
 
@@ -47,6 +48,8 @@ def lib() -> ctypes.CDLL:
         L.ogq_oracle_uniform.restype = ctypes.c_float
         L.ogq_oracle_bingrad_bucket.argtypes = [vp, sz, u32, vp, vp]
         L.ogq_oracle_bingrad_bucket.restype = None
+        L.ogq_oracle_bingrad_pb_level.argtypes = [vp, sz]
+        L.ogq_oracle_bingrad_pb_level.restype = ctypes.c_float
         L.ogq_oracle_qstar.argtypes = [vp, sz, ctypes.c_float, ctypes.c_float]
         L.ogq_oracle_qstar.restype = ctypes.c_float
         L.ogq_oracle_orq_levels_bucket.argtypes = [vp, sz, u32, u32, vp]
@@ -103,6 +106,11 @@ def bingrad_bucket(g, iters: int = 0):
     b0 = np.zeros(1, dtype=np.float32)
     lib().ogq_oracle_bingrad_bucket(_ptr(g), g.size, iters, _ptr(levels), _ptr(b0))
     return levels, np.float32(b0[0])
+
+
+def bingrad_pb_level(g) -> np.float32:
+    g = _f32(g)
+    return np.float32(lib().ogq_oracle_bingrad_pb_level(_ptr(g), g.size))
 
 
 def qstar(sorted_x, L, R) -> np.float32:

@@ -32,13 +32,13 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_BINGRAD_B = 0, ORACLE_ORQ = 1, ORACLE_ORQ_PAPER = 3 };
+enum { ORACLE_BINGRAD_B = 0, ORACLE_ORQ = 1, ORACLE_BINGRAD_PB = 2, ORACLE_ORQ_PAPER = 3 };
 
 /* Levels per bucket: BinGrad-b 2; ORQ 2^bits; ORQ with the paper's level counts s = 2^K + 1
  * (Algorithm 1: 3, 5, 9 levels), whose indices need bits = K + 1 bits.  0 = bad combination. */
 uint32_t ogq_oracle_levels_per_bucket(uint32_t scheme, uint32_t bits)
 {
-    if (scheme == ORACLE_BINGRAD_B) return bits == 1 ? 2u : 0u;
+    if (scheme == ORACLE_BINGRAD_B || scheme == ORACLE_BINGRAD_PB) return bits == 1 ? 2u : 0u;
     if (scheme == ORACLE_ORQ) return (bits >= 1 && bits <= 8) ? 1u << bits : 0u;
     if (scheme == ORACLE_ORQ_PAPER) return (bits >= 2 && bits <= 8) ? (1u << (bits - 1)) + 1u : 0u;
     return 0u;
@@ -113,6 +113,35 @@ void ogq_oracle_bingrad_bucket(const float* g, size_t n, uint32_t iters, float l
     levels[0] = (float)b_lo;
     levels[1] = (float)b_hi;
     *b0_out = b0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * BinGrad-pb (Section 3.2, the partially biased two-level scheme): levels -b_1 and +b_1; elements
+ * outside [-b_1, b_1) are clamped to the nearer level, elements inside are rounded at random, which
+ * is the random-rounding rule of Section 3.1 applied to the two levels (see the encode routine).
+ * b_1 follows the scheme's optimal condition  b_1 * P(v > 0) = integral_{b_1}^inf v p(v) dv, which for
+ * a bucket reads  b_1 * #{v > 0} = sum_{v >= b_1} v;  as the paper prescribes for discrete values, the
+ * absolute difference of the two sides is minimised, here over the bucket's positive values (the
+ * smaller value on a tie).  A bucket without positive values gets b_1 = 0.
+ * ---------------------------------------------------------------------------------------- */
+float ogq_oracle_bingrad_pb_level(const float* g, size_t n)
+{
+    size_t positives = 0;
+    for (size_t i = 0; i < n; ++i) if (g[i] > 0.0f) ++positives;
+    float best = 0.0f;
+    double best_gap = -1.0;
+    for (size_t i = 0; i < n; ++i) {
+        float b = g[i];
+        if (!(b > 0.0f)) continue;
+        double tail = 0.0;
+        for (size_t j = 0; j < n; ++j) if (g[j] >= b) tail += (double)g[j];
+        double gap = fabs((double)b * (double)positives - tail);
+        if (best_gap < 0.0 || gap < best_gap || (gap == best_gap && b < best)) {
+            best_gap = gap;
+            best = b;
+        }
+    }
+    return best;
 }
 
 /* ------------------------------------------------------------------------------------------
@@ -282,7 +311,14 @@ int ogq_oracle_quantize_codes(const float* g, size_t n, uint32_t bucket_size, ui
             if (thresholds) thresholds[b] = b0;
             for (size_t i = 0; i < len; ++i) codes[begin + i] = gb[i] >= b0 ? 1 : 0;
         } else {
-            ogq_oracle_orq_levels_bucket(gb, len, s, level_iters, lv);
+            if (scheme == ORACLE_BINGRAD_PB) {
+                float b1 = ogq_oracle_bingrad_pb_level(gb, len);
+                lv[0] = -b1;
+                lv[1] = b1;
+                if (thresholds) thresholds[b] = b1;
+            } else {
+                ogq_oracle_orq_levels_bucket(gb, len, s, level_iters, lv);
+            }
             for (size_t i = 0; i < len; ++i) {
                 float u = ogq_oracle_uniform(seed, index_offset + begin + i);
                 codes[begin + i] = (uint8_t)ogq_oracle_orq_encode_element(gb[i], lv, s, u);
