@@ -55,6 +55,12 @@ typedef enum {
      * Algorithm 1 followed by re-solve sweeps), unbiased random rounding (Section 3.1).
      * bits in 1..3. */
     OGQ_ORQ = 1,
+    /* BinGrad-pb: two levels -b_1, +b_1, partially biased (Section 3.2): values outside [-b_1, b_1) go to
+     * the nearer level, values inside are rounded at random as in ORQ (same draws).  b_1 minimises
+     * |b * #{v > 0} - sum_{v >= b} v| (the scheme's optimal condition for discrete values) over the
+     * bucket's positive values, the smaller value on a tie; 0 if the bucket has no positive value.
+     * bits must be 1; level_iters is ignored. */
+    OGQ_BINGRAD_PB = 2,
     /* ORQ with the paper's level counts s = 2^K + 1 (Algorithm 1's initialisation: 3, 5 or 9 levels);
      * bits = K + 1 in 2..4 is the width of a level index.  With level_iters = 0 the levels are those of
      * Algorithm 1 as printed.  Encoding and packing as for OGQ_ORQ. */
@@ -86,7 +92,7 @@ typedef struct {
 } ogq_params_t;
 
 /* Sizes of the outputs of ogq_quantize for a gradient of n elements (pure host arithmetic).
- *   levels_per_bucket = 2 (BINGRAD_B), 2^bits (ORQ), 2^(bits-1) + 1 (ORQ_PAPER)
+ *   levels_per_bucket = 2 (BINGRAD_B, BINGRAD_PB), 2^bits (ORQ), 2^(bits-1) + 1 (ORQ_PAPER)
  *   num_buckets       = ceil(n / bucket_size)
  *   levels_count      = num_buckets * levels_per_bucket    fp32 values
  *   codes_bytes       = ceil(n / 64) * bits * 8            bytes

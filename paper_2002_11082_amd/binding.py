@@ -10,6 +10,7 @@ LIB_PATH = os.path.join(_PKG, "libogq.so")
 
 BINGRAD_B = 0
 ORQ = 1
+BINGRAD_PB = 2
 ORQ_PAPER = 3
 MAX_WORKERS = 64
 PROBE_SINK_FLOATS = 8192

@@ -544,7 +544,9 @@ struct OrqShape {
 
 // FULL: the bucket has exactly 256*C elements (no padding, no per-element validity tests).
 // S levels per bucket, BITS bits per level index (S = 2^BITS, or 2^(BITS-1) + 1 for the paper's counts).
-template <int C, int S, int BITS, bool FULL, bool CLIP>
+// PB: BinGrad-pb (Section 3.2): two levels -b_1, +b_1 from the scheme's optimal condition instead of
+// the bucket extremes; the random-rounding encoder then clamps everything outside them.
+template <int C, int S, int BITS, bool FULL, bool CLIP, bool PB>
 __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B>& lds, const float* __restrict__ g,
                                            uint32_t len, size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
                                            uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
@@ -584,6 +586,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
 
     // ---- extremes ------------------------------------------------------------------------------
     float lane_min = __uint_as_float(0x7F800000u), lane_max = __uint_as_float(0xFF800000u);
+    uint32_t lane_zeros = 0;
 #pragma unroll
     for (int c = 0; c < C; ++c)
 #pragma unroll
@@ -591,6 +594,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
             const bool valid = full || (256u * c + 4u * lane + k < len);
             lane_min = fminf(lane_min, valid ? v[c][k] : __uint_as_float(0x7F800000u));
             lane_max = fmaxf(lane_max, valid ? v[c][k] : __uint_as_float(0xFF800000u));
+            if constexpr (PB) lane_zeros += (valid && v[c][k] == 0.0f) ? 1u : 0u;
         }
     const float bucket_min = wave_min(lane_min) + 0.0f;  // -0 -> +0
     const float bucket_max = wave_max(lane_max) + 0.0f;
@@ -599,7 +603,8 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     const uint32_t t_max = mag_max >> SHIFT;
     const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
 
-    if constexpr (S > 2) {
+    float pb_level = 0.0f;
+    if constexpr (S > 2 || PB) {
         // ---- histogram: the returning LDS add hands every element its position inside its bin ------
 #pragma unroll
         for (int t = 0; t < PER; ++t) lds.bin_start[lane * PER + t] = 0u;
@@ -692,7 +697,37 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
+        if constexpr (PB) {
+            // ---- b_1: minimise |b * #{v > 0} - sum_{v >= b} v| over the positive bucket values.  The
+            //      difference grows with b, so the minimiser is one of the two values around its sign
+            //      change, which a bisection over the ranks of the positive values finds. -------------
+            const uint32_t zeros = wave_sum_u32(lane_zeros);
+            const uint32_t not_positive = uniform_u32(lds.bin_start[HALF]) + zeros;  // negatives fill the lower bins
+            const uint32_t positives = len - not_positive;
+            const double total = uniform_f64(lds.lvl_sum_le[S - 1]);
+            if (positives > 0u) {
+                uint32_t lo = not_positive + 1u, hi = len;  // 1-based ranks; the largest value always has gap >= 0
+                while (lo < hi) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    const Picked p = pick_rank<D, B>(lds, my_start, mid, lane);
+                    const double gap = (double)key_to_float(p.key) * (double)positives - (total - p.sum_lt);
+                    if (gap >= 0.0) hi = mid;
+                    else lo = mid + 1u;
+                }
+                const Picked up = pick_rank<D, B>(lds, my_start, lo, lane);
+                const double gap_up = (double)key_to_float(up.key) * (double)positives - (total - up.sum_lt);
+                pb_level = key_to_float(up.key);
+                if (up.count_lt > not_positive) {  // a smaller positive value exists: rank count_lt is the next one down
+                    const Picked down = pick_rank<D, B>(lds, my_start, up.count_lt, lane);
+                    const double gap_down =
+                        (double)key_to_float(down.key) * (double)positives - (total - down.sum_lt);
+                    if (fabs(gap_down) <= fabs(gap_up)) pb_level = key_to_float(down.key);  // ties take the smaller value
+                }
+            }
+        }
+
         // ---- level solves: greedy recursion (Algorithm 1), then re-solve sweeps ------------------
+        if constexpr (S > 2) {
         constexpr GreedyOrder order = greedy_order<S>();
         const uint32_t steps = order.count + sweeps * (S - 2);
         for (uint32_t step = 0; step < steps; ++step) {
@@ -748,12 +783,13 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
+        }
     }
 
     // every lane holds its own copy of the levels (the selects of the encoder take vector sources)
     float lv[S];
-    lv[0] = key_to_float(key_min);
-    lv[S - 1] = key_to_float(key_max);
+    lv[0] = PB ? -pb_level : key_to_float(key_min);
+    lv[S - 1] = PB ? pb_level : key_to_float(key_max);
 #pragma unroll
     for (int k = 1; k < S - 1; ++k) lv[k] = lds.lvl_value[k];
 
@@ -814,7 +850,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     }
 }
 
-template <int C, int S, int BITS, bool CLIP>
+template <int C, int S, int BITS, bool CLIP, bool PB>
 __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
                                                              uint32_t bucket_size, uint32_t sweeps, float clip,
                                                              uint32_t num_buckets, uint64_t seed,
@@ -828,9 +864,9 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
     const size_t rest = n - begin;
     const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
     if (len == (uint32_t)OrqShape<C>::D)
-        orq_bucket<C, S, BITS, true, CLIP>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+        orq_bucket<C, S, BITS, true, CLIP, PB>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
     else
-        orq_bucket<C, S, BITS, false, CLIP>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+        orq_bucket<C, S, BITS, false, CLIP, PB>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -976,7 +1012,7 @@ __global__ __launch_bounds__(kBlock) void probe_copy_kernel(const float4* __rest
 // Levels per bucket, 0 for a scheme / bits combination that does not exist.
 uint32_t levels_per_bucket(uint32_t scheme, uint32_t bits)
 {
-    if (scheme == OGQ_BINGRAD_B) return bits == 1 ? 2u : 0u;
+    if (scheme == OGQ_BINGRAD_B || scheme == OGQ_BINGRAD_PB) return bits == 1 ? 2u : 0u;
     if (scheme == OGQ_ORQ) return (bits >= 1 && bits <= 3) ? 1u << bits : 0u;
     if (scheme == OGQ_ORQ_PAPER) return (bits >= 2 && bits <= 4) ? (1u << (bits - 1)) + 1u : 0u;
     return 0u;
@@ -989,7 +1025,8 @@ int check_params(const ogq_params_t* p, bool quantize)
     if (!p) return OGQ_ERR_NULL_POINTER;
     if (p->bucket_size == 0 || p->bucket_size % 64 != 0 || p->bucket_size > OGQ_MAX_BUCKET_SIZE)
         return OGQ_ERR_BUCKET_SIZE;
-    if (p->scheme != OGQ_BINGRAD_B && p->scheme != OGQ_ORQ && p->scheme != OGQ_ORQ_PAPER) return OGQ_ERR_SCHEME;
+    if (p->scheme != OGQ_BINGRAD_B && p->scheme != OGQ_ORQ && p->scheme != OGQ_BINGRAD_PB && p->scheme != OGQ_ORQ_PAPER)
+        return OGQ_ERR_SCHEME;
     if (levels_per_bucket(p->scheme, p->bits) == 0) return OGQ_ERR_BITS;
     if (quantize) {
         if (p->index_offset % 64 != 0) return OGQ_ERR_INDEX_OFFSET;
@@ -1021,15 +1058,15 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
                            p->bucket_size, p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
 }
 
-template <int C, int S, int BITS>
+template <int C, int S, int BITS, bool PB = false>
 void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
     if (p->clip_factor > 0.0f)
-        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, true>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, true, PB>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
                            p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
                            static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, false>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, false, PB>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
                            p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
                            static_cast<uint32_t*>(codes));
 }
@@ -1038,7 +1075,9 @@ template <int C>
 void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                        hipStream_t st)
 {
-    if (p->scheme == OGQ_ORQ) {
+    if (p->scheme == OGQ_BINGRAD_PB) {
+        launch_orq<C, 2, 1, true>(g, n, p, nb, lv, codes, st);
+    } else if (p->scheme == OGQ_ORQ) {
         switch (p->bits) {
             case 1: launch_orq<C, 2, 1>(g, n, p, nb, lv, codes, st); break;
             case 2: launch_orq<C, 4, 2>(g, n, p, nb, lv, codes, st); break;
@@ -1187,7 +1226,7 @@ const char* ogq_strerror(int status)
         case OGQ_OK: return "ok";
         case OGQ_ERR_NULL_POINTER: return "a required pointer is NULL";
         case OGQ_ERR_BUCKET_SIZE: return "bucket_size must be a multiple of 64 in [64, 4096]";
-        case OGQ_ERR_BITS: return "bits not supported by the scheme (BinGrad-b: 1, ORQ: 1..3, ORQ_PAPER: 2..4)";
+        case OGQ_ERR_BITS: return "bits not supported by the scheme (BinGrad-b / -pb: 1, ORQ: 1..3, ORQ_PAPER: 2..4)";
         case OGQ_ERR_SCHEME: return "unknown scheme";
         case OGQ_ERR_NUM_WORKERS: return "num_workers must be in [1, 64]";
         case OGQ_ERR_ALIGNMENT: return "device pointers must be 16-byte aligned";

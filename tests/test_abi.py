@@ -63,6 +63,8 @@ def test_size_queries(lib):
     assert ogq.ogq_levels_per_bucket(ogq.make_params(2048, 1, ogq.ORQ_PAPER)) == 0
     assert ogq.ogq_levels_per_bucket(ogq.make_params(2048, 3, ogq.ORQ)) == 8
     assert ogq.ogq_levels_per_bucket(ogq.make_params(2048, 1, ogq.BINGRAD_B)) == 2
+    assert ogq.ogq_levels_per_bucket(ogq.make_params(2048, 1, ogq.BINGRAD_PB)) == 2
+    assert ogq.ogq_levels_per_bucket(ogq.make_params(2048, 2, ogq.BINGRAD_PB)) == 0
     # one bit per element is the paper's x32 compression (level floats not counted)
     p = ogq.make_params(512, 1, ogq.BINGRAD_B)
     assert 4 * 1_048_576 / ogq.ogq_codes_bytes(1_048_576, p) == 32

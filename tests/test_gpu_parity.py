@@ -59,6 +59,34 @@ def test_orq_small(bits, d):
                 parity.check_quantize(g, d, bits, ogq.ORQ, sweeps, seed=1234 + n, tag=f"orq{bits}-{kind}-d{d}-n{n}")
 
 
+@pytest.mark.parametrize("d", [64, 256, 320, 512, 2048, 4096])
+def test_bingrad_pb_small(d):
+    rng = np.random.default_rng(1000 + d)
+    for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
+        for n in (1, 2, 65, d - 1, d, 3 * d + 129):
+            g = _rng_bucket(rng, n, kind)
+            parity.check_quantize(g, d, 1, ogq.BINGRAD_PB, 0, seed=31 + n, tag=f"bingradpb-{kind}-d{d}-n{n}")
+            parity.check_quantize(-g, d, 1, ogq.BINGRAD_PB, 0, seed=31 + n, tag=f"bingradpb-neg-{kind}-d{d}-n{n}")
+    g = _rng_bucket(rng, 4 * d + 3, "heavy")
+    parity.check_quantize(g, d, 1, ogq.BINGRAD_PB, 0, seed=5, clip_factor=2.5, tag=f"bingradpb-clip-d{d}")
+
+
+def test_bingrad_pb_resnet50_size_sampled():
+    wl = synth.WORKLOADS["cfg2"]
+    g = wl.gradient()
+    d = 2048
+    nb = (g.size + d - 1) // d
+    lv, codes, rep = parity.check_quantize(g, d, 1, ogq.BINGRAD_PB, 0, seed=9, buckets=_sample(nb, 120, 4),
+                                           tag="bingradpb-cfg2")
+    out = ogq.ogq_dequantize_average([codes], [lv], g.size, ogq.make_params(d, 1, ogq.BINGRAD_PB))
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    for b in _sample(nb, 40, 2):
+        lo, hi = b * d, min((b + 1) * d, g.size)
+        l, w = oracle.quantize(g[lo:hi], d, 1, ogq.BINGRAD_PB, 0, 9, lo)
+        assert np.array_equal(out[lo:hi], oracle.dequantize_average([w], [l], hi - lo, d, 1, 2))
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("d", [64, 512, 2048, 4096])
 def test_orq_paper_level_counts_small(bits, d):
@@ -130,7 +158,7 @@ def test_empty_input_is_a_noop():
 # ------------------------------------------------------------------------------------------------
 # decode + average
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("bits,scheme", [(1, ogq.BINGRAD_B), (1, ogq.ORQ), (2, ogq.ORQ), (3, ogq.ORQ),
+@pytest.mark.parametrize("bits,scheme", [(1, ogq.BINGRAD_B), (1, ogq.BINGRAD_PB), (1, ogq.ORQ), (2, ogq.ORQ), (3, ogq.ORQ),
                                          (2, ogq.ORQ_PAPER), (3, ogq.ORQ_PAPER), (4, ogq.ORQ_PAPER)])
 @pytest.mark.parametrize("d", [64, 192, 1024, 1536, 2048, 4096])
 def test_decode_average_small(bits, scheme, d):
