@@ -27,12 +27,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 
-def algorithmic_bytes(n: int, bucket_size: int, bits: int, workers: int):
+def algorithmic_bytes(n: int, bucket_size: int, bits: int, workers: int, levels_per_bucket: int):
     """Bytes the method must move per launch: quantize reads the gradient once and writes codes and
     levels; decode-average reads every worker's codes and levels and writes the fp32 average."""
     nb = (n + bucket_size - 1) // bucket_size
     codes = ((n + 63) // 64) * bits * 8
-    levels = (nb << bits) * 4
+    levels = nb * levels_per_bucket * 4
     return 4 * n + codes + levels, workers * (codes + levels) + 4 * n
 
 
@@ -57,7 +57,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "pb2", "orq5", "orq3clip", "cfg2clip"])
     ap.add_argument("--buffers", type=int, default=0, help="distinct input buffers (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -94,7 +94,7 @@ def main() -> int:
     grads = []  # grads[b][w]
     for b in range(n_buf):
         grads.append([torch.from_numpy(np.roll(h, 7919 * b) if b else h).to(dev) for h in host])
-    params = [ogq.make_params(d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w)) for w in range(W)]
+    params = [ogq.make_params(d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w), 0, wl.clip_factor) for w in range(W)]
     n_levels = ogq.ogq_levels_count(n, params[0])
     n_words = ogq.ogq_codes_bytes(n, params[0]) // 8
     levels = [[torch.empty(n_levels + 4, dtype=torch.float32, device=dev) for _ in range(W)] for _ in range(n_buf)]
@@ -170,7 +170,7 @@ def main() -> int:
     torch.cuda.synchronize()
     q_avg = eq0.elapsed_time(eq1) / (args.steps * W)  # ms per quantize launch
     a_avg = ea0.elapsed_time(ea1) / args.steps        # ms per decode-average launch
-    q_bytes, a_bytes = algorithmic_bytes(n, d, bits, W)
+    q_bytes, a_bytes = algorithmic_bytes(n, d, bits, W, ogq.ogq_levels_per_bucket(params[0]))
     q_gbs = q_bytes / (q_avg * 1e-3) / 1e9
     a_gbs = a_bytes / (a_avg * 1e-3) / 1e9
 
@@ -194,6 +194,8 @@ def main() -> int:
     copy_gbs = 8 * (n - n % 4) / timed(lambda i: ogq.ogq_probe_copy(grads[i % n_buf][0], outs[(i + 1) % n_buf])) / 1e9
 
     quant_name = "bingrad_quantize_kernel" if wl.scheme == synth.BINGRAD_B else "orq_quantize_kernel"
+    # The wave-per-bucket ORQ / BinGrad-pb kernel issues ~110 VALU instructions per element (Philox, exact
+    # rank selection): it is bound by VALU issue, not by HBM; its line still prices it against the HBM peak.
     dominant_is_quant = q_avg * W >= a_avg
     roof = {
         "bound": "hbm", "kernel": quant_name if dominant_is_quant else "dequantize_average_kernel",
@@ -221,7 +223,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 data, f64 sums", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.description}", "n": n, "bucket_size": d, "bits": bits,
-                   "workers": W, "level_iters": wl.level_iters, "input_buffers": n_buf},
+                   "workers": W, "level_iters": wl.level_iters, "clip_factor": wl.clip_factor,
+                   "input_buffers": n_buf},
         "elements_per_s": round(n * W / (ms_per_step * 1e-3), 1),
         "quantize_gbs_fp32_in": round(4 * n / (q_avg * 1e-3) / 1e9, 1),
         "dequant_avg_gbs_fp32_out": round(4 * n / (a_avg * 1e-3) / 1e9, 1),
@@ -241,9 +244,10 @@ def main() -> int:
         t_cpu, reps_cpu = 0.0, 0
         while t_cpu < args.cpu_seconds and reps_cpu < 1000:
             c0 = time.perf_counter()
-            q = [oracle.quantize(g0[w][:sample_n], d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w))
-                 for w in range(W)]
-            oracle.dequantize_average([x[1] for x in q], [x[0] for x in q], sample_n, d, bits)
+            q = [oracle.quantize(g0[w][:sample_n], d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w), 0,
+                                 wl.clip_factor) for w in range(W)]
+            oracle.dequantize_average([x[1] for x in q], [x[0] for x in q], sample_n, d, bits,
+                                      ogq.ogq_levels_per_bucket(params[0]))
             t_cpu += time.perf_counter() - c0
             reps_cpu += 1
         result["cpu_baseline"] = {

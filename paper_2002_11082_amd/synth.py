@@ -14,6 +14,8 @@ import numpy as np
 
 BINGRAD_B = 0
 ORQ = 1
+BINGRAD_PB = 2
+ORQ_PAPER = 3
 
 
 def gaussian(n: int, sigma: float, seed: int) -> np.ndarray:
@@ -82,9 +84,13 @@ class Workload:
     workers: int
     seed: int            # Philox seed of worker 0 (worker w uses seed + w)
     description: str
+    clip_factor: float = 0.0
+    data: str = ""       # name of the workload whose gradient recipe is reused ("" = own)
 
     def gradient(self, worker: int = 0, n: int | None = None) -> np.ndarray:
         n = self.n if n is None else n
+        if self.data:
+            return WORKLOADS[self.data].gradient(worker, n)
         if self.name == "cfg1":
             return gaussian(n, 1e-3, 0)
         if self.name == "cfg2":
@@ -112,4 +118,15 @@ WORKLOADS = {
                      "ORQ 3-bit (s=8), VGG-19-shaped 143.7M x Student-t(3)/sqrt(fan_in), bucket 4096, 2 sweeps"),
     "cfg5": Workload("cfg5", 61_100_000, 2048, 2, ORQ, 2, 8, 200,
                      "8 workers x AlexNet-sized 61.1M x N(0,1e-3^2), ORQ 2-bit, bucket 2048, decode-average"),
+    # the rows added after the five configurations (same inputs, other quantizers)
+    "pb2": Workload("pb2", 25_600_000, 2048, 1, BINGRAD_PB, 0, 1, 4,
+                    "BinGrad-pb 1-bit on the cfg2 gradient, bucket 2048", data="cfg2"),
+    "orq5": Workload("orq5", 25_600_000, 2048, 3, ORQ_PAPER, 0, 1, 5,
+                     "ORQ-5 (Algorithm 1 as printed, 5 levels in 3 bits) on the cfg3 gradient, bucket 2048", data="cfg3"),
+    "orq3clip": Workload("orq3clip", 25_600_000, 512, 2, ORQ_PAPER, 0, 1, 6,
+                         "ORQ-3 with clipping c=2.5, bucket 512 (the paper's ImageNet setting) on the cfg3 gradient",
+                         clip_factor=2.5, data="cfg3"),
+    "cfg2clip": Workload("cfg2clip", 25_600_000, 2048, 1, BINGRAD_B, 0, 1, 0,
+                         "BinGrad-b 1-bit with clipping c=2.5 on the cfg2 gradient, bucket 2048",
+                         clip_factor=2.5, data="cfg2"),
 }
