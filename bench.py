@@ -39,7 +39,12 @@ def algorithmic_bytes(n: int, bucket_size: int, bits: int, workers: int, levels_
 def read_traffic_note(kernel_key: str):
     """Measured HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy
     kernel of known size) as recorded in profiles/hbm_traffic.txt, or None."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    return read_note("hbm_traffic.txt", kernel_key)
+
+
+def read_note(file_name: str, kernel_key: str):
+    """A figure recorded from a separate rocprofv3 counter run: `<workload>:<kernel> <value>` lines."""
+    path = os.path.join(ROOT, "profiles", file_name)
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -214,6 +219,16 @@ def main() -> int:
         "avg_launch_us": round((a_avg if dominant_is_quant else q_avg) * 1e3, 2),
     }
 
+    # VALU instructions per wavefront of the quantize kernel, from rocprofv3 --pmc SQ_INSTS_VALU / SQ_WAVES
+    # (profiles/valu_instructions.txt), priced against 78.6 T lane-operations/s (256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz)
+    valu_per_wave = read_note("valu_instructions.txt", f"{args.workload}:{quant_name}")
+    alu = None
+    if valu_per_wave is not None and wl.scheme != synth.BINGRAD_B:
+        lane_ops = valu_per_wave * 64 * ((n + d - 1) // d)
+        achieved = lane_ops / (q_avg * 1e-3) / 1e12
+        alu = {"bound": "alu", "kernel": quant_name, "achieved": round(achieved, 2), "peak": 78.6,
+               "unit": "T lane-op/s", "frac": round(achieved / 78.6, 4), "valu_instructions_per_wavefront": valu_per_wave}
+
     result = {
         "metric": "quantize+pack GB/s of fp32 gradient (fraction of HBM peak); dequant-avg GB/s",
         "value": round(grad_bytes / (ms_per_step * 1e-3) / 1e9, 2),
@@ -233,6 +248,8 @@ def main() -> int:
         "roofline": roof,
         "roofline_other_kernel": other,
     }
+    if alu:
+        result["alu"] = alu
 
     if not args.no_cpu_baseline:
         import oracle
