@@ -147,6 +147,26 @@ def test_clipping_before_quantization(clip):
                                       tag=f"clip{clip}-orq{bits}-{kind}-d{d}")
 
 
+def test_random_shapes_and_parameters():
+    # many small random problems: sizes, bucket sizes (every multiple of 64 is legal), schemes, widths, iterations,
+    # clipping, value distributions, including buckets dominated by repeated values
+    rng = np.random.default_rng(20260101)
+    kinds = ("normal", "ints", "heavy", "shifted", "const", "zeros")
+    for trial in range(240):
+        d = int(rng.choice([64, 128, 192, 256, 448, 512, 1024, 1536, 2048, 3072, 4096]))
+        n = int(rng.integers(1, 5 * d + 2))
+        scheme, bits = [(ogq.BINGRAD_B, 1), (ogq.BINGRAD_PB, 1), (ogq.ORQ, 1), (ogq.ORQ, 2), (ogq.ORQ, 3),
+                        (ogq.ORQ_PAPER, 2), (ogq.ORQ_PAPER, 3), (ogq.ORQ_PAPER, 4)][trial % 8]
+        g = _rng_bucket(rng, n, kinds[int(rng.integers(len(kinds)))])
+        if trial % 5 == 0:  # mixed magnitudes inside one bucket
+            g = (g * np.float32(10.0) ** rng.integers(-6, 4, n).astype(np.float32)).astype(np.float32)
+        clip = float(rng.choice([0.0, 0.0, 1.7, 2.5]))
+        iters = int(rng.integers(0, 4))
+        off = 64 * int(rng.integers(0, 1 << 20))
+        parity.check_quantize(g, d, bits, scheme, iters, seed=int(rng.integers(1 << 62)), index_offset=off,
+                              clip_factor=clip, tag=f"random-{trial}")
+
+
 def test_empty_input_is_a_noop():
     p = ogq.make_params(512, 1, ogq.BINGRAD_B)
     x = torch.zeros(4, device=DEV)
