@@ -799,6 +799,15 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     }
 
     // ---- encode (random rounding, Section 3.1) + pack ----------------------------------------------
+    // Per element only the level compares, the selects of (level below, interval width) and the rounding
+    // test run on the vector unit; the level index is assembled from the compare masks on the scalar unit
+    // (the masks are a thermometer code of the interval, to which the rounding bit is added with carry).
+    float width[S - 1];
+#pragma unroll
+    for (int k = 0; k < S - 1; ++k) width[k] = lv[k + 1] - lv[k];
+    uint32_t bit_of[4];  // where element k of this lane sits in its 32-bit half of a packed word
+#pragma unroll
+    for (int k = 0; k < 4; ++k) bit_of[k] = 1u << (4u * (lane & 7u) + k);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t padded_len = (len + 63u) & ~63u;
     const size_t word0 = begin / 64;
@@ -813,25 +822,35 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const float x = v[c][k];
-            const bool valid = full || (256u * c + 4u * lane + k < len);
-            // interval index: last level not above x, at most S-2
-            uint32_t idx = 0;
-            float base = lv[0], next = lv[1];
+            // interval: last level not above x, at most S-2
+            uint64_t not_below[S];  // [t]: lanes whose element is >= level t, t = 1 .. S-2
+            float base = lv[0], w = width[0];
 #pragma unroll
             for (int t = 1; t < S - 1; ++t) {
                 const bool ge = lv[t] <= x;
-                idx += ge ? 1u : 0u;
+                not_below[t] = __ballot(ge);
                 base = ge ? lv[t] : base;
-                next = ge ? lv[t + 1] : next;
+                w = ge ? width[t] : w;
             }
-            const float w = next - base;
             const float delta = x - base;
             const float u = (float)(r[k] >> 8) * 0x1p-24f;
             const float scaled = u * w;
-            uint32_t code = idx + (scaled < delta ? 1u : 0u);
-            code = valid ? code : 0u;
+            uint64_t carry = __ballot(scaled < delta);  // rounded up
+            if constexpr (!FULL) carry &= __ballot(256u * c + 4u * lane + k < len);
 #pragma unroll
-            for (int p = 0; p < BITS; ++p) plane[p] |= ((code >> p) & 1u) << (4u * (lane & 7u) + k);
+            for (int p = 0; p < BITS; ++p) {
+                // bit p of the number of levels 1..S-2 not above x
+                uint64_t index_bit = 0;
+#pragma unroll
+                for (int j = 1; (j << p) <= S - 2; j += 2) {
+                    const int lo_t = j << p, hi_t = (j + 1) << p;
+                    index_bit |= hi_t <= S - 2 ? (not_below[lo_t] & ~not_below[hi_t]) : not_below[lo_t];
+                }
+                if constexpr (!FULL) index_bit &= __ballot(256u * c + 4u * lane + k < len);
+                const uint64_t code_bit = index_bit ^ carry;
+                carry &= index_bit;
+                plane[p] |= __builtin_amdgcn_inverse_ballot_w64(code_bit) ? bit_of[k] : 0u;
+            }
         }
         // OR over the 8 lanes that make up one 32-bit half of a packed word
 #pragma unroll
