@@ -114,6 +114,36 @@ __device__ __forceinline__ float wave_max(float x)
     return fmaxf(fmaxf(readlane_f32(x, 0), readlane_f32(x, 16)), fmaxf(readlane_f32(x, 32), readlane_f32(x, 48)));
 }
 
+constexpr int kDppRor8 = 0x128;   // rotate by 8 inside a row of 16 lanes: partner lane ^ 8
+constexpr int kDppRowShl4 = 0x104;  // lane i takes lane i + 4 of its row
+constexpr int kDppRowShr4 = 0x114;  // lane i takes lane i - 4 of its row
+
+// Value held by lane (lane ^ DIST).
+template <int DIST>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t x, uint32_t lane)
+{
+    if constexpr (DIST == 1) {
+        return dpp_u32<kDppXor1>(x);
+    } else if constexpr (DIST == 2) {
+        return dpp_u32<kDppXor2>(x);
+    } else if constexpr (DIST == 4) {
+        // banks (groups of 4 lanes) 0 and 2 of every row take the lane 4 above, banks 1 and 3 the lane 4 below
+        int y = __builtin_amdgcn_update_dpp((int)x, (int)x, kDppRowShl4, 0xF, 0x5, false);
+        y = __builtin_amdgcn_update_dpp(y, (int)x, kDppRowShr4, 0xF, 0xA, false);
+        return (uint32_t)y;
+    } else if constexpr (DIST == 8) {
+        return dpp_u32<kDppRor8>(x);
+    } else if constexpr (DIST == 16) {
+        // rows (0,1) and (2,3) trade places
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        return (lane & 16u) ? r[0] : r[1];
+    } else {
+        // the two halves of the wave trade places
+        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        return (lane & 32u) ? r[0] : r[1];
+    }
+}
+
 // Gradient clipping of a register-resident bucket (Section 5): v <- sign(v) * min(|v|, c * sigma) with
 // sigma^2 the population variance about the bucket mean, both in fp64.  valid(j) tells whether
 // register j of this lane holds a bucket element.
@@ -262,6 +292,257 @@ __global__ __launch_bounds__(kWave* kBinGradWaves)
 }
 
 // ----------------------------------------------------------------------------------------------
+// BinGrad-b for bucket sizes that divide 2048: one wavefront quantizes NB = 2048 / bucket_size whole
+// buckets at once (registers E*q .. E*q + E - 1 hold its bucket q in the layout above), so that a
+// small bucket keeps as many loads in flight per wave as a 2048-element one and the per-bucket
+// reductions and divisions are shared.  The NB partial results of a pass are reduced together: a
+// step over lane bit 5, 4, 3, ... combines two partner lanes and halves the number of values a lane
+// carries, the lanes with the bit clear keeping the even-numbered values and the others the
+// odd-numbered ones.  When one value is left lane l holds the result of bucket q(l) = (l with its six
+// bits reversed) mod NB, and the remaining low lane bits are reduced as in wave_sum.
+// ----------------------------------------------------------------------------------------------
+constexpr int kDppXor1From0 = 0xA0;  // quad_perm [0,0,2,2]: an odd lane takes the even lane below it
+
+__device__ __forceinline__ double words_to_f64(uint32_t lo, uint32_t hi)
+{
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// swap_halves: first = {a[0..31], b[0..31]}, second = {a[32..63], b[32..63]} (v_permlane32_swap).
+// swap_rows: the same over pairs of 16-lane rows: first = {a.row0, b.row0, a.row2, b.row2},
+// second = {a.row1, b.row1, a.row3, b.row3} (v_permlane16_swap).
+__device__ __forceinline__ void swap_halves(float a, float b, float& first, float& second)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    first = __uint_as_float(r[0]);
+    second = __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ void swap_halves(double a, double b, double& first, double& second)
+{
+    const uint64_t ua = (uint64_t)__double_as_longlong(a), ub = (uint64_t)__double_as_longlong(b);
+    const auto lo = __builtin_amdgcn_permlane32_swap((uint32_t)ua, (uint32_t)ub, false, false);
+    const auto hi = __builtin_amdgcn_permlane32_swap((uint32_t)(ua >> 32), (uint32_t)(ub >> 32), false, false);
+    first = words_to_f64(lo[0], hi[0]);
+    second = words_to_f64(lo[1], hi[1]);
+}
+
+__device__ __forceinline__ void swap_rows(float a, float b, float& first, float& second)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    first = __uint_as_float(r[0]);
+    second = __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ void swap_rows(double a, double b, double& first, double& second)
+{
+    const uint64_t ua = (uint64_t)__double_as_longlong(a), ub = (uint64_t)__double_as_longlong(b);
+    const auto lo = __builtin_amdgcn_permlane16_swap((uint32_t)ua, (uint32_t)ub, false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap((uint32_t)(ua >> 32), (uint32_t)(ub >> 32), false, false);
+    first = words_to_f64(lo[0], hi[0]);
+    second = words_to_f64(lo[1], hi[1]);
+}
+
+template <int DIST>
+__device__ __forceinline__ float lane_xor_val(float x, uint32_t lane)
+{
+    return __uint_as_float(lane_xor<DIST>(__float_as_uint(x), lane));
+}
+
+template <int DIST>
+__device__ __forceinline__ double lane_xor_val(double x, uint32_t lane)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    return words_to_f64(lane_xor<DIST>((uint32_t)u, lane), lane_xor<DIST>((uint32_t)(u >> 32), lane));
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_val(float x) { return dpp_f32<CTRL>(x); }
+template <int CTRL>
+__device__ __forceinline__ double dpp_val(double x) { return dpp_f64<CTRL>(x); }
+
+// One reduction step over lane bit DIST (8, 4 or 2): lanes with the bit clear get a (+) a of the
+// partner lane, the others b (+) b of the partner lane.
+template <int DIST, class T, class Op>
+__device__ __forceinline__ T fold_pair(T a, T b, uint32_t lane, Op op)
+{
+    const bool odd = (lane & (uint32_t)DIST) != 0;
+    const T keep = odd ? b : a, send = odd ? a : b;
+    return op(keep, lane_xor_val<DIST>(send, lane));
+}
+
+template <int Q>
+struct BucketIndex {
+    static constexpr int value = Q;
+};
+
+// Buckets FIRST .. FIRST + N - 1 of the wavefront, reduced depth first so that only one partial result
+// per tree level is alive: leaf(BucketIndex<q>) yields this lane's partial value of bucket q.
+template <int N, int FIRST, class T, class Leaf, class Op>
+__device__ __forceinline__ T reduce_bucket_tree(uint32_t lane, Leaf& leaf, Op op)
+{
+    if constexpr (N == 1) {
+        return leaf(BucketIndex<FIRST>{});
+    } else {
+        const T a = reduce_bucket_tree<N / 2, FIRST, T>(lane, leaf, op);
+        const T b = reduce_bucket_tree<N / 2, FIRST + N / 2, T>(lane, leaf, op);
+        if constexpr (N == 2) {
+            T first, second;
+            swap_halves(a, b, first, second);
+            return op(first, second);
+        } else if constexpr (N == 4) {
+            T first, second;
+            swap_rows(a, b, first, second);
+            return op(first, second);
+        } else if constexpr (N == 8) {
+            return fold_pair<8>(a, b, lane, op);
+        } else if constexpr (N == 16) {
+            return fold_pair<4>(a, b, lane, op);
+        } else {
+            return fold_pair<2>(a, b, lane, op);
+        }
+    }
+}
+
+template <int NB, class T, class Leaf, class Op>
+__device__ __forceinline__ T reduce_buckets(uint32_t lane, Leaf leaf, Op op)
+{
+    static_assert(NB == 2 || NB == 4 || NB == 8 || NB == 16 || NB == 32, "buckets per wavefront");
+    T r = reduce_bucket_tree<NB, 0, T>(lane, leaf, op);
+    // the lane bits that select no bucket
+    r = op(r, dpp_val<kDppXor1>(r));
+    if constexpr (NB <= 16) r = op(r, dpp_val<kDppXor2>(r));
+    if constexpr (NB <= 8) r = op(r, dpp_val<kDppHalfMirror>(r));
+    if constexpr (NB <= 4) r = op(r, dpp_val<kDppMirror>(r));
+    if constexpr (NB <= 2) {
+        T first, second;
+        swap_rows(r, r, first, second);
+        r = op(first, second);
+    }
+    return r;
+}
+
+constexpr uint32_t reverse6(uint32_t x)
+{
+    uint32_t r = 0;
+    for (int b = 0; b < 6; ++b) r |= ((x >> b) & 1u) << (5 - b);
+    return r;
+}
+
+constexpr uint32_t kChunk = 2048;  // elements one wavefront of the kernel below quantizes
+constexpr uint32_t kMinChunks = 2048;
+
+template <int NB>
+__global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_chunk_kernel(
+    const float* __restrict__ grad, uint32_t num_chunks, uint32_t iters, float* __restrict__ levels,
+    uint64_t* __restrict__ codes)
+{
+    constexpr int R = kChunk / 64, E = R / NB;
+    constexpr uint32_t D = 64u * E;             // bucket size
+    constexpr uint32_t kFreeBits = 64u / NB - 1u;  // lane bits that select no bucket; bit 0 is always among them
+    const uint32_t chunk = uniform_u32(blockIdx.x * kBinGradWaves + (threadIdx.x >> 6));
+    if (chunk >= num_chunks) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const float* g = grad + (size_t)chunk * kChunk;
+    float v[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) v[j] = __builtin_nontemporal_load(g + 64u * j + lane);
+
+    const auto add = [](double a, double b) { return a + b; };
+    const auto larger = [](float a, float b) { return fmaxf(a, b); };
+    // From here on lane l works for bucket q(l); the lane with the free bits clear ("home") and the one
+    // above it divide the lower and the upper side of that bucket.
+    const double total = reduce_buckets<NB, double>(
+        lane,
+        [&](auto q) {
+            double s = 0.0;
+#pragma unroll
+            for (int j = 0; j < E; ++j) s += (double)v[decltype(q)::value * E + j];
+            return s;
+        },
+        add);
+    const float trust_above = 1e-3f * reduce_buckets<NB, float>(  // see bingrad_bucket
+                                          lane,
+                                          [&](auto q) {
+                                              float m = 0.0f;
+#pragma unroll
+                                              for (int j = 0; j < E; ++j) m = fmaxf(m, fabsf(v[decltype(q)::value * E + j]));
+                                              return m;
+                                          },
+                                          larger);
+    float b0 = (float)(total / (double)D);
+    const bool upper = (lane & 1u) != 0;
+    const bool home = (lane & kFreeBits) == 0;
+
+    double b_lo = 0.0, b_hi = 0.0;
+    uint32_t word_lo = 0, word_hi = 0;  // lane j ends up holding packed word j of the chunk
+    uint32_t prev_n_lo = 0xFFFFFFFFu;
+    for (uint32_t it = 0;; ++it) {
+        uint32_t n_lo = 0;
+        const double s_lo = reduce_buckets<NB, double>(
+            lane,
+            [&](auto q) {
+                constexpr int kQ = decltype(q)::value;
+                const float threshold = readlane_f32(b0, (int)reverse6(kQ));
+                double s = 0.0;
+                uint32_t below = 0;
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    const int reg = kQ * E + j;
+                    const bool lo = v[reg] < threshold;
+                    const uint64_t lo_mask = __ballot(lo);
+                    const uint64_t hi_mask = ~lo_mask;
+                    below += (uint32_t)__popcll(lo_mask);
+                    s += (double)(lo ? v[reg] : 0.0f);
+                    word_lo = writelane(word_lo, (uint32_t)hi_mask, reg);
+                    word_hi = writelane(word_hi, (uint32_t)(hi_mask >> 32), reg);
+                }
+                n_lo = writelane(n_lo, below, (int)reverse6(kQ));
+                return s;
+            },
+            add);
+        n_lo = dpp_u32<kDppXor1From0>(n_lo);
+        double s_hi = total - s_lo;
+        const bool doubtful = !(fabs(s_hi) >= (double)trust_above);
+        if (__ballot(doubtful) != 0) {
+            const double direct = reduce_buckets<NB, double>(
+                lane,
+                [&](auto q) {
+                    constexpr int kQ = decltype(q)::value;
+                    const float threshold = readlane_f32(b0, (int)reverse6(kQ));
+                    double s = 0.0;
+#pragma unroll
+                    for (int j = 0; j < E; ++j) s += (double)(!(v[kQ * E + j] < threshold) ? v[kQ * E + j] : 0.0f);
+                    return s;
+                },
+                add);
+            if (doubtful) s_hi = direct;
+        }
+        const uint32_t n_hi = D - n_lo;
+        const double num = upper ? s_hi : s_lo;
+        const uint32_t den = upper ? n_hi : n_lo;
+        const double quot = num / (double)(den > 0 ? den : 1u);
+        const double other = dpp_f64<kDppXor1>(quot);
+        const double mean_lo = upper ? other : quot, mean_hi = upper ? quot : other;
+        b_lo = n_lo > 0 ? mean_lo : mean_hi;  // constant bucket: both levels equal
+        b_hi = n_hi > 0 ? mean_hi : mean_lo;
+        // Further threshold updates are identities for a bucket once its partition repeats.
+        if (it == iters || __ballot(home && n_lo != prev_n_lo) == 0) break;
+        prev_n_lo = n_lo;
+        b0 = (float)((b_lo + b_hi) * 0.5);
+    }
+
+    if (home) {
+        const uint32_t q = (__brev(lane) >> 26) & (uint32_t)(NB - 1);
+        float2 pair;
+        pair.x = (float)b_lo;
+        pair.y = (float)b_hi;
+        *reinterpret_cast<float2*>(levels + ((size_t)chunk * NB + q) * 2) = pair;
+    }
+    if (lane < (uint32_t)R) codes[(size_t)chunk * R + lane] = ((uint64_t)word_hi << 32) | word_lo;
+}
+
+// ----------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter (c0, c1, 0, 0), key (k0, k1).
 // ----------------------------------------------------------------------------------------------
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1, uint32_t (&r)[4])
@@ -392,36 +673,6 @@ __device__ __forceinline__ double wave_inclusive_scan_f64(double x, uint32_t lan
 }
 
 // Ascending bitonic sort of one key per lane across the 64 lanes.
-constexpr int kDppRor8 = 0x128;   // rotate by 8 inside a row of 16 lanes: partner lane ^ 8
-constexpr int kDppRowShl4 = 0x104;  // lane i takes lane i + 4 of its row
-constexpr int kDppRowShr4 = 0x114;  // lane i takes lane i - 4 of its row
-
-// Value held by lane (lane ^ DIST).
-template <int DIST>
-__device__ __forceinline__ uint32_t lane_xor(uint32_t x, uint32_t lane)
-{
-    if constexpr (DIST == 1) {
-        return dpp_u32<kDppXor1>(x);
-    } else if constexpr (DIST == 2) {
-        return dpp_u32<kDppXor2>(x);
-    } else if constexpr (DIST == 4) {
-        // banks (groups of 4 lanes) 0 and 2 of every row take the lane 4 above, banks 1 and 3 the lane 4 below
-        int y = __builtin_amdgcn_update_dpp((int)x, (int)x, kDppRowShl4, 0xF, 0x5, false);
-        y = __builtin_amdgcn_update_dpp(y, (int)x, kDppRowShr4, 0xF, 0xA, false);
-        return (uint32_t)y;
-    } else if constexpr (DIST == 8) {
-        return dpp_u32<kDppRor8>(x);
-    } else if constexpr (DIST == 16) {
-        // rows (0,1) and (2,3) trade places
-        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-        return (lane & 16u) ? r[0] : r[1];
-    } else {
-        // the two halves of the wave trade places
-        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-        return (lane & 32u) ? r[0] : r[1];
-    }
-}
-
 template <int K, int DIST>
 __device__ __forceinline__ uint32_t bitonic_step(uint32_t x, uint32_t lane)
 {
@@ -1077,6 +1328,19 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
                            p->bucket_size, p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
 }
 
+void launch_bingrad_chunks(const float* g, uint32_t chunks, const ogq_params_t* p, float* lv, void* codes, hipStream_t st)
+{
+    const dim3 grid((chunks + kBinGradWaves - 1) / kBinGradWaves), block(kWave * kBinGradWaves);
+    uint64_t* words = static_cast<uint64_t*>(codes);
+    switch (kChunk / p->bucket_size) {
+        case 2: hipLaunchKernelGGL(bingrad_chunk_kernel<2>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
+        case 4: hipLaunchKernelGGL(bingrad_chunk_kernel<4>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
+        case 8: hipLaunchKernelGGL(bingrad_chunk_kernel<8>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
+        case 16: hipLaunchKernelGGL(bingrad_chunk_kernel<16>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
+        default: hipLaunchKernelGGL(bingrad_chunk_kernel<32>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
+    }
+}
+
 template <int C, int S, int BITS, bool PB = false>
 void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
@@ -1145,10 +1409,26 @@ int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params, floa
     if (!aligned(d_grad, 16) || !aligned(d_levels, 16) || !aligned(d_codes, 16)) return OGQ_ERR_ALIGNMENT;
     const size_t nb64 = ogq_num_buckets(n, params);
     if (nb64 >= (1ull << 31)) return OGQ_ERR_SIZE;
-    const uint32_t nb = (uint32_t)nb64;
+    uint32_t nb = (uint32_t)nb64;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const uint32_t d = params->bucket_size;
     if (params->scheme == OGQ_BINGRAD_B) {
+        // Whole chunks of 2048 elements go to the kernel that packs several buckets into a wavefront; what
+        // is left (fewer than 2048 elements) takes the one-bucket-per-wavefront kernel below.  Buckets of
+        // 512 and 1024 elements stay with that kernel for gradients too short to give every SIMD a chunk
+        // or two (it was the faster one below about four million elements).
+        const size_t chunks = n / kChunk;
+        if (params->clip_factor == 0.0f && d <= kChunk / 2 && kChunk % d == 0 && chunks > 0 &&
+            (d <= 256 || chunks >= kMinChunks)) {
+            launch_bingrad_chunks(d_grad, (uint32_t)chunks, params, d_levels, d_codes, st);
+            const size_t done = chunks * kChunk;
+            if (done == n) return finish_launch();
+            d_grad += done;
+            d_levels += done / d * 2;
+            d_codes = static_cast<uint64_t*>(d_codes) + done / 64;
+            n -= done;
+        }
+        nb = (uint32_t)ogq_num_buckets(n, params);
         const uint32_t regs = d / 64;
         if (regs <= 1) launch_bingrad<1>(d_grad, n, params, nb, d_levels, d_codes, st);
         else if (regs <= 2) launch_bingrad<2>(d_grad, n, params, nb, d_levels, d_codes, st);

@@ -34,16 +34,54 @@ def _rng_bucket(rng, n, kind):
 # ------------------------------------------------------------------------------------------------
 # small sizes: every element compared; several tiles and ragged tails
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("d", [64, 128, 192, 512, 2048, 4096])
+@pytest.mark.parametrize("d", [64, 128, 192, 256, 512, 1024, 2048, 4096])
 @pytest.mark.parametrize("kind", ["normal", "ints", "heavy", "shifted", "const", "zeros"])
 def test_bingrad_small(d, kind):
     rng = np.random.default_rng(d + len(kind))
-    for n in (1, 63, 64, 65, d - 1, d, d + 1, 5 * d + 37, 16 * d):
+    # bucket sizes dividing 2048 send whole 2048-element chunks and the rest to different kernels
+    for n in (1, 63, 64, 65, d - 1, d, d + 1, 5 * d + 37, 16 * d, 3 * 2048 + 2 * d + 11, 9 * 2048):
         if n < 1:
             continue
         g = _rng_bucket(rng, n, kind)
         for iters in (0, 1, 4):
             parity.check_quantize(g, d, 1, ogq.BINGRAD_B, iters, tag=f"bingrad-{kind}-d{d}-n{n}-it{iters}")
+
+
+@pytest.mark.parametrize("d", [64, 128, 256, 512, 1024])
+def test_bingrad_unlike_buckets_in_one_wavefront(d):
+    """Neighbouring buckets of one 2048-element chunk with nothing in common: constant, all equal but one,
+    one huge outlier, integers (the per-bucket special cases of the level solve)."""
+    rng = np.random.default_rng(77 + d)
+    kinds = ["const", "normal", "zeros", "heavy", "ints", "shifted"]
+    nb = (5 if d <= 256 else 2050) * (2048 // d) + 3
+    parts = []
+    for b in range(nb):
+        kind = kinds[int(rng.integers(len(kinds)))]
+        x = _rng_bucket(rng, d, kind)
+        r = b % 7
+        if r == 3:
+            x = np.full(d, 1e-3, np.float32)
+            x[int(rng.integers(d))] = 2.0
+        elif r == 5:
+            x = rng.normal(0, 1e-3, d).astype(np.float32)
+            x[int(rng.integers(d))] = -3000.0  # upper-side sum far below the largest magnitude
+        parts.append(x)
+    g = np.concatenate(parts)[: nb * d - 17]
+    for iters in (0, 3):
+        parity.check_quantize(g, d, 1, ogq.BINGRAD_B, iters, tag=f"bingrad-unlike-d{d}-it{iters}")
+
+
+@pytest.mark.parametrize("d", [512, 1024])
+def test_bingrad_several_buckets_per_wavefront_above_four_million_elements(d):
+    """Buckets of 512 and 1024 elements are packed several to a wavefront only for long gradients."""
+    rng = np.random.default_rng(d)
+    n = 2100 * 2048 + d + 77
+    g = (rng.standard_t(3, n) * 1e-3).astype(np.float32)
+    g[5 * d:6 * d] = 0.25          # a constant bucket
+    g[9 * d:10 * d] = rng.normal(0, 1e-3, d).astype(np.float32)
+    g[9 * d + 3] = -3000.0         # upper-side sum far below the largest magnitude
+    for iters in (0, 2):
+        parity.check_quantize(g, d, 1, ogq.BINGRAD_B, iters, tag=f"bingrad-long-d{d}-it{iters}")
 
 
 @pytest.mark.parametrize("bits", [1, 2, 3])
