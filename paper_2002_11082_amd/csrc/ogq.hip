@@ -1193,9 +1193,12 @@ __device__ __forceinline__ void load_levels(const float* __restrict__ table, flo
     for (int k = 0; k < S; ++k) asm("v_mov_b32 %0, %1" : "=v"(lv[k]) : "s"(s[k]));
 }
 
-// ONE_BUCKET: the 16 word groups of a span lie in one bucket (bucket_size is a multiple of 1024),
-// so each worker's level table is fetched once per span; otherwise once per word group.
-template <int BITS, int S, bool ONE_BUCKET>
+// WPB = packed word groups per bucket when the span splits into whole buckets at fixed places: 16 = the
+// span lies in one bucket (bucket_size is a multiple of 1024; its index is word0 / words_per_bucket),
+// 1, 2, 4 or 8 = bucket_size 64 .. 512, the span holds 16 / WPB buckets whose level tables are
+// consecutive in memory.  Each table is fetched once per span and worker.  WPB = 0: any other bucket
+// size, the table is looked up per word group.
+template <int BITS, int S, int WPB>
 __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs ptrs, uint32_t num_workers, size_t n,
                                                                     uint32_t words_per_bucket, uint32_t total_words,
                                                                     double inv_workers, float* __restrict__ out)
@@ -1216,16 +1219,28 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
     for (uint32_t w = 0; w < num_workers; ++w) {
         const uint64_t* __restrict__ cw = ptrs.codes[w] + (size_t)word0 * BITS;
         const float* __restrict__ table = ptrs.levels[w];
-        if constexpr (ONE_BUCKET) {
-            float lv[S];
-            load_levels<S>(table + (size_t)(word0 / words_per_bucket) * S, lv);
+        if constexpr (WPB > 0) {
+            constexpr int kTables = kSpanWords / WPB;
+            const uint32_t first_bucket = WPB == kSpanWords ? word0 / words_per_bucket : word0 / (uint32_t)WPB;
+            const float* __restrict__ first_table = table + (size_t)first_bucket * S;
             if (whole) {
 #pragma unroll
-                for (int j = 0; j < kSpanWords; ++j) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
+                for (int t = 0; t < kTables; ++t) {
+                    float lv[S];
+                    load_levels<S>(first_table + t * S, lv);
+#pragma unroll
+                    for (int j = t * WPB; j < (t + 1) * WPB; ++j) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
+                }
             } else {
 #pragma unroll
-                for (int j = 0; j < kSpanWords; ++j)
-                    if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
+                for (int t = 0; t < kTables; ++t)
+                    if ((uint32_t)(t * WPB) < n_words) {  // a bucket past the end has no table
+                        float lv[S];
+                        load_levels<S>(first_table + t * S, lv);
+#pragma unroll
+                        for (int j = t * WPB; j < (t + 1) * WPB; ++j)
+                            if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
+                    }
             }
         } else {
 #pragma unroll
@@ -1477,15 +1492,21 @@ int ogq_dequantize_average(const void* const* d_codes, const float* const* d_lev
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const double inv = 1.0 / (double)num_workers;
     const uint32_t wpb = d / 64;
-    const bool one_bucket = d % (kSpanWords * 64) == 0;
-#define OGQ_LAUNCH_DEQUANT(BITS, S)                                                                                   \
-    do {                                                                                                              \
-        if (one_bucket)                                                                                               \
-            hipLaunchKernelGGL((dequantize_average_kernel<BITS, S, true>), grid, block, 0, st, ptrs, num_workers, n,  \
-                               wpb, total_words, inv, d_out);                                                         \
-        else                                                                                                          \
-            hipLaunchKernelGGL((dequantize_average_kernel<BITS, S, false>), grid, block, 0, st, ptrs, num_workers, n, \
-                               wpb, total_words, inv, d_out);                                                         \
+    const uint32_t span_elements = kSpanWords * 64;
+    const uint32_t fixed_wpb = d % span_elements == 0 ? (uint32_t)kSpanWords : (span_elements % d == 0 ? wpb : 0u);
+#define OGQ_LAUNCH_DEQUANT_WPB(BITS, S, WPB)                                                                      \
+    hipLaunchKernelGGL((dequantize_average_kernel<BITS, S, WPB>), grid, block, 0, st, ptrs, num_workers, n, wpb, \
+                       total_words, inv, d_out)
+#define OGQ_LAUNCH_DEQUANT(BITS, S)                                \
+    do {                                                           \
+        switch (fixed_wpb) {                                       \
+            case 16: OGQ_LAUNCH_DEQUANT_WPB(BITS, S, 16); break;   \
+            case 8: OGQ_LAUNCH_DEQUANT_WPB(BITS, S, 8); break;     \
+            case 4: OGQ_LAUNCH_DEQUANT_WPB(BITS, S, 4); break;     \
+            case 2: OGQ_LAUNCH_DEQUANT_WPB(BITS, S, 2); break;     \
+            case 1: OGQ_LAUNCH_DEQUANT_WPB(BITS, S, 1); break;     \
+            default: OGQ_LAUNCH_DEQUANT_WPB(BITS, S, 0); break;    \
+        }                                                          \
     } while (0)
     switch (levels_per_bucket(params->scheme, params->bits)) {
         case 2: OGQ_LAUNCH_DEQUANT(1, 2); break;
@@ -1496,6 +1517,7 @@ int ogq_dequantize_average(const void* const* d_codes, const float* const* d_lev
         default: OGQ_LAUNCH_DEQUANT(4, 9); break;
     }
 #undef OGQ_LAUNCH_DEQUANT
+#undef OGQ_LAUNCH_DEQUANT_WPB
     return finish_launch();
 }
 

@@ -218,11 +218,12 @@ def test_empty_input_is_a_noop():
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("bits,scheme", [(1, ogq.BINGRAD_B), (1, ogq.BINGRAD_PB), (1, ogq.ORQ), (2, ogq.ORQ), (3, ogq.ORQ),
                                          (2, ogq.ORQ_PAPER), (3, ogq.ORQ_PAPER), (4, ogq.ORQ_PAPER)])
-@pytest.mark.parametrize("d", [64, 192, 1024, 1536, 2048, 4096])
+@pytest.mark.parametrize("d", [64, 128, 192, 256, 512, 1024, 1536, 2048, 4096])
 def test_decode_average_small(bits, scheme, d):
     rng = np.random.default_rng(bits * 1000 + d)
     stride = oracle.levels_per_bucket(scheme, bits)
-    for n in (1, 65, d, 2 * d + 63, 7 * d + 1):
+    # a wavefront decodes 1024 elements: whole spans and a ragged last one for every bucket size
+    for n in (1, 65, d, 2 * d + 63, 7 * d + 1, 3 * 1024 + 2 * d + 65):
         for W in (1, 2, 3, 8):
             gs = [_rng_bucket(rng, n, "heavy" if w % 2 else "normal") for w in range(W)]
             # oracle streams decoded by the oracle = expected; the same streams uploaded and decoded on the GPU
