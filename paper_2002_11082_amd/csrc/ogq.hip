@@ -146,24 +146,30 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t x, uint32_t lane)
 
 // Gradient clipping of a register-resident bucket (Section 5): v <- sign(v) * min(|v|, c * sigma) with
 // sigma^2 the population variance about the bucket mean, both in fp64.  valid(j) tells whether
-// register j of this lane holds a bucket element.
-template <int N, class ValidFn>
-__device__ __forceinline__ void clip_in_registers(float (&v)[N], uint32_t len, float c, ValidFn valid)
+// register j of this lane holds a bucket element; bucket_sum(x) adds x over all lanes that hold the bucket.
+template <int N, class ValidFn, class SumFn>
+__device__ __forceinline__ void clip_in_registers(float (&v)[N], uint32_t len, float c, ValidFn valid, SumFn bucket_sum)
 {
     double part = 0.0;
 #pragma unroll
     for (int j = 0; j < N; ++j) part += valid(j) ? (double)v[j] : 0.0;
-    const double mean = wave_sum(part) / (double)len;
+    const double mean = bucket_sum(part) / (double)len;
     part = 0.0;
 #pragma unroll
     for (int j = 0; j < N; ++j) {
         const double dv = (double)v[j] - mean;
         part += valid(j) ? dv * dv : 0.0;
     }
-    const double sigma = sqrt(wave_sum(part) / (double)len);
+    const double sigma = sqrt(bucket_sum(part) / (double)len);
     const float limit = (float)((double)c * sigma);
 #pragma unroll
     for (int j = 0; j < N; ++j) v[j] = fminf(fmaxf(v[j], -limit), limit);
+}
+
+template <int N, class ValidFn>
+__device__ __forceinline__ void clip_in_registers(float (&v)[N], uint32_t len, float c, ValidFn valid)
+{
+    clip_in_registers<N>(v, len, c, valid, [](double x) { return wave_sum(x); });
 }
 
 __device__ __forceinline__ uint32_t uniform_u32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -183,20 +189,81 @@ __device__ __forceinline__ double uniform_f64(double x)
 
 // ----------------------------------------------------------------------------------------------
 // BinGrad-b quantize.  Lane l register j holds bucket element 64*j + l, so a ballot over
-// register j is the packed code word j of the bucket.
+// register j is the packed code word j of the bucket.  A bucket is held by one wavefront, or by the
+// two wavefronts of a workgroup (elements 0..2047 and 2048..4095): the Team types say how a
+// wave-wide result becomes a bucket-wide one.
 // ----------------------------------------------------------------------------------------------
-template <int E, bool FULL, bool CLIP>
-__device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint32_t len, uint32_t iters, float clip,
-                                               float* __restrict__ levels2, uint64_t* __restrict__ words)
+struct OneWave {
+    __device__ __forceinline__ uint32_t first_element() const { return 0; }  // of the bucket, held by this wavefront
+    __device__ __forceinline__ bool leader() const { return true; }
+    __device__ __forceinline__ double sum(double x) { return x; }
+    __device__ __forceinline__ void sum_and_max(double&, float&) {}
+    __device__ __forceinline__ void sum_and_count(double&, uint32_t&) {}
+};
+
+// Both wavefronts call every combine in the same order (their control flow depends on combined values
+// only).  Two alternating LDS slots are enough: a wavefront that writes a slot for the second time has
+// passed the barrier in between, which the other one reaches only after it has read the first value.
+struct TeamSlot {
+    double sum;
+    uint32_t word;
+    uint32_t pad;
+};
+
+struct TwoWaves {
+    TeamSlot (*slots)[2];  // [2][2] in LDS: [call parity][wavefront]
+    uint32_t wave;
+    uint32_t calls;
+    __device__ __forceinline__ uint32_t first_element() const { return wave * 2048u; }
+    __device__ __forceinline__ bool leader() const { return wave == 0; }
+    __device__ __forceinline__ const TeamSlot* exchange(double sum, uint32_t word)
+    {
+        TeamSlot* slot = slots[calls & 1u];
+        ++calls;
+        if ((threadIdx.x & 63u) == 0) {
+            slot[wave].sum = sum;
+            slot[wave].word = word;
+        }
+        __syncthreads();
+        return slot;
+    }
+    __device__ __forceinline__ double sum(double x)
+    {
+        const TeamSlot* s = exchange(x, 0u);
+        return s[0].sum + s[1].sum;
+    }
+    __device__ __forceinline__ void sum_and_max(double& x, float& m)
+    {
+        const TeamSlot* s = exchange(x, __float_as_uint(m));
+        x = s[0].sum + s[1].sum;
+        m = fmaxf(__uint_as_float(s[0].word), __uint_as_float(s[1].word));
+    }
+    __device__ __forceinline__ void sum_and_count(double& x, uint32_t& c)
+    {
+        const TeamSlot* s = exchange(x, c);
+        x = s[0].sum + s[1].sum;
+        c = s[0].word + s[1].word;
+    }
+};
+
+// E registers per lane; FULL: every register of this wavefront holds a bucket element.  g, len, levels2
+// and words belong to the whole bucket.
+template <int E, bool FULL, bool CLIP, class Team>
+__device__ __forceinline__ void bingrad_bucket(Team team, const float* __restrict__ g, uint32_t len, uint32_t iters,
+                                               float clip, float* __restrict__ levels2, uint64_t* __restrict__ words)
 {
     const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t first = team.first_element() + lane;
     float v[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
-        const uint32_t e = 64u * j + lane;
+        const uint32_t e = first + 64u * j;
         v[j] = (FULL || e < len) ? __builtin_nontemporal_load(g + e) : 0.0f;  // read once: bypass the caches
     }
-    if constexpr (CLIP) clip_in_registers<E>(v, len, clip, [&](int j) { return FULL || (64u * j + lane < len); });
+    if constexpr (CLIP)
+        clip_in_registers<E>(
+            v, len, clip, [&](int j) { return FULL || (first + 64u * j < len); },
+            [&](double x) { return team.sum(wave_sum(x)); });
 
     double part = 0.0;
     float mag = 0.0f;
@@ -205,23 +272,25 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
         part += (double)v[j];
         mag = fmaxf(mag, fabsf(v[j]));
     }
-    const double total = wave_sum(part);
+    double total = wave_sum(part);
+    float largest = wave_max(mag);
+    team.sum_and_max(total, largest);
     float b0 = (float)(total / (double)len);  // threshold starts at the bucket mean
     // The upper sum is taken as total - lower sum.  Both are fp64 sums of at most 4096 fp32 values
     // (error below 2^-53 * n^2 * max|v| each, and exact for any bucket whose values span fewer than
     // ~18 binades), so the difference is trusted unless it is tiny against the largest element; such
     // a bucket sums its upper side directly.
-    const float trust_above = 1e-3f * wave_max(mag);
+    const float trust_above = 1e-3f * largest;
 
     double b_lo = 0.0, b_hi = 0.0;
-    uint32_t word_lo = 0, word_hi = 0;  // lane j ends up holding packed word j of the bucket
+    uint32_t word_lo = 0, word_hi = 0;  // lane j ends up holding packed word j of this wavefront's elements
     uint32_t prev_n_lo = 0xFFFFFFFFu;
     for (uint32_t it = 0;; ++it) {
         double s_lo = 0.0;
         uint32_t below = 0;
 #pragma unroll
         for (int j = 0; j < E; ++j) {
-            const bool valid = FULL || (64u * j + lane < len);
+            const bool valid = FULL || (first + 64u * j < len);
             const bool lo = valid && (v[j] < b0);
             const uint64_t lo_mask = __ballot(lo);
             const uint64_t hi_mask = FULL ? ~lo_mask : __ballot(valid && !lo);
@@ -231,16 +300,17 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
             word_hi = writelane(word_hi, (uint32_t)(hi_mask >> 32), j);
         }
         s_lo = wave_sum(s_lo);
-        const uint32_t n_lo = wave_sum_u32(below);
+        uint32_t n_lo = wave_sum_u32(below);
+        team.sum_and_count(s_lo, n_lo);
         double s_hi = total - s_lo;
         if (!(fabs(s_hi) >= (double)trust_above)) {
             double direct = 0.0;
 #pragma unroll
             for (int j = 0; j < E; ++j) {
-                const bool valid = FULL || (64u * j + lane < len);
+                const bool valid = FULL || (first + 64u * j < len);
                 direct += (double)((valid && !(v[j] < b0)) ? v[j] : 0.0f);
             }
-            s_hi = wave_sum(direct);
+            s_hi = team.sum(wave_sum(direct));
         }
         const uint32_t n_hi = len - n_lo;
         {
@@ -260,12 +330,13 @@ __device__ __forceinline__ void bingrad_bucket(const float* __restrict__ g, uint
         b0 = (float)((b_lo + b_hi) * 0.5);
     }
 
-    if (lane == 0) {
+    if (lane == 0 && team.leader()) {
         levels2[0] = (float)b_lo;
         levels2[1] = (float)b_hi;
     }
     const uint32_t n_words = (len + 63u) / 64u;
-    if (lane < n_words) words[lane] = ((uint64_t)word_hi << 32) | word_lo;
+    const uint32_t word = team.first_element() / 64u + lane;
+    if (lane < (uint32_t)E && word < n_words) words[word] = ((uint64_t)word_hi << 32) | word_lo;
 }
 
 constexpr int kBinGradWaves = 2;  // buckets per workgroup
@@ -274,8 +345,7 @@ constexpr int kBinGradWaves = 2;  // buckets per workgroup
 // compute in lock-step and the tail of a launch that is only ~1.5 waves of workgroups deep is not
 // overlapped.
 template <int E, bool CLIP>
-__global__ __launch_bounds__(kWave* kBinGradWaves)
-    __attribute__((amdgpu_waves_per_eu(E > 32 ? 2 : 4, 4))) void bingrad_quantize_kernel(
+__global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_quantize_kernel(
     const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, float clip, uint32_t num_buckets,
     float* __restrict__ levels, uint64_t* __restrict__ codes)
 {
@@ -287,8 +357,29 @@ __global__ __launch_bounds__(kWave* kBinGradWaves)
     const float* g = grad + begin;
     float* lv = levels + (size_t)bucket * 2;
     uint64_t* w = codes + begin / 64;
-    if (len == 64u * E) bingrad_bucket<E, true, CLIP>(g, len, iters, clip, lv, w);
-    else bingrad_bucket<E, false, CLIP>(g, len, iters, clip, lv, w);
+    if (len == 64u * E) bingrad_bucket<E, true, CLIP>(OneWave{}, g, len, iters, clip, lv, w);
+    else bingrad_bucket<E, false, CLIP>(OneWave{}, g, len, iters, clip, lv, w);
+}
+
+// Buckets of more than 2048 elements: the two wavefronts of a workgroup hold one bucket, 32 registers
+// per lane each as for a 2048-element bucket, and combine their sums and counts through LDS.
+template <bool CLIP>
+__global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_pair_kernel(
+    const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, float clip, uint32_t num_buckets,
+    float* __restrict__ levels, uint64_t* __restrict__ codes)
+{
+    __shared__ TeamSlot slots[2][2];
+    const uint32_t bucket = blockIdx.x;
+    if (bucket >= num_buckets) return;
+    const size_t begin = (size_t)bucket * bucket_size;
+    const size_t rest = n - begin;
+    const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
+    const float* g = grad + begin;
+    float* lv = levels + (size_t)bucket * 2;
+    uint64_t* w = codes + begin / 64;
+    const TwoWaves team{slots, uniform_u32(threadIdx.x >> 6), 0u};
+    if (len == 4096u) bingrad_bucket<32, true, CLIP>(team, g, len, iters, clip, lv, w);
+    else bingrad_bucket<32, false, CLIP>(team, g, len, iters, clip, lv, w);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1343,6 +1434,17 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
                            p->bucket_size, p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
 }
 
+void launch_bingrad_pairs(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                          hipStream_t st)
+{
+    if (p->clip_factor > 0.0f)
+        hipLaunchKernelGGL(bingrad_pair_kernel<true>, dim3(nb), dim3(2 * kWave), 0, st, g, n, p->bucket_size,
+                           p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
+    else
+        hipLaunchKernelGGL(bingrad_pair_kernel<false>, dim3(nb), dim3(2 * kWave), 0, st, g, n, p->bucket_size,
+                           p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
+}
+
 void launch_bingrad_chunks(const float* g, uint32_t chunks, const ogq_params_t* p, float* lv, void* codes, hipStream_t st)
 {
     const dim3 grid((chunks + kBinGradWaves - 1) / kBinGradWaves), block(kWave * kBinGradWaves);
@@ -1451,7 +1553,7 @@ int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params, floa
         else if (regs <= 8) launch_bingrad<8>(d_grad, n, params, nb, d_levels, d_codes, st);
         else if (regs <= 16) launch_bingrad<16>(d_grad, n, params, nb, d_levels, d_codes, st);
         else if (regs <= 32) launch_bingrad<32>(d_grad, n, params, nb, d_levels, d_codes, st);
-        else launch_bingrad<64>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else launch_bingrad_pairs(d_grad, n, params, nb, d_levels, d_codes, st);
     } else {
         const uint32_t chunks = (d + 255) / 256;
         if (chunks <= 1) launch_orq_levels<1>(d_grad, n, params, nb, d_levels, d_codes, st);

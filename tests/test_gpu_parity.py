@@ -34,7 +34,7 @@ def _rng_bucket(rng, n, kind):
 # ------------------------------------------------------------------------------------------------
 # small sizes: every element compared; several tiles and ragged tails
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("d", [64, 128, 192, 256, 512, 1024, 2048, 4096])
+@pytest.mark.parametrize("d", [64, 128, 192, 256, 512, 1024, 2048, 3072, 4096])
 @pytest.mark.parametrize("kind", ["normal", "ints", "heavy", "shifted", "const", "zeros"])
 def test_bingrad_small(d, kind):
     rng = np.random.default_rng(d + len(kind))
@@ -177,7 +177,7 @@ def test_orq_sweeps_and_offsets():
 def test_clipping_before_quantization(clip):
     rng = np.random.default_rng(int(clip * 10))
     for kind in ("normal", "heavy", "shifted", "const", "ints"):
-        for d, n in ((64, 200), (512, 5 * 512 + 77), (2048, 3 * 2048), (4096, 4096 + 5)):
+        for d, n in ((64, 200), (512, 5 * 512 + 77), (2048, 3 * 2048), (3072, 3 * 3072 + 2500), (4096, 2 * 4096 + 5)):
             g = _rng_bucket(rng, n, kind)
             parity.check_quantize(g, d, 1, ogq.BINGRAD_B, 1, clip_factor=clip, tag=f"clip{clip}-bingrad-{kind}-d{d}")
             for bits in (2, 3):
