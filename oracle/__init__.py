@@ -21,6 +21,9 @@ BINGRAD_B = 0
 ORQ = 1
 BINGRAD_PB = 2
 ORQ_PAPER = 3
+SCALED_SIGN = 4
+EVEN = 5
+LINEAR = 6
 
 
 def build(force: bool = False) -> str:
@@ -54,6 +57,12 @@ def lib() -> ctypes.CDLL:
         L.ogq_oracle_qstar.restype = ctypes.c_float
         L.ogq_oracle_orq_levels_bucket.argtypes = [vp, sz, u32, u32, vp]
         L.ogq_oracle_orq_levels_bucket.restype = None
+        L.ogq_oracle_scaled_sign_bucket.argtypes = [vp, sz, vp]
+        L.ogq_oracle_scaled_sign_bucket.restype = None
+        L.ogq_oracle_even_levels_bucket.argtypes = [vp, sz, u32, vp]
+        L.ogq_oracle_even_levels_bucket.restype = None
+        L.ogq_oracle_linear_levels_bucket.argtypes = [vp, sz, u32, vp]
+        L.ogq_oracle_linear_levels_bucket.restype = None
         L.ogq_oracle_orq_encode_element.argtypes = [ctypes.c_float, vp, u32, ctypes.c_float]
         L.ogq_oracle_orq_encode_element.restype = u32
         L.ogq_oracle_pack.argtypes = [vp, sz, u32, vp]
@@ -122,6 +131,27 @@ def orq_levels_bucket(g, s: int, sweeps: int = 0) -> np.ndarray:
     g = _f32(g)
     levels = np.zeros(s, dtype=np.float32)
     lib().ogq_oracle_orq_levels_bucket(_ptr(g), g.size, s, sweeps, _ptr(levels))
+    return levels
+
+
+def scaled_sign_bucket(g) -> np.ndarray:
+    g = _f32(g)
+    levels = np.zeros(2, dtype=np.float32)
+    lib().ogq_oracle_scaled_sign_bucket(_ptr(g), g.size, _ptr(levels))
+    return levels
+
+
+def even_levels_bucket(g, s: int) -> np.ndarray:
+    g = _f32(g)
+    levels = np.zeros(s, dtype=np.float32)
+    lib().ogq_oracle_even_levels_bucket(_ptr(g), g.size, s, _ptr(levels))
+    return levels
+
+
+def linear_levels_bucket(g, s: int) -> np.ndarray:
+    g = _f32(g)
+    levels = np.zeros(s, dtype=np.float32)
+    lib().ogq_oracle_linear_levels_bucket(_ptr(g), g.size, s, _ptr(levels))
     return levels
 
 

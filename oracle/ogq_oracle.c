@@ -18,7 +18,9 @@
  * conditional means, reduce to Scaled SignSGD on +-paired data and converge to 1-D 2-means;
  * random rounding is unbiased with variance (v-b_k)(b_{k+1}-v) by Monte Carlo; pack/unpack
  * round trip and hand-placed bits; decode-average special cases; clipping against a hand example,
- * the library standard deviation and its limiting cases.
+ * the library standard deviation and its limiting cases; the comparison rules against their
+ * closed forms (mean magnitude, TernGrad's {-max, 0, +max}, numpy's lower quantiles) and the
+ * ordering of the quantization errors the paper reports.
  * No function here is "parity unpinned".
  *
  * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC ogq_oracle.c -o libogq_oracle.so -lm
@@ -32,15 +34,20 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_BINGRAD_B = 0, ORACLE_ORQ = 1, ORACLE_BINGRAD_PB = 2, ORACLE_ORQ_PAPER = 3 };
+enum { ORACLE_BINGRAD_B = 0, ORACLE_ORQ = 1, ORACLE_BINGRAD_PB = 2, ORACLE_ORQ_PAPER = 3,
+       ORACLE_SCALED_SIGN = 4, ORACLE_EVEN = 5, ORACLE_LINEAR = 6 };
 
-/* Levels per bucket: BinGrad-b 2; ORQ 2^bits; ORQ with the paper's level counts s = 2^K + 1
- * (Algorithm 1: 3, 5, 9 levels), whose indices need bits = K + 1 bits.  0 = bad combination. */
+/* Levels per bucket: BinGrad-b, BinGrad-pb and Scaled SignSGD 2; ORQ 2^bits; ORQ with the paper's
+ * level counts s = 2^K + 1 (Algorithm 1: 3, 5, 9 levels), whose indices need bits = K + 1 bits, and
+ * the same counts for the evenly spaced (QSGD-s, TernGrad) and Linear-s comparison rules.
+ * 0 = bad combination. */
 uint32_t ogq_oracle_levels_per_bucket(uint32_t scheme, uint32_t bits)
 {
-    if (scheme == ORACLE_BINGRAD_B || scheme == ORACLE_BINGRAD_PB) return bits == 1 ? 2u : 0u;
+    if (scheme == ORACLE_BINGRAD_B || scheme == ORACLE_BINGRAD_PB || scheme == ORACLE_SCALED_SIGN)
+        return bits == 1 ? 2u : 0u;
     if (scheme == ORACLE_ORQ) return (bits >= 1 && bits <= 8) ? 1u << bits : 0u;
-    if (scheme == ORACLE_ORQ_PAPER) return (bits >= 2 && bits <= 8) ? (1u << (bits - 1)) + 1u : 0u;
+    if (scheme == ORACLE_ORQ_PAPER || scheme == ORACLE_EVEN || scheme == ORACLE_LINEAR)
+        return (bits >= 2 && bits <= 8) ? (1u << (bits - 1)) + 1u : 0u;
     return 0u;
 }
 
@@ -219,6 +226,49 @@ void ogq_oracle_orq_levels_bucket(const float* g, size_t n, uint32_t s, uint32_t
     free(x);
 }
 
+/* ------------------------------------------------------------------------------------------
+ * The level rules the paper compares against (Section 5, list of methods), per bucket.  They
+ * feed the same random rounding, packing and decoding as ORQ.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Scaled SignSGD (first equation of Section 3.2): Q(G) = (||G||_1 / dim G) * sign(G).  As a
+ * two-level code: levels {-m, +m} with m = mean |v| (fp64 sum in index order, rounded to fp32
+ * once); the code of an element is 1 when v >= 0 (reading: a zero, whose sign the formula leaves
+ * at 0, goes to +m, since two levels have no zero). */
+void ogq_oracle_scaled_sign_bucket(const float* g, size_t n, float levels[2])
+{
+    double sum = 0.0;
+    for (size_t i = 0; i < n; ++i) sum += fabs((double)g[i]);
+    float m = (float)(sum / (double)n);
+    levels[0] = -m;
+    levels[1] = m;
+}
+
+/* QSGD-s and TernGrad (Section 3.1, the paragraph after the random-rounding equation): s levels
+ * evenly spaced from -||G|| to +||G||.  Reading: ||G|| is the largest magnitude M of the bucket
+ * (TernGrad's scaler; any larger norm would only widen every interval), s is odd so that 0 is a
+ * level, and b_k = M * (2k - (s-1)) / (s-1), k = 0..s-1, in fp64 rounded to fp32 once. */
+void ogq_oracle_even_levels_bucket(const float* g, size_t n, uint32_t s, float* levels)
+{
+    double M = 0.0;
+    for (size_t i = 0; i < n; ++i) if (fabs((double)g[i]) > M) M = fabs((double)g[i]);
+    for (uint32_t k = 0; k < s; ++k)
+        levels[k] = (float)(M * ((double)(2 * (long long)k) - (double)(s - 1)) / (double)(s - 1));
+}
+
+/* Linear-s (Section 5): s levels that divide the bucket's cumulative distribution linearly.
+ * Reading: level k is the order statistic at the fraction k/(s-1) of the sorted bucket,
+ * x_(floor(k (n-1) / (s-1))) with 0-based ranks, so that level 0 is the minimum and level s-1
+ * the maximum and random rounding is defined for every element. */
+void ogq_oracle_linear_levels_bucket(const float* g, size_t n, uint32_t s, float* levels)
+{
+    float* x = (float*)malloc(n * sizeof(float));
+    memcpy(x, g, n * sizeof(float));
+    qsort(x, n, sizeof(float), cmp_float_asc);
+    for (uint32_t k = 0; k < s; ++k) levels[k] = x[(size_t)(((unsigned long long)k * (n - 1)) / (s - 1))];
+    free(x);
+}
+
 /* Random rounding of one element (Section 3.1): v in [b_k, b_{k+1}] goes up to b_{k+1} with
  * probability (v-b_k)/(b_{k+1}-b_k).  k is the last level not above v (at most s-2); the
  * probability test is the division-free u*w < delta, in fp32, one rounding per operation. */
@@ -310,12 +360,20 @@ int ogq_oracle_quantize_codes(const float* g, size_t n, uint32_t bucket_size, ui
             ogq_oracle_bingrad_bucket(gb, len, level_iters, lv, &b0);
             if (thresholds) thresholds[b] = b0;
             for (size_t i = 0; i < len; ++i) codes[begin + i] = gb[i] >= b0 ? 1 : 0;
+        } else if (scheme == ORACLE_SCALED_SIGN) {
+            ogq_oracle_scaled_sign_bucket(gb, len, lv);
+            if (thresholds) thresholds[b] = 0.0f;
+            for (size_t i = 0; i < len; ++i) codes[begin + i] = gb[i] >= 0.0f ? 1 : 0;
         } else {
             if (scheme == ORACLE_BINGRAD_PB) {
                 float b1 = ogq_oracle_bingrad_pb_level(gb, len);
                 lv[0] = -b1;
                 lv[1] = b1;
                 if (thresholds) thresholds[b] = b1;
+            } else if (scheme == ORACLE_EVEN) {
+                ogq_oracle_even_levels_bucket(gb, len, s, lv);
+            } else if (scheme == ORACLE_LINEAR) {
+                ogq_oracle_linear_levels_bucket(gb, len, s, lv);
             } else {
                 ogq_oracle_orq_levels_bucket(gb, len, s, level_iters, lv);
             }
