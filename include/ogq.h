@@ -64,7 +64,20 @@ typedef enum {
     /* ORQ with the paper's level counts s = 2^K + 1 (Algorithm 1's initialisation: 3, 5 or 9 levels);
      * bits = K + 1 in 2..4 is the width of a level index.  With level_iters = 0 the levels are those of
      * Algorithm 1 as printed.  Encoding and packing as for OGQ_ORQ. */
-    OGQ_ORQ_PAPER = 3
+    OGQ_ORQ_PAPER = 3,
+    /* The level rules the paper compares against (Section 5, list of methods), on the same kernels, so that
+     * their quantization error can be set beside ORQ's and BinGrad's on equal inputs.  level_iters is ignored.
+     * Scaled SignSGD (first equation of Section 3.2), per bucket: two levels -m, +m, m = mean |v| (fp64 sum,
+     * rounded to fp32); index = (v >= 0), deterministic.  bits must be 1. */
+    OGQ_SCALED_SIGN = 4,
+    /* QSGD-s / TernGrad (Section 3.1): s = 2^(bits-1) + 1 levels evenly spaced from -M to +M, M the largest
+     * magnitude of the bucket: level k = M * (2k - (s-1)) / (s-1) (fp64, rounded to fp32); bits in 2..4
+     * (bits = 2 is TernGrad's {-M, 0, +M}).  Random rounding, encoding and packing as for OGQ_ORQ. */
+    OGQ_EVEN = 5,
+    /* Linear-s (Section 5): s = 2^(bits-1) + 1 levels dividing the bucket's cumulative distribution linearly:
+     * level k is the element of 0-based rank floor(k * (len-1) / (s-1)) of the sorted bucket (level 0 the
+     * minimum, level s-1 the maximum); bits in 2..4.  Random rounding, encoding and packing as for OGQ_ORQ. */
+    OGQ_LINEAR = 6
 } ogq_scheme_t;
 
 #define OGQ_MAX_WORKERS 64u
@@ -78,8 +91,8 @@ typedef struct {
      * mean (0 = the paper's shortcut).  ORQ: number of sweeps that re-solve every interior level
      * between its current neighbours after the greedy placement. */
     uint32_t level_iters;
-    uint64_t seed;         /* Philox key (ORQ only) */
-    /* Global index of d_grad[0] (ORQ only; a multiple of 64): element i draws the random number
+    uint64_t seed;         /* Philox key (schemes with random rounding) */
+    /* Global index of d_grad[0] (schemes with random rounding; a multiple of 64): element i draws the random number
      * that belongs to global index index_offset + i, so a bucket-aligned shard reproduces the
      * codes of the full vector. */
     uint64_t index_offset;
@@ -92,7 +105,7 @@ typedef struct {
 } ogq_params_t;
 
 /* Sizes of the outputs of ogq_quantize for a gradient of n elements (pure host arithmetic).
- *   levels_per_bucket = 2 (BINGRAD_B, BINGRAD_PB), 2^bits (ORQ), 2^(bits-1) + 1 (ORQ_PAPER)
+ *   levels_per_bucket = 2 (BINGRAD_B, BINGRAD_PB, SCALED_SIGN), 2^bits (ORQ), 2^(bits-1) + 1 (ORQ_PAPER, EVEN, LINEAR)
  *   num_buckets       = ceil(n / bucket_size)
  *   levels_count      = num_buckets * levels_per_bucket    fp32 values
  *   codes_bytes       = ceil(n / 64) * bits * 8            bytes

@@ -12,6 +12,9 @@ BINGRAD_B = 0
 ORQ = 1
 BINGRAD_PB = 2
 ORQ_PAPER = 3
+SCALED_SIGN = 4
+EVEN = 5
+LINEAR = 6
 MAX_WORKERS = 64
 PROBE_SINK_FLOATS = 8192
 

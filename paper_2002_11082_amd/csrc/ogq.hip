@@ -247,8 +247,9 @@ struct TwoWaves {
 };
 
 // E registers per lane; FULL: every register of this wavefront holds a bucket element.  g, len, levels2
-// and words belong to the whole bucket.
-template <int E, bool FULL, bool CLIP, class Team>
+// and words belong to the whole bucket.  SIGN: Scaled SignSGD instead (first equation of Section 3.2):
+// levels -m, +m with m the mean magnitude of the bucket, index = (v >= 0).
+template <int E, bool FULL, bool CLIP, bool SIGN, class Team>
 __device__ __forceinline__ void bingrad_bucket(Team team, const float* __restrict__ g, uint32_t len, uint32_t iters,
                                                float clip, float* __restrict__ levels2, uint64_t* __restrict__ words)
 {
@@ -269,7 +270,7 @@ __device__ __forceinline__ void bingrad_bucket(Team team, const float* __restric
     float mag = 0.0f;
 #pragma unroll
     for (int j = 0; j < E; ++j) {
-        part += (double)v[j];
+        part += (double)(SIGN ? fabsf(v[j]) : v[j]);
         mag = fmaxf(mag, fabsf(v[j]));
     }
     double total = wave_sum(part);
@@ -285,6 +286,17 @@ __device__ __forceinline__ void bingrad_bucket(Team team, const float* __restric
     double b_lo = 0.0, b_hi = 0.0;
     uint32_t word_lo = 0, word_hi = 0;  // lane j ends up holding packed word j of this wavefront's elements
     uint32_t prev_n_lo = 0xFFFFFFFFu;
+    if constexpr (SIGN) {
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            const bool valid = FULL || (first + 64u * j < len);
+            const uint64_t hi_mask = __ballot(valid && !(v[j] < 0.0f));
+            word_lo = writelane(word_lo, (uint32_t)hi_mask, j);
+            word_hi = writelane(word_hi, (uint32_t)(hi_mask >> 32), j);
+        }
+        b_hi = total / (double)len;
+        b_lo = -b_hi;
+    } else
     for (uint32_t it = 0;; ++it) {
         double s_lo = 0.0;
         uint32_t below = 0;
@@ -344,7 +356,7 @@ constexpr int kBinGradWaves = 2;  // buckets per workgroup
 // At most 4 waves per SIMD and small workgroups: with more, all resident waves load and then
 // compute in lock-step and the tail of a launch that is only ~1.5 waves of workgroups deep is not
 // overlapped.
-template <int E, bool CLIP>
+template <int E, bool CLIP, bool SIGN>
 __global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_quantize_kernel(
     const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, float clip, uint32_t num_buckets,
     float* __restrict__ levels, uint64_t* __restrict__ codes)
@@ -357,13 +369,13 @@ __global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_p
     const float* g = grad + begin;
     float* lv = levels + (size_t)bucket * 2;
     uint64_t* w = codes + begin / 64;
-    if (len == 64u * E) bingrad_bucket<E, true, CLIP>(OneWave{}, g, len, iters, clip, lv, w);
-    else bingrad_bucket<E, false, CLIP>(OneWave{}, g, len, iters, clip, lv, w);
+    if (len == 64u * E) bingrad_bucket<E, true, CLIP, SIGN>(OneWave{}, g, len, iters, clip, lv, w);
+    else bingrad_bucket<E, false, CLIP, SIGN>(OneWave{}, g, len, iters, clip, lv, w);
 }
 
 // Buckets of more than 2048 elements: the two wavefronts of a workgroup hold one bucket, 32 registers
 // per lane each as for a 2048-element bucket, and combine their sums and counts through LDS.
-template <bool CLIP>
+template <bool CLIP, bool SIGN>
 __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_pair_kernel(
     const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, float clip, uint32_t num_buckets,
     float* __restrict__ levels, uint64_t* __restrict__ codes)
@@ -378,8 +390,8 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(4, 4)
     float* lv = levels + (size_t)bucket * 2;
     uint64_t* w = codes + begin / 64;
     const TwoWaves team{slots, uniform_u32(threadIdx.x >> 6), 0u};
-    if (len == 4096u) bingrad_bucket<32, true, CLIP>(team, g, len, iters, clip, lv, w);
-    else bingrad_bucket<32, false, CLIP>(team, g, len, iters, clip, lv, w);
+    if (len == 4096u) bingrad_bucket<32, true, CLIP, SIGN>(team, g, len, iters, clip, lv, w);
+    else bingrad_bucket<32, false, CLIP, SIGN>(team, g, len, iters, clip, lv, w);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -523,7 +535,7 @@ constexpr uint32_t reverse6(uint32_t x)
 constexpr uint32_t kChunk = 2048;  // elements one wavefront of the kernel below quantizes
 constexpr uint32_t kMinChunks = 2048;
 
-template <int NB>
+template <int NB, bool SIGN>
 __global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_chunk_kernel(
     const float* __restrict__ grad, uint32_t num_chunks, uint32_t iters, float* __restrict__ levels,
     uint64_t* __restrict__ codes)
@@ -548,7 +560,10 @@ __global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_p
         [&](auto q) {
             double s = 0.0;
 #pragma unroll
-            for (int j = 0; j < E; ++j) s += (double)v[decltype(q)::value * E + j];
+            for (int j = 0; j < E; ++j) {
+                const float x = v[decltype(q)::value * E + j];
+                s += (double)(SIGN ? fabsf(x) : x);
+            }
             return s;
         },
         add);
@@ -568,6 +583,16 @@ __global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_p
     double b_lo = 0.0, b_hi = 0.0;
     uint32_t word_lo = 0, word_hi = 0;  // lane j ends up holding packed word j of the chunk
     uint32_t prev_n_lo = 0xFFFFFFFFu;
+    if constexpr (SIGN) {  // Scaled SignSGD: see bingrad_bucket
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const uint64_t hi_mask = ~__ballot(v[j] < 0.0f);
+            word_lo = writelane(word_lo, (uint32_t)hi_mask, j);
+            word_hi = writelane(word_hi, (uint32_t)(hi_mask >> 32), j);
+        }
+        b_hi = total / (double)D;
+        b_lo = -b_hi;
+    } else
     for (uint32_t it = 0;; ++it) {
         uint32_t n_lo = 0;
         const double s_lo = reduce_buckets<NB, double>(
@@ -884,11 +909,17 @@ struct OrqShape {
     static constexpr int SHIFT = C >= 16 ? 19 : 20; // magnitude bits dropped: keeps exponent + 4 (3) mantissa bits
 };
 
+// Where the levels come from; all rules share the random-rounding encoder.
+//   kOptimal: ORQ (Theorem 1, Algorithm 1).
+//   kPb: BinGrad-pb (Section 3.2): two levels -b_1, +b_1 from the scheme's optimal condition instead of the
+//        bucket extremes; the encoder then clamps everything outside them.
+//   kEven: QSGD-s / TernGrad (Section 3.1): S levels evenly spaced from -M to +M, M the largest magnitude.
+//   kLinear: Linear-s (Section 5): the order statistics at the fractions k/(S-1) of the sorted bucket.
+enum LevelRule { kOptimal = 0, kPb = 1, kEven = 2, kLinear = 3 };
+
 // FULL: the bucket has exactly 256*C elements (no padding, no per-element validity tests).
 // S levels per bucket, BITS bits per level index (S = 2^BITS, or 2^(BITS-1) + 1 for the paper's counts).
-// PB: BinGrad-pb (Section 3.2): two levels -b_1, +b_1 from the scheme's optimal condition instead of
-// the bucket extremes; the random-rounding encoder then clamps everything outside them.
-template <int C, int S, int BITS, bool FULL, bool CLIP, bool PB>
+template <int C, int S, int BITS, bool FULL, bool CLIP, int RULE>
 __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B>& lds, const float* __restrict__ g,
                                            uint32_t len, size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
                                            uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
@@ -901,6 +932,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     constexpr int HALF = B / 2;   // bins per sign
     constexpr int SHIFT = OrqShape<C>::SHIFT;
     constexpr bool full = FULL;
+    constexpr bool PB = RULE == kPb;
     const uint32_t lane = threadIdx.x & 63u;
 
     // ---- load (read once: bypass the caches); padding holds +0 and is never binned or encoded ----
@@ -946,7 +978,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
 
     float pb_level = 0.0f;
-    if constexpr (S > 2 || PB) {
+    if constexpr ((S > 2 && RULE != kEven) || PB) {
         // ---- histogram: the returning LDS add hands every element its position inside its bin ------
 #pragma unroll
         for (int t = 0; t < PER; ++t) lds.bin_start[lane * PER + t] = 0u;
@@ -1068,8 +1100,18 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
             }
         }
 
+        if constexpr (RULE == kLinear) {
+            for (uint32_t k = 1; k + 1 < (uint32_t)S; ++k) {
+                const uint32_t rank = 1u + (uint32_t)(((uint64_t)k * (len - 1u)) / (uint32_t)(S - 1));
+                const Picked p = pick_rank<D, B>(lds, my_start, rank, lane);
+                if (lane == 0u) lds.lvl_value[k] = key_to_float(p.key);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+
         // ---- level solves: greedy recursion (Algorithm 1), then re-solve sweeps ------------------
-        if constexpr (S > 2) {
+        if constexpr (S > 2 && RULE == kOptimal) {
         constexpr GreedyOrder order = greedy_order<S>();
         const uint32_t steps = order.count + sweeps * (S - 2);
         for (uint32_t step = 0; step < steps; ++step) {
@@ -1130,10 +1172,16 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
 
     // every lane holds its own copy of the levels (the selects of the encoder take vector sources)
     float lv[S];
-    lv[0] = PB ? -pb_level : key_to_float(key_min);
-    lv[S - 1] = PB ? pb_level : key_to_float(key_max);
+    if constexpr (RULE == kEven) {
+        const double largest = (double)__uint_as_float(mag_max);
 #pragma unroll
-    for (int k = 1; k < S - 1; ++k) lv[k] = lds.lvl_value[k];
+        for (int k = 0; k < S; ++k) lv[k] = (float)(largest * (double)(2 * k - (S - 1)) / (double)(S - 1));
+    } else {
+        lv[0] = PB ? -pb_level : key_to_float(key_min);
+        lv[S - 1] = PB ? pb_level : key_to_float(key_max);
+#pragma unroll
+        for (int k = 1; k < S - 1; ++k) lv[k] = lds.lvl_value[k];
+    }
 
     if (lane == 0) {
 #pragma unroll
@@ -1211,7 +1259,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     }
 }
 
-template <int C, int S, int BITS, bool CLIP, bool PB>
+template <int C, int S, int BITS, bool CLIP, int RULE>
 __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
                                                              uint32_t bucket_size, uint32_t sweeps, float clip,
                                                              uint32_t num_buckets, uint64_t seed,
@@ -1225,9 +1273,9 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
     const size_t rest = n - begin;
     const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
     if (len == (uint32_t)OrqShape<C>::D)
-        orq_bucket<C, S, BITS, true, CLIP, PB>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+        orq_bucket<C, S, BITS, true, CLIP, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
     else
-        orq_bucket<C, S, BITS, false, CLIP, PB>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+        orq_bucket<C, S, BITS, false, CLIP, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1388,9 +1436,10 @@ __global__ __launch_bounds__(kBlock) void probe_copy_kernel(const float4* __rest
 // Levels per bucket, 0 for a scheme / bits combination that does not exist.
 uint32_t levels_per_bucket(uint32_t scheme, uint32_t bits)
 {
-    if (scheme == OGQ_BINGRAD_B || scheme == OGQ_BINGRAD_PB) return bits == 1 ? 2u : 0u;
+    if (scheme == OGQ_BINGRAD_B || scheme == OGQ_BINGRAD_PB || scheme == OGQ_SCALED_SIGN) return bits == 1 ? 2u : 0u;
     if (scheme == OGQ_ORQ) return (bits >= 1 && bits <= 3) ? 1u << bits : 0u;
-    if (scheme == OGQ_ORQ_PAPER) return (bits >= 2 && bits <= 4) ? (1u << (bits - 1)) + 1u : 0u;
+    if (scheme == OGQ_ORQ_PAPER || scheme == OGQ_EVEN || scheme == OGQ_LINEAR)
+        return (bits >= 2 && bits <= 4) ? (1u << (bits - 1)) + 1u : 0u;
     return 0u;
 }
 
@@ -1401,8 +1450,7 @@ int check_params(const ogq_params_t* p, bool quantize)
     if (!p) return OGQ_ERR_NULL_POINTER;
     if (p->bucket_size == 0 || p->bucket_size % 64 != 0 || p->bucket_size > OGQ_MAX_BUCKET_SIZE)
         return OGQ_ERR_BUCKET_SIZE;
-    if (p->scheme != OGQ_BINGRAD_B && p->scheme != OGQ_ORQ && p->scheme != OGQ_BINGRAD_PB && p->scheme != OGQ_ORQ_PAPER)
-        return OGQ_ERR_SCHEME;
+    if (p->scheme > OGQ_LINEAR) return OGQ_ERR_SCHEME;
     if (levels_per_bucket(p->scheme, p->bits) == 0) return OGQ_ERR_BITS;
     if (quantize) {
         if (p->index_offset % 64 != 0) return OGQ_ERR_INDEX_OFFSET;
@@ -1425,70 +1473,102 @@ template <int E>
 void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                     hipStream_t st)
 {
-    const uint32_t blocks = (nb + kBinGradWaves - 1) / kBinGradWaves;
-    if (p->clip_factor > 0.0f)
-        hipLaunchKernelGGL((bingrad_quantize_kernel<E, true>), dim3(blocks), dim3(kWave * kBinGradWaves), 0, st, g, n,
-                           p->bucket_size, p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
-    else
-        hipLaunchKernelGGL((bingrad_quantize_kernel<E, false>), dim3(blocks), dim3(kWave * kBinGradWaves), 0, st, g, n,
-                           p->bucket_size, p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
+    const dim3 grid((nb + kBinGradWaves - 1) / kBinGradWaves), block(kWave * kBinGradWaves);
+    const bool clip = p->clip_factor > 0.0f, sign = p->scheme == OGQ_SCALED_SIGN;
+#define OGQ_LAUNCH(CLIP, SIGN)                                                                                        \
+    hipLaunchKernelGGL((bingrad_quantize_kernel<E, CLIP, SIGN>), grid, block, 0, st, g, n, p->bucket_size,           \
+                       p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes))
+    if (sign) {
+        if (clip) OGQ_LAUNCH(true, true);
+        else OGQ_LAUNCH(false, true);
+    } else {
+        if (clip) OGQ_LAUNCH(true, false);
+        else OGQ_LAUNCH(false, false);
+    }
+#undef OGQ_LAUNCH
 }
 
 void launch_bingrad_pairs(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                           hipStream_t st)
 {
-    if (p->clip_factor > 0.0f)
-        hipLaunchKernelGGL(bingrad_pair_kernel<true>, dim3(nb), dim3(2 * kWave), 0, st, g, n, p->bucket_size,
-                           p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
+    const dim3 grid(nb), block(2 * kWave);
+    const bool clip = p->clip_factor > 0.0f, sign = p->scheme == OGQ_SCALED_SIGN;
+#define OGQ_LAUNCH(CLIP, SIGN)                                                                               \
+    hipLaunchKernelGGL((bingrad_pair_kernel<CLIP, SIGN>), grid, block, 0, st, g, n, p->bucket_size,         \
+                       p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes))
+    if (sign) {
+        if (clip) OGQ_LAUNCH(true, true);
+        else OGQ_LAUNCH(false, true);
+    } else {
+        if (clip) OGQ_LAUNCH(true, false);
+        else OGQ_LAUNCH(false, false);
+    }
+#undef OGQ_LAUNCH
+}
+
+template <int NB>
+void launch_bingrad_chunks_of(const float* g, uint32_t chunks, const ogq_params_t* p, float* lv, uint64_t* words,
+                              hipStream_t st)
+{
+    const dim3 grid((chunks + kBinGradWaves - 1) / kBinGradWaves), block(kWave * kBinGradWaves);
+    if (p->scheme == OGQ_SCALED_SIGN)
+        hipLaunchKernelGGL((bingrad_chunk_kernel<NB, true>), grid, block, 0, st, g, chunks, p->level_iters, lv, words);
     else
-        hipLaunchKernelGGL(bingrad_pair_kernel<false>, dim3(nb), dim3(2 * kWave), 0, st, g, n, p->bucket_size,
-                           p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes));
+        hipLaunchKernelGGL((bingrad_chunk_kernel<NB, false>), grid, block, 0, st, g, chunks, p->level_iters, lv, words);
 }
 
 void launch_bingrad_chunks(const float* g, uint32_t chunks, const ogq_params_t* p, float* lv, void* codes, hipStream_t st)
 {
-    const dim3 grid((chunks + kBinGradWaves - 1) / kBinGradWaves), block(kWave * kBinGradWaves);
     uint64_t* words = static_cast<uint64_t*>(codes);
     switch (kChunk / p->bucket_size) {
-        case 2: hipLaunchKernelGGL(bingrad_chunk_kernel<2>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
-        case 4: hipLaunchKernelGGL(bingrad_chunk_kernel<4>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
-        case 8: hipLaunchKernelGGL(bingrad_chunk_kernel<8>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
-        case 16: hipLaunchKernelGGL(bingrad_chunk_kernel<16>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
-        default: hipLaunchKernelGGL(bingrad_chunk_kernel<32>, grid, block, 0, st, g, chunks, p->level_iters, lv, words); break;
+        case 2: launch_bingrad_chunks_of<2>(g, chunks, p, lv, words, st); break;
+        case 4: launch_bingrad_chunks_of<4>(g, chunks, p, lv, words, st); break;
+        case 8: launch_bingrad_chunks_of<8>(g, chunks, p, lv, words, st); break;
+        case 16: launch_bingrad_chunks_of<16>(g, chunks, p, lv, words, st); break;
+        default: launch_bingrad_chunks_of<32>(g, chunks, p, lv, words, st); break;
     }
 }
 
-template <int C, int S, int BITS, bool PB = false>
+template <int C, int S, int BITS, int RULE = kOptimal>
 void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
     if (p->clip_factor > 0.0f)
-        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, true, PB>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, true, RULE>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
                            p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
                            static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, false, PB>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, false, RULE>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
                            p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
                            static_cast<uint32_t*>(codes));
+}
+
+template <int C, int RULE>
+void launch_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                         hipStream_t st)
+{
+    switch (p->bits) {  // 2^(bits-1) + 1 levels
+        case 2: launch_orq<C, 3, 2, RULE>(g, n, p, nb, lv, codes, st); break;
+        case 3: launch_orq<C, 5, 3, RULE>(g, n, p, nb, lv, codes, st); break;
+        default: launch_orq<C, 9, 4, RULE>(g, n, p, nb, lv, codes, st); break;
+    }
 }
 
 template <int C>
 void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                        hipStream_t st)
 {
-    if (p->scheme == OGQ_BINGRAD_PB) {
-        launch_orq<C, 2, 1, true>(g, n, p, nb, lv, codes, st);
-    } else if (p->scheme == OGQ_ORQ) {
-        switch (p->bits) {
-            case 1: launch_orq<C, 2, 1>(g, n, p, nb, lv, codes, st); break;
-            case 2: launch_orq<C, 4, 2>(g, n, p, nb, lv, codes, st); break;
-            default: launch_orq<C, 8, 3>(g, n, p, nb, lv, codes, st); break;
-        }
-    } else {  // OGQ_ORQ_PAPER: 2^(bits-1) + 1 levels
-        switch (p->bits) {
-            case 2: launch_orq<C, 3, 2>(g, n, p, nb, lv, codes, st); break;
-            case 3: launch_orq<C, 5, 3>(g, n, p, nb, lv, codes, st); break;
-            default: launch_orq<C, 9, 4>(g, n, p, nb, lv, codes, st); break;
-        }
+    switch (p->scheme) {
+        case OGQ_BINGRAD_PB: launch_orq<C, 2, 1, kPb>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_ORQ:
+            switch (p->bits) {
+                case 1: launch_orq<C, 2, 1>(g, n, p, nb, lv, codes, st); break;
+                case 2: launch_orq<C, 4, 2>(g, n, p, nb, lv, codes, st); break;
+                default: launch_orq<C, 8, 3>(g, n, p, nb, lv, codes, st); break;
+            }
+            break;
+        case OGQ_EVEN: launch_paper_counts<C, kEven>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_LINEAR: launch_paper_counts<C, kLinear>(g, n, p, nb, lv, codes, st); break;
+        default: launch_paper_counts<C, kOptimal>(g, n, p, nb, lv, codes, st); break;  // OGQ_ORQ_PAPER
     }
 }
 
@@ -1529,7 +1609,7 @@ int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params, floa
     uint32_t nb = (uint32_t)nb64;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const uint32_t d = params->bucket_size;
-    if (params->scheme == OGQ_BINGRAD_B) {
+    if (params->scheme == OGQ_BINGRAD_B || params->scheme == OGQ_SCALED_SIGN) {
         // Whole chunks of 2048 elements go to the kernel that packs several buckets into a wavefront; what
         // is left (fewer than 2048 elements) takes the one-bucket-per-wavefront kernel below.  Buckets of
         // 512 and 1024 elements stay with that kernel for gradients too short to give every SIMD a chunk

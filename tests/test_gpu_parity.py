@@ -157,6 +157,97 @@ def test_orq_paper_five_levels_resnet50_size_sampled():
             assert np.array_equal(out[lo:hi], ref)
 
 
+# ------------------------------------------------------------------------------------------------
+# the comparison level rules of the paper's Section 5 on the same kernels
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d", [64, 128, 192, 512, 1024, 2048, 3072, 4096])
+def test_scaled_sign_small(d):
+    rng = np.random.default_rng(4000 + d)
+    for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
+        for n in (1, 65, d - 1, d, 3 * d + 129, 3 * 2048 + 2 * d + 11):
+            g = _rng_bucket(rng, n, kind)
+            parity.check_quantize(g, d, 1, ogq.SCALED_SIGN, 0, tag=f"sign-{kind}-d{d}-n{n}")
+        g = _rng_bucket(rng, 4 * d + 3, kind)
+        parity.check_quantize(g, d, 1, ogq.SCALED_SIGN, 0, clip_factor=2.5, tag=f"sign-clip-{kind}-d{d}")
+
+
+@pytest.mark.parametrize("d", [512, 1024])
+def test_scaled_sign_several_buckets_per_wavefront_above_four_million_elements(d):
+    rng = np.random.default_rng(d + 1)
+    n = 2100 * 2048 + d + 77
+    g = (rng.standard_t(3, n) * 1e-3).astype(np.float32)
+    g[5 * d:6 * d] = -0.0
+    parity.check_quantize(g, d, 1, ogq.SCALED_SIGN, 0, tag=f"sign-long-d{d}")
+
+
+@pytest.mark.parametrize("scheme", [ogq.EVEN, ogq.LINEAR])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("d", [64, 320, 512, 2048, 4096])
+def test_even_and_linear_levels_small(scheme, bits, d):
+    rng = np.random.default_rng(17 * bits + d + scheme)
+    for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
+        for n in (1, 2, 3, 65, d - 1, d, 3 * d + 129):
+            g = _rng_bucket(rng, n, kind)
+            parity.check_quantize(g, d, bits, scheme, 0, seed=7 + n, tag=f"rule{scheme}-b{bits}-{kind}-d{d}-n{n}")
+        g = _rng_bucket(rng, 4 * d + 3, kind)
+        parity.check_quantize(g, d, bits, scheme, 0, seed=3, clip_factor=2.5, index_offset=64 * 12345,
+                              tag=f"rule{scheme}-b{bits}-clip-{kind}-d{d}")
+
+
+def _rounding_error(x, levels):
+    lv = np.asarray(levels, np.float64)
+    x = np.asarray(x, np.float64)
+    k = np.clip(np.searchsorted(lv, x, side="right") - 1, 0, lv.size - 2)
+    return float(np.sum((lv[k + 1] - x) * (x - lv[k])))
+
+
+def test_comparison_rules_resnet50_size_and_error_ordering():
+    """The three multi-level rules at full size on one gradient (sampled buckets against the oracle, decode
+    included), and the ordering of their expected rounding errors from the device's own level tables
+    (Section 5.1: ORQ has the smallest error for its number of levels)."""
+    wl = synth.WORKLOADS["cfg3"]
+    g = wl.gradient()
+    d, bits, s = 2048, 3, 5
+    nb = (g.size + d - 1) // d
+    tables = {}
+    for scheme in (ogq.ORQ_PAPER, ogq.EVEN, ogq.LINEAR):
+        lv, codes, rep = parity.check_quantize(g, d, bits, scheme, 0, seed=21, buckets=_sample(nb, 200, scheme),
+                                               tag=f"rule{scheme}-cfg3")
+        tables[scheme] = lv[:nb * s].cpu().numpy().reshape(nb, s)
+        if scheme != ogq.ORQ_PAPER:
+            out = ogq.ogq_dequantize_average([codes], [lv], g.size, ogq.make_params(d, bits, scheme))
+            torch.cuda.synchronize()
+            out = out.cpu().numpy()
+            for b in _sample(nb, 30, 1):
+                lo, hi = b * d, min((b + 1) * d, g.size)
+                l, w = oracle.quantize(g[lo:hi], d, bits, scheme, 0, 21, lo)
+                assert np.array_equal(out[lo:hi], oracle.dequantize_average([w], [l], hi - lo, d, bits, s))
+    err = {k: 0.0 for k in tables}
+    for b in _sample(nb, 300, 9):
+        x = g[b * d:min((b + 1) * d, g.size)]
+        for k in tables:
+            err[k] += _rounding_error(x, tables[k][b])
+    print(f"[parity] expected rounding error, 300 buckets of cfg3: ORQ-5 {err[ogq.ORQ_PAPER]:.4e}, "
+          f"evenly spaced {err[ogq.EVEN]:.4e}, Linear-5 {err[ogq.LINEAR]:.4e}", flush=True)
+    assert err[ogq.ORQ_PAPER] < err[ogq.EVEN] and err[ogq.ORQ_PAPER] < err[ogq.LINEAR]
+
+
+def test_scaled_sign_resnet50_size():
+    wl = synth.WORKLOADS["cfg2"]
+    g = wl.gradient()
+    d = 2048
+    lv, codes, rep = parity.check_quantize(g, d, 1, ogq.SCALED_SIGN, 0, tag="sign-cfg2-all")
+    assert rep["code_mismatches"] == 0
+    # two-level error against BinGrad-b on the same gradient, from the device's outputs
+    out_s = ogq.ogq_dequantize_average([codes], [lv], g.size, ogq.make_params(d, 1, ogq.SCALED_SIGN)).cpu().numpy()
+    lv_b, codes_b = ogq.ogq_quantize(torch.from_numpy(g).to(DEV), ogq.make_params(d, 1, ogq.BINGRAD_B))
+    out_b = ogq.ogq_dequantize_average([codes_b], [lv_b], g.size, ogq.make_params(d, 1, ogq.BINGRAD_B)).cpu().numpy()
+    e_s = float(np.sum((g.astype(np.float64) - out_s) ** 2))
+    e_b = float(np.sum((g.astype(np.float64) - out_b) ** 2))
+    print(f"[parity] squared error on cfg2: BinGrad-b {e_b:.6e}, Scaled SignSGD {e_s:.6e}", flush=True)
+    assert e_b <= e_s * 1.001
+
+
 def test_orq_sweeps_and_offsets():
     rng = np.random.default_rng(77)
     g = _rng_bucket(rng, 8 * 1024 + 100, "heavy")
@@ -190,11 +281,12 @@ def test_random_shapes_and_parameters():
     # clipping, value distributions, including buckets dominated by repeated values
     rng = np.random.default_rng(20260101)
     kinds = ("normal", "ints", "heavy", "shifted", "const", "zeros")
-    for trial in range(240):
+    for trial in range(390):
         d = int(rng.choice([64, 128, 192, 256, 448, 512, 1024, 1536, 2048, 3072, 4096]))
         n = int(rng.integers(1, 5 * d + 2))
         scheme, bits = [(ogq.BINGRAD_B, 1), (ogq.BINGRAD_PB, 1), (ogq.ORQ, 1), (ogq.ORQ, 2), (ogq.ORQ, 3),
-                        (ogq.ORQ_PAPER, 2), (ogq.ORQ_PAPER, 3), (ogq.ORQ_PAPER, 4)][trial % 8]
+                        (ogq.ORQ_PAPER, 2), (ogq.ORQ_PAPER, 3), (ogq.ORQ_PAPER, 4), (ogq.SCALED_SIGN, 1),
+                        (ogq.EVEN, 2), (ogq.EVEN, 4), (ogq.LINEAR, 2), (ogq.LINEAR, 3)][trial % 13]
         g = _rng_bucket(rng, n, kinds[int(rng.integers(len(kinds)))])
         if trial % 5 == 0:  # mixed magnitudes inside one bucket
             g = (g * np.float32(10.0) ** rng.integers(-6, 4, n).astype(np.float32)).astype(np.float32)
@@ -217,7 +309,8 @@ def test_empty_input_is_a_noop():
 # decode + average
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("bits,scheme", [(1, ogq.BINGRAD_B), (1, ogq.BINGRAD_PB), (1, ogq.ORQ), (2, ogq.ORQ), (3, ogq.ORQ),
-                                         (2, ogq.ORQ_PAPER), (3, ogq.ORQ_PAPER), (4, ogq.ORQ_PAPER)])
+                                         (2, ogq.ORQ_PAPER), (3, ogq.ORQ_PAPER), (4, ogq.ORQ_PAPER),
+                                         (1, ogq.SCALED_SIGN), (2, ogq.EVEN), (4, ogq.LINEAR)])
 @pytest.mark.parametrize("d", [64, 128, 192, 256, 512, 1024, 1536, 2048, 4096])
 def test_decode_average_small(bits, scheme, d):
     rng = np.random.default_rng(bits * 1000 + d)
