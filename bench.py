@@ -25,6 +25,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+WORKLOAD_NAMES = ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "pb2", "orq5", "orq3clip", "cfg2clip", "bin512", "sign2",
+                  "tern3", "linear5")
 
 
 def algorithmic_bytes(n: int, bucket_size: int, bits: int, workers: int, levels_per_bucket: int):
@@ -62,7 +64,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "pb2", "orq5", "orq3clip", "cfg2clip"])
+    ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--buffers", type=int, default=0, help="distinct input buffers (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -198,7 +200,15 @@ def main() -> int:
     probe_gbs = 4 * n / timed(lambda i: ogq.ogq_probe_read(grads[i % n_buf][0], sink)) / 1e9
     copy_gbs = 8 * (n - n % 4) / timed(lambda i: ogq.ogq_probe_copy(grads[i % n_buf][0], outs[(i + 1) % n_buf])) / 1e9
 
-    quant_name = "bingrad_quantize_kernel" if wl.scheme == synth.BINGRAD_B else "orq_quantize_kernel"
+    two_level_means = wl.scheme in (synth.BINGRAD_B, synth.SCALED_SIGN)
+    if not two_level_means:
+        quant_name = "orq_quantize_kernel"
+    elif d > 2048:
+        quant_name = "bingrad_pair_kernel"
+    elif wl.clip_factor == 0 and 2048 % d == 0 and d < 2048 and (d <= 256 or n // 2048 >= 2048):
+        quant_name = "bingrad_chunk_kernel"
+    else:
+        quant_name = "bingrad_quantize_kernel"
     # The wave-per-bucket ORQ / BinGrad-pb kernel issues ~110 VALU instructions per element (Philox, exact
     # rank selection): it is bound by VALU issue, not by HBM; its line still prices it against the HBM peak.
     dominant_is_quant = q_avg * W >= a_avg
@@ -223,7 +233,7 @@ def main() -> int:
     # (profiles/valu_instructions.txt), priced against 78.6 T lane-operations/s (256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz)
     valu_per_wave = read_note("valu_instructions.txt", f"{args.workload}:{quant_name}")
     alu = None
-    if valu_per_wave is not None and wl.scheme != synth.BINGRAD_B:
+    if valu_per_wave is not None and not two_level_means:
         lane_ops = valu_per_wave * 64 * ((n + d - 1) // d)
         achieved = lane_ops / (q_avg * 1e-3) / 1e12
         alu = {"bound": "alu", "kernel": quant_name, "achieved": round(achieved, 2), "peak": 78.6,

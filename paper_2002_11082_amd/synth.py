@@ -16,6 +16,9 @@ BINGRAD_B = 0
 ORQ = 1
 BINGRAD_PB = 2
 ORQ_PAPER = 3
+SCALED_SIGN = 4
+EVEN = 5
+LINEAR = 6
 
 
 def gaussian(n: int, sigma: float, seed: int) -> np.ndarray:
@@ -129,4 +132,13 @@ WORKLOADS = {
     "cfg2clip": Workload("cfg2clip", 25_600_000, 2048, 1, BINGRAD_B, 0, 1, 0,
                          "BinGrad-b 1-bit with clipping c=2.5 on the cfg2 gradient, bucket 2048",
                          clip_factor=2.5, data="cfg2"),
+    "bin512": Workload("bin512", 25_600_000, 512, 1, BINGRAD_B, 0, 1, 0,
+                       "BinGrad-b 1-bit on the cfg2 gradient, bucket 512 (the paper's ImageNet bucket size)", data="cfg2"),
+    # the level rules the paper compares against, on the same kernels and inputs
+    "sign2": Workload("sign2", 25_600_000, 2048, 1, SCALED_SIGN, 0, 1, 0,
+                      "Scaled SignSGD per bucket on the cfg2 gradient, bucket 2048", data="cfg2"),
+    "tern3": Workload("tern3", 25_600_000, 2048, 2, EVEN, 0, 1, 7,
+                      "TernGrad / QSGD-3 (3 evenly spaced levels) on the cfg3 gradient, bucket 2048", data="cfg3"),
+    "linear5": Workload("linear5", 25_600_000, 2048, 3, LINEAR, 0, 1, 8,
+                        "Linear-5 (5 equal-mass levels) on the cfg3 gradient, bucket 2048", data="cfg3"),
 }
