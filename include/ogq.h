@@ -36,7 +36,7 @@ extern "C" {
 typedef enum {
     OGQ_OK = 0,
     OGQ_ERR_NULL_POINTER = -1,  /* a required pointer is NULL */
-    OGQ_ERR_BUCKET_SIZE = -2,   /* bucket_size is 0, not a multiple of 64, or above 4096 */
+    OGQ_ERR_BUCKET_SIZE = -2,   /* bucket_size is 0, not a multiple of 64, or above 32768 */
     OGQ_ERR_BITS = -3,          /* bits outside the range the scheme supports */
     OGQ_ERR_SCHEME = -4,        /* unknown scheme */
     OGQ_ERR_NUM_WORKERS = -5,   /* num_workers is 0 or above OGQ_MAX_WORKERS */
@@ -81,10 +81,10 @@ typedef enum {
 } ogq_scheme_t;
 
 #define OGQ_MAX_WORKERS 64u
-#define OGQ_MAX_BUCKET_SIZE 4096u
+#define OGQ_MAX_BUCKET_SIZE 32768u
 
 typedef struct {
-    uint32_t bucket_size;  /* elements per bucket: a multiple of 64 in [64, 4096] */
+    uint32_t bucket_size;  /* elements per bucket: a multiple of 64 in [64, 32768] (the paper's sweep: 128 .. 32768) */
     uint32_t bits;         /* width of a level index; levels per bucket: see ogq_levels_per_bucket */
     uint32_t scheme;       /* ogq_scheme_t */
     /* BINGRAD_B: number of threshold updates b0 <- (b_{-1} + b_1)/2 after the start b0 = bucket

@@ -194,67 +194,79 @@ __device__ __forceinline__ double uniform_f64(double x)
 // wave-wide result becomes a bucket-wide one.
 // ----------------------------------------------------------------------------------------------
 struct OneWave {
-    __device__ __forceinline__ uint32_t first_element() const { return 0; }  // of the bucket, held by this wavefront
-    __device__ __forceinline__ bool leader() const { return true; }
     __device__ __forceinline__ double sum(double x) { return x; }
     __device__ __forceinline__ void sum_and_max(double&, float&) {}
     __device__ __forceinline__ void sum_and_count(double&, uint32_t&) {}
 };
 
-// Both wavefronts call every combine in the same order (their control flow depends on combined values
-// only).  Two alternating LDS slots are enough: a wavefront that writes a slot for the second time has
-// passed the barrier in between, which the other one reaches only after it has read the first value.
+// All wavefronts of the team call every combine in the same order (their control flow depends on combined
+// values only).  Two alternating LDS slots are enough: a wavefront that writes a slot for the second time has
+// passed the barrier in between, which the others reach only after they have read the first value.
 struct TeamSlot {
     double sum;
-    uint32_t word;
-    uint32_t pad;
+    uint32_t a, b;
 };
 
-struct TwoWaves {
-    TeamSlot (*slots)[2];  // [2][2] in LDS: [call parity][wavefront]
+template <int W>
+struct WaveTeam {
+    TeamSlot (*slots)[W];  // [2][W] in LDS: [call parity][wavefront]
     uint32_t wave;
     uint32_t calls;
-    __device__ __forceinline__ uint32_t first_element() const { return wave * 2048u; }
-    __device__ __forceinline__ bool leader() const { return wave == 0; }
-    __device__ __forceinline__ const TeamSlot* exchange(double sum, uint32_t word)
+    __device__ __forceinline__ const TeamSlot* exchange(double sum, uint32_t a, uint32_t b)
     {
         TeamSlot* slot = slots[calls & 1u];
         ++calls;
         if ((threadIdx.x & 63u) == 0) {
             slot[wave].sum = sum;
-            slot[wave].word = word;
+            slot[wave].a = a;
+            slot[wave].b = b;
         }
         __syncthreads();
         return slot;
     }
     __device__ __forceinline__ double sum(double x)
     {
-        const TeamSlot* s = exchange(x, 0u);
-        return s[0].sum + s[1].sum;
+        const TeamSlot* s = exchange(x, 0u, 0u);
+        double r = s[0].sum;
+#pragma unroll
+        for (int w = 1; w < W; ++w) r += s[w].sum;
+        return r;
     }
     __device__ __forceinline__ void sum_and_max(double& x, float& m)
     {
-        const TeamSlot* s = exchange(x, __float_as_uint(m));
-        x = s[0].sum + s[1].sum;
-        m = fmaxf(__uint_as_float(s[0].word), __uint_as_float(s[1].word));
+        const TeamSlot* s = exchange(x, __float_as_uint(m), 0u);
+        x = s[0].sum;
+        m = __uint_as_float(s[0].a);
+#pragma unroll
+        for (int w = 1; w < W; ++w) {
+            x += s[w].sum;
+            m = fmaxf(m, __uint_as_float(s[w].a));
+        }
     }
     __device__ __forceinline__ void sum_and_count(double& x, uint32_t& c)
     {
-        const TeamSlot* s = exchange(x, c);
-        x = s[0].sum + s[1].sum;
-        c = s[0].word + s[1].word;
+        const TeamSlot* s = exchange(x, c, 0u);
+        x = s[0].sum;
+        c = s[0].a;
+#pragma unroll
+        for (int w = 1; w < W; ++w) {
+            x += s[w].sum;
+            c += s[w].a;
+        }
     }
 };
 
 // E registers per lane; FULL: every register of this wavefront holds a bucket element.  g, len, levels2
-// and words belong to the whole bucket.  SIGN: Scaled SignSGD instead (first equation of Section 3.2):
-// levels -m, +m with m the mean magnitude of the bucket, index = (v >= 0).
+// and words belong to the whole bucket, of which this wavefront holds the 64*E elements from `first_element` on;
+// the wavefront with first_element == 0 writes the levels.  SIGN: Scaled SignSGD instead (first equation of
+// Section 3.2): levels -m, +m with m the mean magnitude of the bucket, index = (v >= 0).
 template <int E, bool FULL, bool CLIP, bool SIGN, class Team>
-__device__ __forceinline__ void bingrad_bucket(Team team, const float* __restrict__ g, uint32_t len, uint32_t iters,
-                                               float clip, float* __restrict__ levels2, uint64_t* __restrict__ words)
+__device__ __forceinline__ void bingrad_bucket(Team team, uint32_t first_element, const float* __restrict__ g,
+                                               uint32_t len, uint32_t iters, float clip, float* __restrict__ levels2,
+                                               uint64_t* __restrict__ words)
 {
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t first = team.first_element() + lane;
+    const uint32_t first = first_element + lane;
     float v[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
@@ -342,12 +354,12 @@ __device__ __forceinline__ void bingrad_bucket(Team team, const float* __restric
         b0 = (float)((b_lo + b_hi) * 0.5);
     }
 
-    if (lane == 0 && team.leader()) {
+    if (lane == 0 && first_element == 0) {
         levels2[0] = (float)b_lo;
         levels2[1] = (float)b_hi;
     }
     const uint32_t n_words = (len + 63u) / 64u;
-    const uint32_t word = team.first_element() / 64u + lane;
+    const uint32_t word = first_element / 64u + lane;
     if (lane < (uint32_t)E && word < n_words) words[word] = ((uint64_t)word_hi << 32) | word_lo;
 }
 
@@ -369,18 +381,18 @@ __global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_p
     const float* g = grad + begin;
     float* lv = levels + (size_t)bucket * 2;
     uint64_t* w = codes + begin / 64;
-    if (len == 64u * E) bingrad_bucket<E, true, CLIP, SIGN>(OneWave{}, g, len, iters, clip, lv, w);
-    else bingrad_bucket<E, false, CLIP, SIGN>(OneWave{}, g, len, iters, clip, lv, w);
+    if (len == 64u * E) bingrad_bucket<E, true, CLIP, SIGN>(OneWave{}, 0u, g, len, iters, clip, lv, w);
+    else bingrad_bucket<E, false, CLIP, SIGN>(OneWave{}, 0u, g, len, iters, clip, lv, w);
 }
 
-// Buckets of more than 2048 elements: the two wavefronts of a workgroup hold one bucket, 32 registers
-// per lane each as for a 2048-element bucket, and combine their sums and counts through LDS.
-template <bool CLIP, bool SIGN>
-__global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_pair_kernel(
+// Buckets of more than 2048 elements: the W = 2, 4, 8 or 16 wavefronts of a workgroup hold one bucket, 32
+// registers per lane each as for a 2048-element bucket, and combine their sums and counts through LDS.
+template <int W, bool CLIP, bool SIGN>
+__global__ __launch_bounds__(W* kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_team_kernel(
     const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, float clip, uint32_t num_buckets,
     float* __restrict__ levels, uint64_t* __restrict__ codes)
 {
-    __shared__ TeamSlot slots[2][2];
+    __shared__ TeamSlot slots[2][W];
     const uint32_t bucket = blockIdx.x;
     if (bucket >= num_buckets) return;
     const size_t begin = (size_t)bucket * bucket_size;
@@ -389,9 +401,10 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(4, 4)
     const float* g = grad + begin;
     float* lv = levels + (size_t)bucket * 2;
     uint64_t* w = codes + begin / 64;
-    const TwoWaves team{slots, uniform_u32(threadIdx.x >> 6), 0u};
-    if (len == 4096u) bingrad_bucket<32, true, CLIP, SIGN>(team, g, len, iters, clip, lv, w);
-    else bingrad_bucket<32, false, CLIP, SIGN>(team, g, len, iters, clip, lv, w);
+    const uint32_t wave = uniform_u32(threadIdx.x >> 6);
+    const WaveTeam<W> team{slots, wave, 0u};
+    if (len == 2048u * W) bingrad_bucket<32, true, CLIP, SIGN>(team, 2048u * wave, g, len, iters, clip, lv, w);
+    else bingrad_bucket<32, false, CLIP, SIGN>(team, 2048u * wave, g, len, iters, clip, lv, w);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -733,8 +746,9 @@ constexpr GreedyOrder greedy_order()
 }
 
 // LDS of one bucket: D = element capacity, B = number of bins.
-template <int D, int B>
+template <int D_, int B_>
 struct OrqLds {
+    static constexpr int D = D_, B = B_;
     // fp32 bit patterns (-0 stored as +0) grouped by bin, unsorted inside a bin.  Position i lives at
     // word i + i/32, so that the 64 lanes reading consecutive blocks of D/64 positions hit distinct banks.
     uint32_t grouped[D + D / 32];
@@ -821,18 +835,12 @@ struct Picked {
     double sum_lt, sum_le;
 };
 
-// rank is 1-based, 1 <= rank <= bucket length.  my_start[t] = bin_start[lane * PER + t].
-template <int D, int B>
-__device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint32_t (&my_start)[B / 64],
-                                            uint32_t rank, uint32_t lane)
+// The element of 1-based rank `rank`, which lies in bin `bin`.  BLOCK = positions per entry of the fp64
+// block prefix (at most 64).
+template <int BLOCK, class Lds>
+__device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint32_t rank, uint32_t lane)
 {
-    constexpr int PER = B / 64;
-    constexpr uint32_t BLOCK = D / 64;  // positions per block of the fp64 prefix
-    // the bin holding the rank: the last bin whose first position is below the rank
-    uint32_t starts_below = 0;
-#pragma unroll
-    for (int t = 0; t < PER; ++t) starts_below += (my_start[t] < rank) ? 1u : 0u;
-    const uint32_t bin = wave_sum_u32(starts_below) - 1u;  // bin_start[0] = 0 < rank: at least one
+    static_assert(BLOCK <= 64, "the head of a block is read one position per lane");
     const uint32_t first = uniform_u32(lds.bin_start[bin]);
     const uint32_t count = uniform_u32(lds.bin_start[bin + 1]) - first;
     const uint32_t r_in = rank - first;  // 1-based rank inside the bin
@@ -892,6 +900,33 @@ __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint3
     return p;
 }
 
+// rank is 1-based, 1 <= rank <= bucket length.  my_start[t] = bin_start[lane * PER + t], kept in registers.
+template <int D, int B>
+__device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint32_t (&my_start)[B / 64],
+                                            uint32_t rank, uint32_t lane)
+{
+    constexpr int PER = B / 64;
+    // the bin holding the rank: the last bin whose first position is below the rank
+    uint32_t starts_below = 0;
+#pragma unroll
+    for (int t = 0; t < PER; ++t) starts_below += (my_start[t] < rank) ? 1u : 0u;
+    const uint32_t bin = wave_sum_u32(starts_below) - 1u;  // bin_start[0] = 0 < rank: at least one
+    return pick_in_bin<D / 64>(lds, bin, rank, lane);
+}
+
+// The same with the bin found by two looks into LDS (every (B/64)-th bin start, then the B/64 bins in between):
+// no registers are tied up by the bin starts.
+template <class Lds>
+__device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t rank, uint32_t lane)
+{
+    constexpr uint32_t PER = Lds::B / 64;
+    static_assert(PER <= 64, "one lane per bin of a segment");
+    const uint32_t segment = (uint32_t)__popcll(__ballot(lds.bin_start[lane * PER] < rank)) - 1u;
+    const bool below = lane < PER && lds.bin_start[segment * PER + (lane < PER ? lane : 0u)] < rank;
+    const uint32_t bin = segment * PER + (uint32_t)__popcll(__ballot(below)) - 1u;
+    return pick_in_bin<64>(lds, bin, rank, lane);
+}
+
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // Returns x unchanged but hides it from common-subexpression elimination, so that values derived
@@ -902,12 +937,83 @@ __device__ __forceinline__ float recompute_from(float x)
     return x;
 }
 
-template <int C>
-struct OrqShape {
-    static constexpr int D = 256 * C;               // element capacity of the wave
-    static constexpr int B = C >= 16 ? 512 : 256;   // bins
-    static constexpr int SHIFT = C >= 16 ? 19 : 20; // magnitude bits dropped: keeps exponent + 4 (3) mantissa bits
-};
+// ---- encode (random rounding, Section 3.1) + pack ------------------------------------------------
+// v: the 256*C elements a wavefront holds (lane l, chunk c: elements 256c + 4l + {0..3} of the range that
+// starts at global element `begin` and has `len` valid elements; FULL: len == 256*C); lv: the levels.
+template <int C, int S, int BITS, bool FULL>
+__device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (&lv)[S], uint32_t len, size_t begin,
+                                           uint64_t seed, uint64_t index_offset, uint32_t* __restrict__ codes32)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    // Per element only the level compares, the selects of (level below, interval width) and the rounding
+    // test run on the vector unit; the level index is assembled from the compare masks on the scalar unit
+    // (the masks are a thermometer code of the interval, to which the rounding bit is added with carry).
+    float width[S - 1];
+#pragma unroll
+    for (int k = 0; k < S - 1; ++k) width[k] = lv[k + 1] - lv[k];
+    uint32_t bit_of[4];  // where element k of this lane sits in its 32-bit half of a packed word
+#pragma unroll
+    for (int k = 0; k < 4; ++k) bit_of[k] = 1u << (4u * (lane & 7u) + k);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint32_t padded_len = (len + 63u) & ~63u;
+    const size_t word0 = begin / 64;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const uint64_t block = (index_offset + begin + 256u * c + 4u * lane) >> 2;
+        uint32_t r[4];
+        philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), k0, k1, r);
+        uint32_t plane[BITS];
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) plane[p] = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float x = v[c][k];
+            // interval: last level not above x, at most S-2
+            uint64_t not_below[S];  // [t]: lanes whose element is >= level t, t = 1 .. S-2
+            float base = lv[0], w = width[0];
+#pragma unroll
+            for (int t = 1; t < S - 1; ++t) {
+                const bool ge = lv[t] <= x;
+                not_below[t] = __ballot(ge);
+                base = ge ? lv[t] : base;
+                w = ge ? width[t] : w;
+            }
+            const float delta = x - base;
+            const float u = (float)(r[k] >> 8) * 0x1p-24f;
+            const float scaled = u * w;
+            uint64_t carry = __ballot(scaled < delta);  // rounded up
+            if constexpr (!FULL) carry &= __ballot(256u * c + 4u * lane + k < len);
+#pragma unroll
+            for (int p = 0; p < BITS; ++p) {
+                // bit p of the number of levels 1..S-2 not above x
+                uint64_t index_bit = 0;
+#pragma unroll
+                for (int j = 1; (j << p) <= S - 2; j += 2) {
+                    const int lo_t = j << p, hi_t = (j + 1) << p;
+                    index_bit |= hi_t <= S - 2 ? (not_below[lo_t] & ~not_below[hi_t]) : not_below[lo_t];
+                }
+                if constexpr (!FULL) index_bit &= __ballot(256u * c + 4u * lane + k < len);
+                const uint64_t code_bit = index_bit ^ carry;
+                carry &= index_bit;
+                plane[p] |= __builtin_amdgcn_inverse_ballot_w64(code_bit) ? bit_of[k] : 0u;
+            }
+        }
+        // OR over the 8 lanes that make up one 32-bit half of a packed word
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) {
+            uint32_t x = plane[p];
+            x |= dpp_u32<kDppXor1>(x);
+            x |= dpp_u32<kDppXor2>(x);
+            x |= dpp_u32<kDppHalfMirror>(x);
+            const uint32_t first = 256u * c + 32u * (lane >> 3);  // first element of this half word
+            if ((lane & 7u) == 0 && first < padded_len) {
+                const size_t word = (word0 + 4u * c + (lane >> 4)) * BITS + p;
+                codes32[word * 2 + ((lane >> 3) & 1u)] = x;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
 
 // Where the levels come from; all rules share the random-rounding encoder.
 //   kOptimal: ORQ (Theorem 1, Algorithm 1).
@@ -916,6 +1022,122 @@ struct OrqShape {
 //   kEven: QSGD-s / TernGrad (Section 3.1): S levels evenly spaced from -M to +M, M the largest magnitude.
 //   kLinear: Linear-s (Section 5): the order statistics at the fractions k/(S-1) of the sorted bucket.
 enum LevelRule { kOptimal = 0, kPb = 1, kEven = 2, kLinear = 3 };
+
+// The level solves of one bucket, run by one wavefront once the bucket is grouped in LDS and the level
+// records of the two ends are set.  pick(rank) returns the element of that 1-based rank (Picked); `zeros` is the
+// number of zeros in the bucket (BinGrad-pb only).  Interior levels end up in lds.lvl_value; returns b_1 for
+// BinGrad-pb.
+template <int S, int RULE, class Lds, class PickFn>
+__device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, uint32_t len, uint32_t zeros, uint32_t sweeps,
+                                                  uint32_t lane)
+{
+    constexpr bool PB = RULE == kPb;
+    float pb_level = 0.0f;
+    if constexpr (PB) {
+        // ---- b_1: minimise |b * #{v > 0} - sum_{v >= b} v| over the positive bucket values.  The
+        //      difference grows with b, so the minimiser is one of the two values around its sign
+        //      change, which a bisection over the ranks of the positive values finds. -------------
+                const uint32_t not_positive = uniform_u32(lds.bin_start[Lds::B / 2]) + zeros;  // negatives fill the lower bins
+        const uint32_t positives = len - not_positive;
+        const double total = uniform_f64(lds.lvl_sum_le[S - 1]);
+        if (positives > 0u) {
+            uint32_t lo = not_positive + 1u, hi = len;  // 1-based ranks; the largest value always has gap >= 0
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                const Picked p = pick(mid);
+                const double gap = (double)key_to_float(p.key) * (double)positives - (total - p.sum_lt);
+                if (gap >= 0.0) hi = mid;
+                else lo = mid + 1u;
+            }
+            const Picked up = pick(lo);
+            const double gap_up = (double)key_to_float(up.key) * (double)positives - (total - up.sum_lt);
+            pb_level = key_to_float(up.key);
+            if (up.count_lt > not_positive) {  // a smaller positive value exists: rank count_lt is the next one down
+                const Picked down = pick(up.count_lt);
+                const double gap_down =
+                    (double)key_to_float(down.key) * (double)positives - (total - down.sum_lt);
+                if (fabs(gap_down) <= fabs(gap_up)) pb_level = key_to_float(down.key);  // ties take the smaller value
+            }
+        }
+    }
+
+    if constexpr (RULE == kLinear) {
+        for (uint32_t k = 1; k + 1 < (uint32_t)S; ++k) {
+            const uint32_t rank = 1u + (uint32_t)(((uint64_t)k * (len - 1u)) / (uint32_t)(S - 1));
+            const Picked p = pick(rank);
+            if (lane == 0u) lds.lvl_value[k] = key_to_float(p.key);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- level solves: greedy recursion (Algorithm 1), then re-solve sweeps ------------------
+    if constexpr (S > 2 && RULE == kOptimal) {
+    constexpr GreedyOrder order = greedy_order<S>();
+    const uint32_t steps = order.count + sweeps * (S - 2);
+    for (uint32_t step = 0; step < steps; ++step) {
+        uint32_t k, l, r;
+        if (step < (uint32_t)order.count) {
+            const uint32_t e = step < 5u ? (uint32_t)(order.packed[0] >> (12 * step))
+                                         : (uint32_t)(order.packed[1] >> (12 * (step - 5u)));
+            k = e & 15u; l = (e >> 4) & 15u; r = (e >> 8) & 15u;
+        } else {
+            k = 1u + (step - order.count) % (S - 2);
+            l = k - 1u; r = k + 1u;
+        }
+        const float L = uniform_f32(lds.lvl_value[l]);
+        const float R = uniform_f32(lds.lvl_value[r]);
+        const uint32_t cnt_lt_L = uniform_u32(lds.lvl_count_lt[l]);
+        const uint32_t cnt_le_R = uniform_u32(lds.lvl_count_le[r]);
+        const double sum_lt_L = uniform_f64(lds.lvl_sum_lt[l]);
+        const double sum_le_R = uniform_f64(lds.lvl_sum_le[r]);
+        bool copy_left = !(L < R);
+        Picked p;
+        uint32_t rank = 0;
+        if (!copy_left) {
+            // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
+            const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
+            const double T = Ssum / ((double)R - (double)L);
+            double m = floor(T);
+            if (!(m >= 0.0)) m = 0.0;
+            rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
+            rank = rank < 1u ? 1u : (rank > len ? len : rank);
+            if (rank == uniform_u32(lds.lvl_rank[k])) continue;  // same element as last time
+            p = pick(rank);
+            if (key_to_float(p.key) < L) copy_left = true;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0u) {
+            if (copy_left) {
+                // the level coincides with the left end (L == R, or rounding put it below L)
+                lds.lvl_value[k] = L;
+                lds.lvl_count_lt[k] = cnt_lt_L;
+                lds.lvl_sum_lt[k] = sum_lt_L;
+                lds.lvl_count_le[k] = (L < R) ? uniform_u32(lds.lvl_count_le[l]) : cnt_le_R;
+                lds.lvl_sum_le[k] = (L < R) ? uniform_f64(lds.lvl_sum_le[l]) : sum_le_R;
+                lds.lvl_rank[k] = 0u;
+            } else {
+                lds.lvl_value[k] = key_to_float(p.key);
+                lds.lvl_count_lt[k] = p.count_lt;
+                lds.lvl_count_le[k] = p.count_le;
+                lds.lvl_sum_lt[k] = p.sum_lt;
+                lds.lvl_sum_le[k] = p.sum_le;
+                lds.lvl_rank[k] = rank;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    }
+    return pb_level;
+}
+
+template <int C>
+struct OrqShape {
+    static constexpr int D = 256 * C;               // element capacity of the wave
+    static constexpr int B = C >= 16 ? 512 : 256;   // bins
+    static constexpr int SHIFT = C >= 16 ? 19 : 20; // magnitude bits dropped: keeps exponent + 4 (3) mantissa bits
+};
 
 // FULL: the bucket has exactly 256*C elements (no padding, no per-element validity tests).
 // S levels per bucket, BITS bits per level index (S = 2^BITS, or 2^(BITS-1) + 1 for the paper's counts).
@@ -992,7 +1214,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
                 const bool valid = full || (256u * c + 4u * lane + k < len);
                 const uint32_t bits = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
                 const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
-                const uint32_t u = t > t_low ? t - t_low : 0u;  // 0 .. HALF-1
+                const uint32_t u = t > t_low ? umin32(t - t_low, (uint32_t)(HALF - 1)) : 0u;  // 0 .. HALF-1 (the clamp only acts on NaN)
                 const uint32_t bin = (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
                 slot[c][k] = 0u;
                 if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
@@ -1071,103 +1293,9 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
-        if constexpr (PB) {
-            // ---- b_1: minimise |b * #{v > 0} - sum_{v >= b} v| over the positive bucket values.  The
-            //      difference grows with b, so the minimiser is one of the two values around its sign
-            //      change, which a bisection over the ranks of the positive values finds. -------------
-            const uint32_t zeros = wave_sum_u32(lane_zeros);
-            const uint32_t not_positive = uniform_u32(lds.bin_start[HALF]) + zeros;  // negatives fill the lower bins
-            const uint32_t positives = len - not_positive;
-            const double total = uniform_f64(lds.lvl_sum_le[S - 1]);
-            if (positives > 0u) {
-                uint32_t lo = not_positive + 1u, hi = len;  // 1-based ranks; the largest value always has gap >= 0
-                while (lo < hi) {
-                    const uint32_t mid = (lo + hi) >> 1;
-                    const Picked p = pick_rank<D, B>(lds, my_start, mid, lane);
-                    const double gap = (double)key_to_float(p.key) * (double)positives - (total - p.sum_lt);
-                    if (gap >= 0.0) hi = mid;
-                    else lo = mid + 1u;
-                }
-                const Picked up = pick_rank<D, B>(lds, my_start, lo, lane);
-                const double gap_up = (double)key_to_float(up.key) * (double)positives - (total - up.sum_lt);
-                pb_level = key_to_float(up.key);
-                if (up.count_lt > not_positive) {  // a smaller positive value exists: rank count_lt is the next one down
-                    const Picked down = pick_rank<D, B>(lds, my_start, up.count_lt, lane);
-                    const double gap_down =
-                        (double)key_to_float(down.key) * (double)positives - (total - down.sum_lt);
-                    if (fabs(gap_down) <= fabs(gap_up)) pb_level = key_to_float(down.key);  // ties take the smaller value
-                }
-            }
-        }
-
-        if constexpr (RULE == kLinear) {
-            for (uint32_t k = 1; k + 1 < (uint32_t)S; ++k) {
-                const uint32_t rank = 1u + (uint32_t)(((uint64_t)k * (len - 1u)) / (uint32_t)(S - 1));
-                const Picked p = pick_rank<D, B>(lds, my_start, rank, lane);
-                if (lane == 0u) lds.lvl_value[k] = key_to_float(p.key);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-
-        // ---- level solves: greedy recursion (Algorithm 1), then re-solve sweeps ------------------
-        if constexpr (S > 2 && RULE == kOptimal) {
-        constexpr GreedyOrder order = greedy_order<S>();
-        const uint32_t steps = order.count + sweeps * (S - 2);
-        for (uint32_t step = 0; step < steps; ++step) {
-            uint32_t k, l, r;
-            if (step < (uint32_t)order.count) {
-                const uint32_t e = step < 5u ? (uint32_t)(order.packed[0] >> (12 * step))
-                                             : (uint32_t)(order.packed[1] >> (12 * (step - 5u)));
-                k = e & 15u; l = (e >> 4) & 15u; r = (e >> 8) & 15u;
-            } else {
-                k = 1u + (step - order.count) % (S - 2);
-                l = k - 1u; r = k + 1u;
-            }
-            const float L = uniform_f32(lds.lvl_value[l]);
-            const float R = uniform_f32(lds.lvl_value[r]);
-            const uint32_t cnt_lt_L = uniform_u32(lds.lvl_count_lt[l]);
-            const uint32_t cnt_le_R = uniform_u32(lds.lvl_count_le[r]);
-            const double sum_lt_L = uniform_f64(lds.lvl_sum_lt[l]);
-            const double sum_le_R = uniform_f64(lds.lvl_sum_le[r]);
-            bool copy_left = !(L < R);
-            Picked p;
-            uint32_t rank = 0;
-            if (!copy_left) {
-                // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
-                const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
-                const double T = Ssum / ((double)R - (double)L);
-                double m = floor(T);
-                if (!(m >= 0.0)) m = 0.0;
-                rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
-                rank = rank < 1u ? 1u : (rank > len ? len : rank);
-                if (rank == uniform_u32(lds.lvl_rank[k])) continue;  // same element as last time
-                p = pick_rank<D, B>(lds, my_start, rank, lane);
-                if (key_to_float(p.key) < L) copy_left = true;
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (lane == 0u) {
-                if (copy_left) {
-                    // the level coincides with the left end (L == R, or rounding put it below L)
-                    lds.lvl_value[k] = L;
-                    lds.lvl_count_lt[k] = cnt_lt_L;
-                    lds.lvl_sum_lt[k] = sum_lt_L;
-                    lds.lvl_count_le[k] = (L < R) ? uniform_u32(lds.lvl_count_le[l]) : cnt_le_R;
-                    lds.lvl_sum_le[k] = (L < R) ? uniform_f64(lds.lvl_sum_le[l]) : sum_le_R;
-                    lds.lvl_rank[k] = 0u;
-                } else {
-                    lds.lvl_value[k] = key_to_float(p.key);
-                    lds.lvl_count_lt[k] = p.count_lt;
-                    lds.lvl_count_le[k] = p.count_le;
-                    lds.lvl_sum_lt[k] = p.sum_lt;
-                    lds.lvl_sum_le[k] = p.sum_le;
-                    lds.lvl_rank[k] = rank;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-        }
+        const uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
+        pb_level = orq_solve_levels<S, RULE>(
+            lds, [&](uint32_t rank) { return pick_rank<D, B>(lds, my_start, rank, lane); }, len, zeros, sweeps, lane);
     }
 
     // every lane holds its own copy of the levels (the selects of the encoder take vector sources)
@@ -1188,75 +1316,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         for (int k = 0; k < S; ++k) levels[(size_t)bucket * S + k] = lv[k];
     }
 
-    // ---- encode (random rounding, Section 3.1) + pack ----------------------------------------------
-    // Per element only the level compares, the selects of (level below, interval width) and the rounding
-    // test run on the vector unit; the level index is assembled from the compare masks on the scalar unit
-    // (the masks are a thermometer code of the interval, to which the rounding bit is added with carry).
-    float width[S - 1];
-#pragma unroll
-    for (int k = 0; k < S - 1; ++k) width[k] = lv[k + 1] - lv[k];
-    uint32_t bit_of[4];  // where element k of this lane sits in its 32-bit half of a packed word
-#pragma unroll
-    for (int k = 0; k < 4; ++k) bit_of[k] = 1u << (4u * (lane & 7u) + k);
-    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
-    const uint32_t padded_len = (len + 63u) & ~63u;
-    const size_t word0 = begin / 64;
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-        const uint64_t block = (index_offset + begin + 256u * c + 4u * lane) >> 2;
-        uint32_t r[4];
-        philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), k0, k1, r);
-        uint32_t plane[BITS];
-#pragma unroll
-        for (int p = 0; p < BITS; ++p) plane[p] = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float x = v[c][k];
-            // interval: last level not above x, at most S-2
-            uint64_t not_below[S];  // [t]: lanes whose element is >= level t, t = 1 .. S-2
-            float base = lv[0], w = width[0];
-#pragma unroll
-            for (int t = 1; t < S - 1; ++t) {
-                const bool ge = lv[t] <= x;
-                not_below[t] = __ballot(ge);
-                base = ge ? lv[t] : base;
-                w = ge ? width[t] : w;
-            }
-            const float delta = x - base;
-            const float u = (float)(r[k] >> 8) * 0x1p-24f;
-            const float scaled = u * w;
-            uint64_t carry = __ballot(scaled < delta);  // rounded up
-            if constexpr (!FULL) carry &= __ballot(256u * c + 4u * lane + k < len);
-#pragma unroll
-            for (int p = 0; p < BITS; ++p) {
-                // bit p of the number of levels 1..S-2 not above x
-                uint64_t index_bit = 0;
-#pragma unroll
-                for (int j = 1; (j << p) <= S - 2; j += 2) {
-                    const int lo_t = j << p, hi_t = (j + 1) << p;
-                    index_bit |= hi_t <= S - 2 ? (not_below[lo_t] & ~not_below[hi_t]) : not_below[lo_t];
-                }
-                if constexpr (!FULL) index_bit &= __ballot(256u * c + 4u * lane + k < len);
-                const uint64_t code_bit = index_bit ^ carry;
-                carry &= index_bit;
-                plane[p] |= __builtin_amdgcn_inverse_ballot_w64(code_bit) ? bit_of[k] : 0u;
-            }
-        }
-        // OR over the 8 lanes that make up one 32-bit half of a packed word
-#pragma unroll
-        for (int p = 0; p < BITS; ++p) {
-            uint32_t x = plane[p];
-            x |= dpp_u32<kDppXor1>(x);
-            x |= dpp_u32<kDppXor2>(x);
-            x |= dpp_u32<kDppHalfMirror>(x);
-            const uint32_t first = 256u * c + 32u * (lane >> 3);  // first element of this half word
-            if ((lane & 7u) == 0 && first < padded_len) {
-                const size_t word = (word0 + 4u * c + (lane >> 4)) * BITS + p;
-                codes32[word * 2 + ((lane >> 3) & 1u)] = x;
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    orq_encode<C, S, BITS, FULL>(v, lv, len, begin, seed, index_offset, codes32);
 }
 
 template <int C, int S, int BITS, bool CLIP, int RULE>
@@ -1276,6 +1336,239 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
         orq_bucket<C, S, BITS, true, CLIP, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
     else
         orq_bucket<C, S, BITS, false, CLIP, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+}
+
+// ----------------------------------------------------------------------------------------------
+// ORQ and the other random-rounding rules for buckets above 4096 elements (up to 32768): the W = 2, 4 or 8
+// wavefronts of a workgroup own one bucket, wavefront w holding bucket elements [4096 w, 4096 (w + 1)) in the
+// register layout of orq_bucket.  All of them build the grouping of the whole bucket in LDS (histogram, bin
+// starts, scatter, fp64 block prefix) with workgroup barriers in between; the level solves are serial and run
+// on wavefront 0 alone; then every wavefront encodes its own elements.
+// ----------------------------------------------------------------------------------------------
+template <int W>
+struct OrqTeamLds {
+    static constexpr int D = 4096 * W;
+    static constexpr int B = W >= 4 ? 2048 : 1024;   // bins
+    static constexpr int SHIFT = W >= 4 ? 17 : 18;   // magnitude bits dropped: exponent + 6 (5) mantissa bits
+    uint32_t grouped[D + D / 32];
+    uint32_t bin_start[B + 4];
+    double block_prefix[D / 64];  // fp64 sum of all positions before block i of 64 positions
+    double lvl_sum_lt[10];
+    double lvl_sum_le[10];
+    float lvl_value[10];
+    uint32_t lvl_count_lt[10];
+    uint32_t lvl_count_le[10];
+    uint32_t lvl_rank[10];
+    TeamSlot slots[2][W];
+};
+
+template <int W, int S, int BITS, bool FULL, int RULE>
+__device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W>& lds, const float* __restrict__ g, uint32_t len,
+                                                size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
+                                                uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
+                                                uint32_t* __restrict__ codes32)
+{
+    constexpr int C = 16;
+    constexpr int D = OrqTeamLds<W>::D;
+    constexpr int B = OrqTeamLds<W>::B;
+    constexpr int HALF = B / 2;
+    constexpr int SHIFT = OrqTeamLds<W>::SHIFT;
+    constexpr bool PB = RULE == kPb;
+    constexpr uint32_t THREADS = 64u * W;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = uniform_u32(tid >> 6);
+    const uint32_t first = 4096u * wave;  // first bucket element of this wavefront
+    const uint32_t my_len = len > first ? (len - first < 4096u ? len - first : 4096u) : 0u;
+    WaveTeam<W> team{lds.slots, wave, 0u};
+
+    float v[C][4];
+    if (FULL) {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const floatx4 q =
+                __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + first + 256 * c + 4 * lane));
+            v[c][0] = q.x; v[c][1] = q.y; v[c][2] = q.z; v[c][3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t e = 256u * c + 4u * lane + k;
+                v[c][k] = e < my_len ? g[first + e] : 0.0f;
+            }
+    }
+
+    if (clip > 0.0f) {  // the same for every thread of the grid
+        float(&flat)[4 * C] = reinterpret_cast<float(&)[4 * C]>(v);
+        clip_in_registers<4 * C>(
+            flat, len, clip, [&](int j) { return FULL || (64u * (j & ~3) + 4u * lane + (j & 3) < my_len); },
+            [&](double x) { return team.sum(wave_sum(x)); });
+    }
+
+    // ---- extremes of the whole bucket ----------------------------------------------------------------
+    float lane_min = __uint_as_float(0x7F800000u), lane_max = __uint_as_float(0xFF800000u);
+    uint32_t lane_zeros = 0;
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+            lane_min = fminf(lane_min, valid ? v[c][k] : __uint_as_float(0x7F800000u));
+            lane_max = fmaxf(lane_max, valid ? v[c][k] : __uint_as_float(0xFF800000u));
+            if constexpr (PB) lane_zeros += (valid && v[c][k] == 0.0f) ? 1u : 0u;
+        }
+    float bucket_min = wave_min(lane_min), bucket_max = wave_max(lane_max);
+    uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
+    {
+        const TeamSlot* s = team.exchange((double)zeros, __float_as_uint(bucket_min), __float_as_uint(bucket_max));
+        double z = 0.0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            bucket_min = fminf(bucket_min, __uint_as_float(s[w].a));
+            bucket_max = fmaxf(bucket_max, __uint_as_float(s[w].b));
+            z += s[w].sum;
+        }
+        zeros = (uint32_t)z;
+    }
+    bucket_min += 0.0f;  // -0 -> +0
+    bucket_max += 0.0f;
+    const uint32_t key_min = float_to_key(bucket_min), key_max = float_to_key(bucket_max);
+    const uint32_t mag_max = umax32(__float_as_uint(bucket_min) & 0x7FFFFFFFu, __float_as_uint(bucket_max) & 0x7FFFFFFFu);
+    const uint32_t t_max = mag_max >> SHIFT;
+    const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
+
+    if constexpr ((S > 2 && RULE != kEven) || PB) {
+        // ---- histogram: the returning LDS add hands every element its position inside its bin ------------
+        for (uint32_t i = tid; i < (uint32_t)B; i += THREADS) lds.bin_start[i] = 0u;
+        __syncthreads();
+        uint32_t slot[C][4];  // bin | position inside the bin << 16
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                const uint32_t bits = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
+                const uint32_t u = t > t_low ? umin32(t - t_low, (uint32_t)(HALF - 1)) : 0u;  // 0 .. HALF-1 (the clamp only acts on NaN)
+                const uint32_t bin = (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
+                slot[c][k] = 0u;
+                if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
+            }
+        __syncthreads();
+
+        // ---- exclusive prefix over the bin counts (wavefront 0; lane l owns bins l*PER .. l*PER+PER-1) ------
+        if (wave == 0u) {
+            constexpr uint32_t PER = B / 64;
+            uint32_t tot = 0;
+            for (uint32_t i = 0; i < PER; ++i) tot += lds.bin_start[lane * PER + i];
+            uint32_t run = wave_inclusive_scan_u32(tot, lane) - tot;
+            for (uint32_t i = 0; i < PER; ++i) {
+                const uint32_t count = lds.bin_start[lane * PER + i];
+                lds.bin_start[lane * PER + i] = run;
+                run += count;
+            }
+            if (lane == 63u) lds.bin_start[B] = run;  // = len
+        }
+        __syncthreads();
+
+        // ---- scatter the values into their bins -------------------------------------------------------
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                if (valid) {
+                    const uint32_t bin = slot[c][k] & 0xFFFFu, pos = slot[c][k] >> 16;
+                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                }
+            }
+        __syncthreads();
+
+        // ---- fp64 prefix of the grouped values per block of 64 positions (thread t sums block t) ----------
+        {
+            double part = 0.0;
+            for (uint32_t i = 0; i < 64u; ++i) {
+                const uint32_t position = tid * 64u + i;
+                const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
+                part += (double)x;
+            }
+            const double incl = wave_inclusive_scan_f64(part, lane);
+            const TeamSlot* s = team.exchange(readlane_f64(incl, 63), 0u, 0u);
+            double before = 0.0, total = 0.0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                if ((uint32_t)w < wave) before += s[w].sum;
+                total += s[w].sum;
+            }
+            lds.block_prefix[tid] = before + (incl - part);
+            if (tid == 0u) {
+                // the bottom level is only ever the left end of a solve, the top level the right end
+                lds.lvl_count_lt[0] = 0u;
+                lds.lvl_sum_lt[0] = 0.0;
+                lds.lvl_count_le[0] = 0u;
+                lds.lvl_sum_le[0] = 0.0;
+                lds.lvl_count_le[S - 1] = len;
+                lds.lvl_sum_le[S - 1] = total;
+                lds.lvl_count_lt[S - 1] = len;
+                lds.lvl_sum_lt[S - 1] = total;
+            }
+            if (tid < (uint32_t)S) {
+                lds.lvl_value[tid] = key_to_float(tid == (uint32_t)(S - 1) ? key_max : key_min);
+                lds.lvl_rank[tid] = 0u;
+            }
+        }
+        __syncthreads();
+
+        // ---- the level solves are serial: wavefront 0 ---------------------------------------------------------
+        if (wave == 0u) {
+            const float pb_level = orq_solve_levels<S, RULE>(
+                lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); }, len, zeros, sweeps, lane);
+            if (PB && lane == 0u) {
+                lds.lvl_value[0] = -pb_level;
+                lds.lvl_value[S - 1] = pb_level;
+            }
+        }
+        __syncthreads();
+    }
+
+    float lv[S];
+    if constexpr (RULE == kEven) {
+        const double largest = (double)__uint_as_float(mag_max);
+#pragma unroll
+        for (int k = 0; k < S; ++k) lv[k] = (float)(largest * (double)(2 * k - (S - 1)) / (double)(S - 1));
+    } else if constexpr (S == 2 && !PB) {
+        lv[0] = key_to_float(key_min);
+        lv[1] = key_to_float(key_max);
+    } else {
+#pragma unroll
+        for (int k = 0; k < S; ++k) lv[k] = lds.lvl_value[k];
+    }
+    if (tid == 0u) {
+#pragma unroll
+        for (int k = 0; k < S; ++k) levels[(size_t)bucket * S + k] = lv[k];
+    }
+
+    orq_encode<C, S, BITS, FULL>(v, lv, my_len, begin + first, seed, index_offset, codes32);
+}
+
+template <int W, int S, int BITS, int RULE>
+__global__ __launch_bounds__(W* kWave) void orq_team_kernel(const float* __restrict__ grad, size_t n,
+                                                            uint32_t bucket_size, uint32_t sweeps, float clip,
+                                                            uint32_t num_buckets, uint64_t seed, uint64_t index_offset,
+                                                            float* __restrict__ levels, uint32_t* __restrict__ codes32)
+{
+    __shared__ OrqTeamLds<W> lds;
+    const uint32_t bucket = blockIdx.x;
+    if (bucket >= num_buckets) return;
+    const size_t begin = (size_t)bucket * bucket_size;
+    const size_t rest = n - begin;
+    const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
+    if (len == (uint32_t)OrqTeamLds<W>::D)
+        orq_team_bucket<W, S, BITS, true, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+    else
+        orq_team_bucket<W, S, BITS, false, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1488,13 +1781,14 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
 #undef OGQ_LAUNCH
 }
 
-void launch_bingrad_pairs(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
-                          hipStream_t st)
+template <int W>
+void launch_bingrad_team(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                         hipStream_t st)
 {
-    const dim3 grid(nb), block(2 * kWave);
+    const dim3 grid(nb), block(W * kWave);
     const bool clip = p->clip_factor > 0.0f, sign = p->scheme == OGQ_SCALED_SIGN;
 #define OGQ_LAUNCH(CLIP, SIGN)                                                                               \
-    hipLaunchKernelGGL((bingrad_pair_kernel<CLIP, SIGN>), grid, block, 0, st, g, n, p->bucket_size,         \
+    hipLaunchKernelGGL((bingrad_team_kernel<W, CLIP, SIGN>), grid, block, 0, st, g, n, p->bucket_size,      \
                        p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes))
     if (sign) {
         if (clip) OGQ_LAUNCH(true, true);
@@ -1572,6 +1866,44 @@ void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t
     }
 }
 
+// Buckets above 4096 elements: W wavefronts per bucket.
+template <int W, int S, int BITS, int RULE = kOptimal>
+void launch_orq_team(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
+{
+    hipLaunchKernelGGL((orq_team_kernel<W, S, BITS, RULE>), dim3(nb), dim3(W * kWave), 0, st, g, n, p->bucket_size,
+                       p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
+}
+
+template <int W, int RULE>
+void launch_team_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                              hipStream_t st)
+{
+    switch (p->bits) {  // 2^(bits-1) + 1 levels
+        case 2: launch_orq_team<W, 3, 2, RULE>(g, n, p, nb, lv, codes, st); break;
+        case 3: launch_orq_team<W, 5, 3, RULE>(g, n, p, nb, lv, codes, st); break;
+        default: launch_orq_team<W, 9, 4, RULE>(g, n, p, nb, lv, codes, st); break;
+    }
+}
+
+template <int W>
+void launch_orq_team_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                            hipStream_t st)
+{
+    switch (p->scheme) {
+        case OGQ_BINGRAD_PB: launch_orq_team<W, 2, 1, kPb>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_ORQ:
+            switch (p->bits) {
+                case 1: launch_orq_team<W, 2, 1>(g, n, p, nb, lv, codes, st); break;
+                case 2: launch_orq_team<W, 4, 2>(g, n, p, nb, lv, codes, st); break;
+                default: launch_orq_team<W, 8, 3>(g, n, p, nb, lv, codes, st); break;
+            }
+            break;
+        case OGQ_EVEN: launch_team_paper_counts<W, kEven>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_LINEAR: launch_team_paper_counts<W, kLinear>(g, n, p, nb, lv, codes, st); break;
+        default: launch_team_paper_counts<W, kOptimal>(g, n, p, nb, lv, codes, st); break;  // OGQ_ORQ_PAPER
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -1633,14 +1965,20 @@ int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params, floa
         else if (regs <= 8) launch_bingrad<8>(d_grad, n, params, nb, d_levels, d_codes, st);
         else if (regs <= 16) launch_bingrad<16>(d_grad, n, params, nb, d_levels, d_codes, st);
         else if (regs <= 32) launch_bingrad<32>(d_grad, n, params, nb, d_levels, d_codes, st);
-        else launch_bingrad_pairs(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (regs <= 64) launch_bingrad_team<2>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (regs <= 128) launch_bingrad_team<4>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (regs <= 256) launch_bingrad_team<8>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else launch_bingrad_team<16>(d_grad, n, params, nb, d_levels, d_codes, st);
     } else {
         const uint32_t chunks = (d + 255) / 256;
         if (chunks <= 1) launch_orq_levels<1>(d_grad, n, params, nb, d_levels, d_codes, st);
         else if (chunks <= 2) launch_orq_levels<2>(d_grad, n, params, nb, d_levels, d_codes, st);
         else if (chunks <= 4) launch_orq_levels<4>(d_grad, n, params, nb, d_levels, d_codes, st);
         else if (chunks <= 8) launch_orq_levels<8>(d_grad, n, params, nb, d_levels, d_codes, st);
-        else launch_orq_levels<16>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 16) launch_orq_levels<16>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 32) launch_orq_team_levels<2>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else if (chunks <= 64) launch_orq_team_levels<4>(d_grad, n, params, nb, d_levels, d_codes, st);
+        else launch_orq_team_levels<8>(d_grad, n, params, nb, d_levels, d_codes, st);
     }
     return finish_launch();
 }

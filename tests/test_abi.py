@@ -81,7 +81,7 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert q(A + 4, 100, ok, A, A) == -6
     assert q(A, 100, ogq.make_params(0, 1, ogq.BINGRAD_B), A, A) == -2
     assert q(A, 100, ogq.make_params(100, 1, ogq.BINGRAD_B), A, A) == -2
-    assert q(A, 100, ogq.make_params(8192, 1, ogq.BINGRAD_B), A, A) == -2
+    assert q(A, 100, ogq.make_params(32768 + 64, 1, ogq.BINGRAD_B), A, A) == -2
     assert q(A, 100, ogq.make_params(2048, 2, ogq.BINGRAD_B), A, A) == -3
     assert q(A, 100, ogq.make_params(2048, 4, ogq.ORQ), A, A) == -3
     assert q(A, 100, ogq.make_params(2048, 0, ogq.ORQ), A, A) == -3

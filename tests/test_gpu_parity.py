@@ -248,6 +248,61 @@ def test_scaled_sign_resnet50_size():
     assert e_b <= e_s * 1.001
 
 
+# ------------------------------------------------------------------------------------------------
+# buckets above 4096 elements (the paper's bucket-size sweep goes to 32768): several wavefronts per bucket
+# ------------------------------------------------------------------------------------------------
+LARGE_SCHEMES = [(ogq.BINGRAD_B, 1), (ogq.SCALED_SIGN, 1), (ogq.BINGRAD_PB, 1), (ogq.ORQ, 1), (ogq.ORQ, 2), (ogq.ORQ, 3),
+                 (ogq.ORQ_PAPER, 2), (ogq.ORQ_PAPER, 3), (ogq.ORQ_PAPER, 4), (ogq.EVEN, 2), (ogq.EVEN, 4),
+                 (ogq.LINEAR, 2), (ogq.LINEAR, 3)]
+
+
+@pytest.mark.parametrize("scheme,bits", LARGE_SCHEMES)
+@pytest.mark.parametrize("d", [4160, 6144, 8192, 16384, 20480, 32768])
+def test_buckets_above_4096(scheme, bits, d):
+    rng = np.random.default_rng(d + 31 * scheme + bits)
+    stride = oracle.levels_per_bucket(scheme, bits)
+    cases = [("normal", d), ("heavy", 2 * d + 777), ("ints", d + 4097), ("const", d - 1), ("zeros", 65),
+             ("shifted", 3 * d)]
+    for kind, n in cases:
+        g = _rng_bucket(rng, n, kind)
+        for iters in ((0, 2) if kind in ("normal", "heavy") else (1,)):
+            lv, codes, rep = parity.check_quantize(g, d, bits, scheme, iters, seed=n + 5, index_offset=64 * 77,
+                                                   tag=f"large-s{scheme}b{bits}-{kind}-d{d}-n{n}-it{iters}")
+        out = ogq.ogq_dequantize_average([codes], [lv], n, ogq.make_params(d, bits, scheme))
+        torch.cuda.synchronize()
+        l, w = oracle.quantize(g, d, bits, scheme, iters, n + 5, 64 * 77)
+        assert np.array_equal(out.cpu().numpy(), oracle.dequantize_average([w], [l], n, d, bits, stride)), (kind, n)
+    g = _rng_bucket(rng, 2 * d + 5, "heavy")
+    parity.check_quantize(g, d, bits, scheme, 1, seed=3, clip_factor=2.5, tag=f"large-clip-s{scheme}b{bits}-d{d}")
+
+
+def test_bucket_size_sweep_of_the_paper_at_resnet50_size():
+    """ORQ-3 and TernGrad-noclip over the bucket sizes of the paper's CIFAR-10 sweep (128 .. 32768), sampled
+    buckets against the oracle; the expected rounding error per element must grow with the bucket size for
+    both and stay lower for ORQ-3 (the trend behind the accuracy table of Section 5.1)."""
+    wl = synth.WORKLOADS["cfg3"]
+    g = wl.gradient()[:8_000_000]
+    err = {ogq.ORQ_PAPER: [], ogq.EVEN: []}
+    sizes = (128, 512, 1024, 2048, 4096, 8192, 16384, 32768)
+    for d in sizes:
+        nb = (g.size + d - 1) // d
+        for scheme in err:
+            picks = _sample(nb, max(8, 65536 // d), d + scheme)
+            lv, codes, rep = parity.check_quantize(g, d, 2, scheme, 0, seed=13, buckets=picks, tag=f"sweep-s{scheme}-d{d}")
+            table = lv[:nb * 3].cpu().numpy().reshape(nb, 3)
+            e, cnt = 0.0, 0
+            for b in picks:
+                x = g[b * d:min((b + 1) * d, g.size)]
+                e += _rounding_error(x, table[b])
+                cnt += x.size
+            err[scheme].append(e / cnt)
+    print("[parity] expected rounding error per element by bucket size", sizes, {k: [f"{x:.3e}" for x in v] for k, v in err.items()},
+          flush=True)
+    for i in range(len(sizes)):
+        assert err[ogq.ORQ_PAPER][i] < err[ogq.EVEN][i]
+    assert err[ogq.ORQ_PAPER][-1] > err[ogq.ORQ_PAPER][0] and err[ogq.EVEN][-1] > err[ogq.EVEN][0]
+
+
 def test_orq_sweeps_and_offsets():
     rng = np.random.default_rng(77)
     g = _rng_bucket(rng, 8 * 1024 + 100, "heavy")
