@@ -1,0 +1,35 @@
+// Internal header of libogq: the host-side launchers each kernel source exports to the C ABI in api.hip.
+// A launcher only enqueues; the caller picks up launch errors with hipGetLastError.
+#ifndef OGQ_LAUNCH_H
+#define OGQ_LAUNCH_H
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ogq.h"
+
+namespace ogq {
+
+// Levels per bucket, 0 for a scheme / bits combination that does not exist.
+uint32_t levels_per_bucket(uint32_t scheme, uint32_t bits);
+
+// BinGrad-b and Scaled SignSGD (bingrad.hip): picks the kernel for the bucket size and gradient length.
+void launch_two_level(const float* g, size_t n, const ogq_params_t* p, float* lv, void* codes, hipStream_t st);
+
+// The schemes with random rounding (rounding_part.hip, one object file per bucket capacity): _cN = one
+// wavefront per bucket of at most 256*N elements, _wN = N wavefronts per bucket of at most 4096*N elements.
+// nb = number of buckets.
+typedef void RoundingLauncher(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                              hipStream_t st);
+RoundingLauncher launch_rounding_c1, launch_rounding_c2, launch_rounding_c4, launch_rounding_c8, launch_rounding_c16,
+    launch_rounding_w2, launch_rounding_w4, launch_rounding_w8;
+
+// Decode + average and the bandwidth probes (decode.hip).  Pointers already validated.
+void launch_decode(const void* const* d_codes, const float* const* d_levels, uint32_t num_workers, size_t n,
+                   const ogq_params_t* p, float* d_out, hipStream_t st);
+void launch_probe_read(const float* d_src, size_t n, float* d_sink, hipStream_t st);
+void launch_probe_copy(const float* d_src, float* d_dst, size_t n, hipStream_t st);
+
+}  // namespace ogq
+#endif  // OGQ_LAUNCH_H

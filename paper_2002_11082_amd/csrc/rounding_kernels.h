@@ -1,0 +1,998 @@
+// Internal header of libogq: the quantize kernels of the schemes with random rounding (ORQ: Theorem 1, its
+// discrete remark, Corollary 1, Algorithm 1 and the random rounding of Section 3.1 of arXiv 2002.11082;
+// BinGrad-pb; evenly spaced and Linear-s levels) and their launcher templates.  Included by rounding_part.hip,
+// which instantiates one bucket capacity per object file.  Compile with -ffp-contract=off: the rounding decision
+// is specified operation by operation in fp32.
+#ifndef OGQ_ROUNDING_KERNELS_H
+#define OGQ_ROUNDING_KERNELS_H
+
+#include "device_common.h"
+
+namespace ogq {
+
+// ----------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter (c0, c1, 0, 0), key (k0, k1).
+// ----------------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1, uint32_t (&r)[4])
+{
+    uint32_t c2 = 0, c3 = 0;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t pa = (uint64_t)0xD2511F53u * c0;
+        const uint64_t pb = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)pb;
+        c3 = (uint32_t)pa;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    r[0] = c0; r[1] = c1; r[2] = c2; r[3] = c3;
+}
+
+// ----------------------------------------------------------------------------------------------
+// ORQ quantize.  One wavefront (= one workgroup) owns one bucket.  Lane l holds, for chunk c, the
+// four consecutive bucket elements 256*c + 4*l + {0,1,2,3} (one 16-byte load), which are also the
+// four elements that share one Philox block.
+//
+// A level solve needs (a) counts and sums of the elements below a level and (b) the element of a
+// given rank.  The bucket is therefore grouped once, in LDS, by a monotone bin of the value (sign,
+// exponent and top mantissa bits, relative to the largest magnitude of the bucket; everything more
+// than 16 binades below that shares the two centre bins).  Per-bin counts and fp64 sums are
+// prefix-summed; after that a solve touches one bin: the bin holding the wanted rank is sorted
+// across the 64 lanes, and the counts and sums below the chosen element are added to the bin's
+// prefix.  All values of a regular bin share sign and exponent, so its fp64 sum is exact.
+// ----------------------------------------------------------------------------------------------
+// Order-preserving map of fp32 onto unsigned integers.
+__device__ __forceinline__ uint32_t float_to_key(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+}
+
+__device__ __forceinline__ float key_to_float(uint32_t k)
+{
+    const uint32_t u = (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
+    return __uint_as_float(u);
+}
+
+// Order of the greedy solves (Algorithm 1): the level in the middle of [l, r] is solved from the
+// two outer levels, then both halves are treated the same way; the middle index is rounded down
+// when s is not of the form 2^K + 1.  Each step is packed as 4 bits of k, l, r; five steps per word.
+struct GreedyOrder {
+    uint64_t packed[2];
+    int count;
+};
+
+constexpr void greedy_visit(GreedyOrder& o, int l, int r)
+{
+    if (r - l < 2) return;
+    const int mid = (l + r) / 2;
+    o.packed[o.count / 5] |= (uint64_t)(mid | (l << 4) | (r << 8)) << (12 * (o.count % 5));
+    ++o.count;
+    greedy_visit(o, l, mid);
+    greedy_visit(o, mid, r);
+}
+
+template <int S>
+constexpr GreedyOrder greedy_order()
+{
+    GreedyOrder o{{0, 0}, 0};
+    greedy_visit(o, 0, S - 1);
+    return o;
+}
+
+// LDS of one bucket: D = element capacity, B = number of bins.
+template <int D_, int B_>
+struct OrqLds {
+    static constexpr int D = D_, B = B_;
+    // fp32 bit patterns (-0 stored as +0) grouped by bin, unsorted inside a bin.  Position i lives at
+    // word i + i/32, so that the 64 lanes reading consecutive blocks of D/64 positions hit distinct banks.
+    uint32_t grouped[D + D / 32];
+    uint32_t bin_start[B + 4];  // histogram, then first position of each bin; [B] = bucket length
+    double block_prefix[64];    // fp64 sum of all positions before block l (block = D/64 positions)
+    // per level k: value; #{v < value}; #{v <= value}; sum{v < value}; sum{v <= value}; the rank it
+    // was picked at (0 = not picked by rank)
+    double lvl_sum_lt[10];
+    double lvl_sum_le[10];
+    float lvl_value[10];
+    uint32_t lvl_count_lt[10];
+    uint32_t lvl_count_le[10];
+    uint32_t lvl_rank[10];
+};
+
+__device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 5); }
+
+__device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__device__ __forceinline__ uint32_t umax32(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
+{
+    x = umax32(x, dpp_u32<kDppXor1>(x));
+    x = umax32(x, dpp_u32<kDppXor2>(x));
+    x = umax32(x, dpp_u32<kDppHalfMirror>(x));
+    x = umax32(x, dpp_u32<kDppMirror>(x));
+    return umax32(umax32(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+                  umax32(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
+}
+
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) { return ~wave_max_u32(~x); }
+
+// Inclusive scans over the lanes in ascending lane order.
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t x, uint32_t lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t y = (uint32_t)__shfl_up((int)x, off, kWave);
+        x += (lane >= (uint32_t)off) ? y : 0u;
+    }
+    return x;
+}
+
+__device__ __forceinline__ double wave_inclusive_scan_f64(double x, uint32_t lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double y = __shfl_up(x, off, kWave);
+        x += (lane >= (uint32_t)off) ? y : 0.0;
+    }
+    return x;
+}
+
+// Ascending bitonic sort of one key per lane across the 64 lanes.
+template <int K, int DIST>
+__device__ __forceinline__ uint32_t bitonic_step(uint32_t x, uint32_t lane)
+{
+    const uint32_t y = lane_xor<DIST>(x, lane);
+    const bool ascending = (lane & (uint32_t)K) == 0;
+    const bool lower = (lane & (uint32_t)DIST) == 0;
+    const uint32_t mn = umin32(x, y), mx = umax32(x, y);
+    return (ascending == lower) ? mn : mx;
+}
+
+__device__ __forceinline__ uint32_t wave_sort_u32(uint32_t x, uint32_t lane)
+{
+    x = bitonic_step<2, 1>(x, lane);
+    x = bitonic_step<4, 2>(x, lane);   x = bitonic_step<4, 1>(x, lane);
+    x = bitonic_step<8, 4>(x, lane);   x = bitonic_step<8, 2>(x, lane);   x = bitonic_step<8, 1>(x, lane);
+    x = bitonic_step<16, 8>(x, lane);  x = bitonic_step<16, 4>(x, lane);  x = bitonic_step<16, 2>(x, lane);
+    x = bitonic_step<16, 1>(x, lane);
+    x = bitonic_step<32, 16>(x, lane); x = bitonic_step<32, 8>(x, lane);  x = bitonic_step<32, 4>(x, lane);
+    x = bitonic_step<32, 2>(x, lane);  x = bitonic_step<32, 1>(x, lane);
+    x = bitonic_step<64, 32>(x, lane); x = bitonic_step<64, 16>(x, lane); x = bitonic_step<64, 8>(x, lane);
+    x = bitonic_step<64, 4>(x, lane);  x = bitonic_step<64, 2>(x, lane);  x = bitonic_step<64, 1>(x, lane);
+    return x;
+}
+
+// The bucket element of a given rank, with the counts and sums of the bucket elements strictly
+// below it and not above it.
+struct Picked {
+    uint32_t key;
+    uint32_t count_lt, count_le;
+    double sum_lt, sum_le;
+};
+
+// The element of 1-based rank `rank`, which lies in bin `bin`.  BLOCK = positions per entry of the fp64
+// block prefix (at most 64).
+template <int BLOCK, class Lds>
+__device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint32_t rank, uint32_t lane)
+{
+    static_assert(BLOCK <= 64, "the head of a block is read one position per lane");
+    const uint32_t first = uniform_u32(lds.bin_start[bin]);
+    const uint32_t count = uniform_u32(lds.bin_start[bin + 1]) - first;
+    const uint32_t r_in = rank - first;  // 1-based rank inside the bin
+
+    // sum of everything before the bin = prefix of its block + the block's positions before `first`
+    const uint32_t block = first / BLOCK;
+    const uint32_t block_first = block * BLOCK;
+    const double before_block = uniform_f64(lds.block_prefix[block]);
+    const float head = lane < first - block_first ? __uint_as_float(lds.grouped[skewed(block_first + lane)]) : 0.0f;
+
+    uint32_t key, c_lt, c_le;
+    double s_lt;
+    if (count <= 64u) {
+        const uint32_t mine =
+            lane < count ? float_to_key(__uint_as_float(lds.grouped[skewed(first + lane)])) : 0xFFFFFFFFu;
+        const uint32_t sorted = wave_sort_u32(mine, lane);
+        key = __builtin_amdgcn_readlane(sorted, r_in - 1u);
+        const bool lt = sorted < key;
+        const bool le = (sorted <= key) && (lane < count);
+        c_lt = (uint32_t)__popcll(__ballot(lt));
+        c_le = (uint32_t)__popcll(__ballot(le));
+        s_lt = wave_sum((double)head + (lt ? (double)key_to_float(sorted) : 0.0));
+    } else {
+        // a crowded bin (many equal or nearly equal values): bisection on the key over all its chunks
+        uint32_t prefix = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand = prefix | (1u << bit);
+            uint32_t below = 0;
+            for (uint32_t base = 0; base < count; base += 64u) {
+                const uint32_t i = base + lane;
+                const uint32_t k = i < count ? float_to_key(__uint_as_float(lds.grouped[skewed(first + i)])) : 0xFFFFFFFFu;
+                below += (uint32_t)__popcll(__ballot(k < cand));
+            }
+            if (below < r_in) prefix = cand;
+        }
+        key = prefix;
+        c_lt = 0;
+        c_le = 0;
+        double part = (double)head;
+        for (uint32_t base = 0; base < count; base += 64u) {
+            const uint32_t i = base + lane;
+            const float x = i < count ? __uint_as_float(lds.grouped[skewed(first + i)]) : 0.0f;
+            const uint32_t k = i < count ? float_to_key(x) : 0xFFFFFFFFu;
+            const bool lt = k < key;
+            c_lt += (uint32_t)__popcll(__ballot(lt));
+            c_le += (uint32_t)__popcll(__ballot(k <= key && i < count));
+            part += lt ? (double)x : 0.0;
+        }
+        s_lt = wave_sum(part);
+    }
+    Picked p;
+    p.key = key;
+    p.count_lt = first + c_lt;
+    p.count_le = first + c_le;
+    p.sum_lt = before_block + s_lt;
+    p.sum_le = p.sum_lt + (double)(c_le - c_lt) * (double)key_to_float(key);
+    return p;
+}
+
+// rank is 1-based, 1 <= rank <= bucket length.  my_start[t] = bin_start[lane * PER + t], kept in registers.
+template <int D, int B>
+__device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint32_t (&my_start)[B / 64],
+                                            uint32_t rank, uint32_t lane)
+{
+    constexpr int PER = B / 64;
+    // the bin holding the rank: the last bin whose first position is below the rank
+    uint32_t starts_below = 0;
+#pragma unroll
+    for (int t = 0; t < PER; ++t) starts_below += (my_start[t] < rank) ? 1u : 0u;
+    const uint32_t bin = wave_sum_u32(starts_below) - 1u;  // bin_start[0] = 0 < rank: at least one
+    return pick_in_bin<D / 64>(lds, bin, rank, lane);
+}
+
+// The same with the bin found by two looks into LDS (every (B/64)-th bin start, then the B/64 bins in between):
+// no registers are tied up by the bin starts.
+template <class Lds>
+__device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t rank, uint32_t lane)
+{
+    constexpr uint32_t PER = Lds::B / 64;
+    static_assert(PER <= 64, "one lane per bin of a segment");
+    const uint32_t segment = (uint32_t)__popcll(__ballot(lds.bin_start[lane * PER] < rank)) - 1u;
+    const bool below = lane < PER && lds.bin_start[segment * PER + (lane < PER ? lane : 0u)] < rank;
+    const uint32_t bin = segment * PER + (uint32_t)__popcll(__ballot(below)) - 1u;
+    return pick_in_bin<64>(lds, bin, rank, lane);
+}
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Returns x unchanged but hides it from common-subexpression elimination, so that values derived
+// from the register-resident bucket are recomputed in each phase instead of being kept alive.
+__device__ __forceinline__ float recompute_from(float x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+// ---- encode (random rounding, Section 3.1) + pack ------------------------------------------------
+// v: the 256*C elements a wavefront holds (lane l, chunk c: elements 256c + 4l + {0..3} of the range that
+// starts at global element `begin` and has `len` valid elements; FULL: len == 256*C); lv: the levels.
+template <int C, int S, int BITS, bool FULL>
+__device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (&lv)[S], uint32_t len, size_t begin,
+                                           uint64_t seed, uint64_t index_offset, uint32_t* __restrict__ codes32)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    // Per element only the level compares, the selects of (level below, interval width) and the rounding
+    // test run on the vector unit; the level index is assembled from the compare masks on the scalar unit
+    // (the masks are a thermometer code of the interval, to which the rounding bit is added with carry).
+    float width[S - 1];
+#pragma unroll
+    for (int k = 0; k < S - 1; ++k) width[k] = lv[k + 1] - lv[k];
+    uint32_t bit_of[4];  // where element k of this lane sits in its 32-bit half of a packed word
+#pragma unroll
+    for (int k = 0; k < 4; ++k) bit_of[k] = 1u << (4u * (lane & 7u) + k);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint32_t padded_len = (len + 63u) & ~63u;
+    const size_t word0 = begin / 64;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const uint64_t block = (index_offset + begin + 256u * c + 4u * lane) >> 2;
+        uint32_t r[4];
+        philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), k0, k1, r);
+        uint32_t plane[BITS];
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) plane[p] = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float x = v[c][k];
+            // interval: last level not above x, at most S-2
+            uint64_t not_below[S];  // [t]: lanes whose element is >= level t, t = 1 .. S-2
+            float base = lv[0], w = width[0];
+#pragma unroll
+            for (int t = 1; t < S - 1; ++t) {
+                const bool ge = lv[t] <= x;
+                not_below[t] = __ballot(ge);
+                base = ge ? lv[t] : base;
+                w = ge ? width[t] : w;
+            }
+            const float delta = x - base;
+            const float u = (float)(r[k] >> 8) * 0x1p-24f;
+            const float scaled = u * w;
+            uint64_t carry = __ballot(scaled < delta);  // rounded up
+            if constexpr (!FULL) carry &= __ballot(256u * c + 4u * lane + k < len);
+#pragma unroll
+            for (int p = 0; p < BITS; ++p) {
+                // bit p of the number of levels 1..S-2 not above x
+                uint64_t index_bit = 0;
+#pragma unroll
+                for (int j = 1; (j << p) <= S - 2; j += 2) {
+                    const int lo_t = j << p, hi_t = (j + 1) << p;
+                    index_bit |= hi_t <= S - 2 ? (not_below[lo_t] & ~not_below[hi_t]) : not_below[lo_t];
+                }
+                if constexpr (!FULL) index_bit &= __ballot(256u * c + 4u * lane + k < len);
+                const uint64_t code_bit = index_bit ^ carry;
+                carry &= index_bit;
+                plane[p] |= __builtin_amdgcn_inverse_ballot_w64(code_bit) ? bit_of[k] : 0u;
+            }
+        }
+        // OR over the 8 lanes that make up one 32-bit half of a packed word
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) {
+            uint32_t x = plane[p];
+            x |= dpp_u32<kDppXor1>(x);
+            x |= dpp_u32<kDppXor2>(x);
+            x |= dpp_u32<kDppHalfMirror>(x);
+            const uint32_t first = 256u * c + 32u * (lane >> 3);  // first element of this half word
+            if ((lane & 7u) == 0 && first < padded_len) {
+                const size_t word = (word0 + 4u * c + (lane >> 4)) * BITS + p;
+                codes32[word * 2 + ((lane >> 3) & 1u)] = x;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Where the levels come from; all rules share the random-rounding encoder.
+//   kOptimal: ORQ (Theorem 1, Algorithm 1).
+//   kPb: BinGrad-pb (Section 3.2): two levels -b_1, +b_1 from the scheme's optimal condition instead of the
+//        bucket extremes; the encoder then clamps everything outside them.
+//   kEven: QSGD-s / TernGrad (Section 3.1): S levels evenly spaced from -M to +M, M the largest magnitude.
+//   kLinear: Linear-s (Section 5): the order statistics at the fractions k/(S-1) of the sorted bucket.
+enum LevelRule { kOptimal = 0, kPb = 1, kEven = 2, kLinear = 3 };
+
+// The level solves of one bucket, run by one wavefront once the bucket is grouped in LDS and the level
+// records of the two ends are set.  pick(rank) returns the element of that 1-based rank (Picked); `zeros` is the
+// number of zeros in the bucket (BinGrad-pb only).  Interior levels end up in lds.lvl_value; returns b_1 for
+// BinGrad-pb.
+template <int S, int RULE, class Lds, class PickFn>
+__device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, uint32_t len, uint32_t zeros, uint32_t sweeps,
+                                                  uint32_t lane)
+{
+    constexpr bool PB = RULE == kPb;
+    float pb_level = 0.0f;
+    if constexpr (PB) {
+        // ---- b_1: minimise |b * #{v > 0} - sum_{v >= b} v| over the positive bucket values.  The
+        //      difference grows with b, so the minimiser is one of the two values around its sign
+        //      change, which a bisection over the ranks of the positive values finds. -------------
+                const uint32_t not_positive = uniform_u32(lds.bin_start[Lds::B / 2]) + zeros;  // negatives fill the lower bins
+        const uint32_t positives = len - not_positive;
+        const double total = uniform_f64(lds.lvl_sum_le[S - 1]);
+        if (positives > 0u) {
+            uint32_t lo = not_positive + 1u, hi = len;  // 1-based ranks; the largest value always has gap >= 0
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                const Picked p = pick(mid);
+                const double gap = (double)key_to_float(p.key) * (double)positives - (total - p.sum_lt);
+                if (gap >= 0.0) hi = mid;
+                else lo = mid + 1u;
+            }
+            const Picked up = pick(lo);
+            const double gap_up = (double)key_to_float(up.key) * (double)positives - (total - up.sum_lt);
+            pb_level = key_to_float(up.key);
+            if (up.count_lt > not_positive) {  // a smaller positive value exists: rank count_lt is the next one down
+                const Picked down = pick(up.count_lt);
+                const double gap_down =
+                    (double)key_to_float(down.key) * (double)positives - (total - down.sum_lt);
+                if (fabs(gap_down) <= fabs(gap_up)) pb_level = key_to_float(down.key);  // ties take the smaller value
+            }
+        }
+    }
+
+    if constexpr (RULE == kLinear) {
+        for (uint32_t k = 1; k + 1 < (uint32_t)S; ++k) {
+            const uint32_t rank = 1u + (uint32_t)(((uint64_t)k * (len - 1u)) / (uint32_t)(S - 1));
+            const Picked p = pick(rank);
+            if (lane == 0u) lds.lvl_value[k] = key_to_float(p.key);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- level solves: greedy recursion (Algorithm 1), then re-solve sweeps ------------------
+    if constexpr (S > 2 && RULE == kOptimal) {
+    constexpr GreedyOrder order = greedy_order<S>();
+    const uint32_t steps = order.count + sweeps * (S - 2);
+    for (uint32_t step = 0; step < steps; ++step) {
+        uint32_t k, l, r;
+        if (step < (uint32_t)order.count) {
+            const uint32_t e = step < 5u ? (uint32_t)(order.packed[0] >> (12 * step))
+                                         : (uint32_t)(order.packed[1] >> (12 * (step - 5u)));
+            k = e & 15u; l = (e >> 4) & 15u; r = (e >> 8) & 15u;
+        } else {
+            k = 1u + (step - order.count) % (S - 2);
+            l = k - 1u; r = k + 1u;
+        }
+        const float L = uniform_f32(lds.lvl_value[l]);
+        const float R = uniform_f32(lds.lvl_value[r]);
+        const uint32_t cnt_lt_L = uniform_u32(lds.lvl_count_lt[l]);
+        const uint32_t cnt_le_R = uniform_u32(lds.lvl_count_le[r]);
+        const double sum_lt_L = uniform_f64(lds.lvl_sum_lt[l]);
+        const double sum_le_R = uniform_f64(lds.lvl_sum_le[r]);
+        bool copy_left = !(L < R);
+        Picked p;
+        uint32_t rank = 0;
+        if (!copy_left) {
+            // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
+            const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
+            const double T = Ssum / ((double)R - (double)L);
+            double m = floor(T);
+            if (!(m >= 0.0)) m = 0.0;
+            rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
+            rank = rank < 1u ? 1u : (rank > len ? len : rank);
+            if (rank == uniform_u32(lds.lvl_rank[k])) continue;  // same element as last time
+            p = pick(rank);
+            if (key_to_float(p.key) < L) copy_left = true;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0u) {
+            if (copy_left) {
+                // the level coincides with the left end (L == R, or rounding put it below L)
+                lds.lvl_value[k] = L;
+                lds.lvl_count_lt[k] = cnt_lt_L;
+                lds.lvl_sum_lt[k] = sum_lt_L;
+                lds.lvl_count_le[k] = (L < R) ? uniform_u32(lds.lvl_count_le[l]) : cnt_le_R;
+                lds.lvl_sum_le[k] = (L < R) ? uniform_f64(lds.lvl_sum_le[l]) : sum_le_R;
+                lds.lvl_rank[k] = 0u;
+            } else {
+                lds.lvl_value[k] = key_to_float(p.key);
+                lds.lvl_count_lt[k] = p.count_lt;
+                lds.lvl_count_le[k] = p.count_le;
+                lds.lvl_sum_lt[k] = p.sum_lt;
+                lds.lvl_sum_le[k] = p.sum_le;
+                lds.lvl_rank[k] = rank;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    }
+    return pb_level;
+}
+
+template <int C>
+struct OrqShape {
+    static constexpr int D = 256 * C;               // element capacity of the wave
+    static constexpr int B = C >= 16 ? 512 : 256;   // bins
+    static constexpr int SHIFT = C >= 16 ? 19 : 20; // magnitude bits dropped: keeps exponent + 4 (3) mantissa bits
+};
+
+// FULL: the bucket has exactly 256*C elements (no padding, no per-element validity tests).
+// S levels per bucket, BITS bits per level index (S = 2^BITS, or 2^(BITS-1) + 1 for the paper's counts).
+template <int C, int S, int BITS, bool FULL, bool CLIP, int RULE>
+__device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B>& lds, const float* __restrict__ g,
+                                           uint32_t len, size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
+                                           uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
+                                           uint32_t* __restrict__ codes32)
+{
+    static_assert(S >= 2 && S <= 9 && S <= (1 << BITS), "level count does not fit the index width");
+    constexpr int D = OrqShape<C>::D;
+    constexpr int B = OrqShape<C>::B;
+    constexpr int PER = B / 64;   // bins per lane in the prefix step
+    constexpr int HALF = B / 2;   // bins per sign
+    constexpr int SHIFT = OrqShape<C>::SHIFT;
+    constexpr bool full = FULL;
+    constexpr bool PB = RULE == kPb;
+    const uint32_t lane = threadIdx.x & 63u;
+
+    // ---- load (read once: bypass the caches); padding holds +0 and is never binned or encoded ----
+    float v[C][4];
+    if (full) {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + 256 * c + 4 * lane));
+            v[c][0] = q.x; v[c][1] = q.y; v[c][2] = q.z; v[c][3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t e = 256u * c + 4u * lane + k;
+                v[c][k] = e < len ? g[e] : 0.0f;
+            }
+    }
+
+    if constexpr (CLIP) {
+        float(&flat)[4 * C] = reinterpret_cast<float(&)[4 * C]>(v);
+        clip_in_registers<4 * C>(flat, len, clip, [&](int j) { return full || (64u * (j & ~3) + 4u * lane + (j & 3) < len); });
+    }
+
+    // ---- extremes ------------------------------------------------------------------------------
+    float lane_min = __uint_as_float(0x7F800000u), lane_max = __uint_as_float(0xFF800000u);
+    uint32_t lane_zeros = 0;
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool valid = full || (256u * c + 4u * lane + k < len);
+            lane_min = fminf(lane_min, valid ? v[c][k] : __uint_as_float(0x7F800000u));
+            lane_max = fmaxf(lane_max, valid ? v[c][k] : __uint_as_float(0xFF800000u));
+            if constexpr (PB) lane_zeros += (valid && v[c][k] == 0.0f) ? 1u : 0u;
+        }
+    const float bucket_min = wave_min(lane_min) + 0.0f;  // -0 -> +0
+    const float bucket_max = wave_max(lane_max) + 0.0f;
+    const uint32_t key_min = float_to_key(bucket_min), key_max = float_to_key(bucket_max);
+    const uint32_t mag_max = umax32(__float_as_uint(bucket_min) & 0x7FFFFFFFu, __float_as_uint(bucket_max) & 0x7FFFFFFFu);
+    const uint32_t t_max = mag_max >> SHIFT;
+    const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
+
+    float pb_level = 0.0f;
+    if constexpr ((S > 2 && RULE != kEven) || PB) {
+        // ---- histogram: the returning LDS add hands every element its position inside its bin ------
+#pragma unroll
+        for (int t = 0; t < PER; ++t) lds.bin_start[lane * PER + t] = 0u;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        uint32_t slot[C][4];  // bin | position inside the bin << 16
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = full || (256u * c + 4u * lane + k < len);
+                const uint32_t bits = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
+                const uint32_t u = t > t_low ? umin32(t - t_low, (uint32_t)(HALF - 1)) : 0u;  // 0 .. HALF-1 (the clamp only acts on NaN)
+                const uint32_t bin = (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
+                slot[c][k] = 0u;
+                if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
+            }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- exclusive prefix over the bin counts (lane l owns bins l*PER .. l*PER+PER-1) ------------
+        uint32_t my_start[PER];
+        {
+            uint32_t cnt[PER];
+            uint32_t tot = 0;
+#pragma unroll
+            for (int t = 0; t < PER; ++t) {
+                cnt[t] = lds.bin_start[lane * PER + t];
+                tot += cnt[t];
+            }
+            uint32_t run = wave_inclusive_scan_u32(tot, lane) - tot;
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int t = 0; t < PER; ++t) {
+                my_start[t] = run;
+                lds.bin_start[lane * PER + t] = run;
+                run += cnt[t];
+            }
+            if (lane == 63u) lds.bin_start[B] = run;  // = len
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- scatter the values into their bins ---------------------------------------------------
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = full || (256u * c + 4u * lane + k < len);
+                if (valid) {
+                    const uint32_t bin = slot[c][k] & 0xFFFFu, pos = slot[c][k] >> 16;
+                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                }
+            }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- fp64 prefix of the grouped values at block granularity (lane l sums block l) ------------
+        {
+            constexpr uint32_t BLOCK = D / 64;
+            double part = 0.0;
+#pragma unroll
+            for (uint32_t i = 0; i < BLOCK; ++i) {
+                const uint32_t position = lane * BLOCK + i;
+                const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
+                part += (double)x;
+            }
+            const double incl = wave_inclusive_scan_f64(part, lane);
+            lds.block_prefix[lane] = incl - part;
+            if (lane == 63u) {
+                // the top level is only ever the right end of a solve
+                lds.lvl_count_le[S - 1] = len;
+                lds.lvl_sum_le[S - 1] = incl;
+                lds.lvl_count_lt[S - 1] = len;
+                lds.lvl_sum_lt[S - 1] = incl;
+            }
+        }
+        if (lane == 0u) {
+            // the bottom level is only ever the left end of a solve
+            lds.lvl_count_lt[0] = 0u;
+            lds.lvl_sum_lt[0] = 0.0;
+            lds.lvl_count_le[0] = 0u;
+            lds.lvl_sum_le[0] = 0.0;
+        }
+        if (lane < (uint32_t)S) {
+            lds.lvl_value[lane] = key_to_float(lane == (uint32_t)(S - 1) ? key_max : key_min);
+            lds.lvl_rank[lane] = 0u;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        const uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
+        pb_level = orq_solve_levels<S, RULE>(
+            lds, [&](uint32_t rank) { return pick_rank<D, B>(lds, my_start, rank, lane); }, len, zeros, sweeps, lane);
+    }
+
+    // every lane holds its own copy of the levels (the selects of the encoder take vector sources)
+    float lv[S];
+    if constexpr (RULE == kEven) {
+        const double largest = (double)__uint_as_float(mag_max);
+#pragma unroll
+        for (int k = 0; k < S; ++k) lv[k] = (float)(largest * (double)(2 * k - (S - 1)) / (double)(S - 1));
+    } else {
+        lv[0] = PB ? -pb_level : key_to_float(key_min);
+        lv[S - 1] = PB ? pb_level : key_to_float(key_max);
+#pragma unroll
+        for (int k = 1; k < S - 1; ++k) lv[k] = lds.lvl_value[k];
+    }
+
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < S; ++k) levels[(size_t)bucket * S + k] = lv[k];
+    }
+
+    orq_encode<C, S, BITS, FULL>(v, lv, len, begin, seed, index_offset, codes32);
+}
+
+template <int C, int S, int BITS, bool CLIP, int RULE>
+__global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
+                                                             uint32_t bucket_size, uint32_t sweeps, float clip,
+                                                             uint32_t num_buckets, uint64_t seed,
+                                                             uint64_t index_offset, float* __restrict__ levels,
+                                                             uint32_t* __restrict__ codes32)
+{
+    __shared__ OrqLds<OrqShape<C>::D, OrqShape<C>::B> lds;
+    const uint32_t bucket = blockIdx.x;
+    if (bucket >= num_buckets) return;
+    const size_t begin = (size_t)bucket * bucket_size;
+    const size_t rest = n - begin;
+    const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
+    if (len == (uint32_t)OrqShape<C>::D)
+        orq_bucket<C, S, BITS, true, CLIP, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+    else
+        orq_bucket<C, S, BITS, false, CLIP, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+}
+
+// ----------------------------------------------------------------------------------------------
+// ORQ and the other random-rounding rules for buckets above 4096 elements (up to 32768): the W = 2, 4 or 8
+// wavefronts of a workgroup own one bucket, wavefront w holding bucket elements [4096 w, 4096 (w + 1)) in the
+// register layout of orq_bucket.  All of them build the grouping of the whole bucket in LDS (histogram, bin
+// starts, scatter, fp64 block prefix) with workgroup barriers in between; the level solves are serial and run
+// on wavefront 0 alone; then every wavefront encodes its own elements.
+// ----------------------------------------------------------------------------------------------
+template <int W>
+struct OrqTeamLds {
+    static constexpr int D = 4096 * W;
+    static constexpr int B = W >= 4 ? 2048 : 1024;   // bins
+    static constexpr int SHIFT = W >= 4 ? 17 : 18;   // magnitude bits dropped: exponent + 6 (5) mantissa bits
+    uint32_t grouped[D + D / 32];
+    uint32_t bin_start[B + 4];
+    double block_prefix[D / 64];  // fp64 sum of all positions before block i of 64 positions
+    double lvl_sum_lt[10];
+    double lvl_sum_le[10];
+    float lvl_value[10];
+    uint32_t lvl_count_lt[10];
+    uint32_t lvl_count_le[10];
+    uint32_t lvl_rank[10];
+    TeamSlot slots[2][W];
+};
+
+template <int W, int S, int BITS, bool FULL, int RULE>
+__device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W>& lds, const float* __restrict__ g, uint32_t len,
+                                                size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
+                                                uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
+                                                uint32_t* __restrict__ codes32)
+{
+    constexpr int C = 16;
+    constexpr int D = OrqTeamLds<W>::D;
+    constexpr int B = OrqTeamLds<W>::B;
+    constexpr int HALF = B / 2;
+    constexpr int SHIFT = OrqTeamLds<W>::SHIFT;
+    constexpr bool PB = RULE == kPb;
+    constexpr uint32_t THREADS = 64u * W;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = uniform_u32(tid >> 6);
+    const uint32_t first = 4096u * wave;  // first bucket element of this wavefront
+    const uint32_t my_len = len > first ? (len - first < 4096u ? len - first : 4096u) : 0u;
+    WaveTeam<W> team{lds.slots, wave, 0u};
+
+    float v[C][4];
+    if (FULL) {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const floatx4 q =
+                __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + first + 256 * c + 4 * lane));
+            v[c][0] = q.x; v[c][1] = q.y; v[c][2] = q.z; v[c][3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t e = 256u * c + 4u * lane + k;
+                v[c][k] = e < my_len ? g[first + e] : 0.0f;
+            }
+    }
+
+    if (clip > 0.0f) {  // the same for every thread of the grid
+        float(&flat)[4 * C] = reinterpret_cast<float(&)[4 * C]>(v);
+        clip_in_registers<4 * C>(
+            flat, len, clip, [&](int j) { return FULL || (64u * (j & ~3) + 4u * lane + (j & 3) < my_len); },
+            [&](double x) { return team.sum(wave_sum(x)); });
+    }
+
+    // ---- extremes of the whole bucket ----------------------------------------------------------------
+    float lane_min = __uint_as_float(0x7F800000u), lane_max = __uint_as_float(0xFF800000u);
+    uint32_t lane_zeros = 0;
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+            lane_min = fminf(lane_min, valid ? v[c][k] : __uint_as_float(0x7F800000u));
+            lane_max = fmaxf(lane_max, valid ? v[c][k] : __uint_as_float(0xFF800000u));
+            if constexpr (PB) lane_zeros += (valid && v[c][k] == 0.0f) ? 1u : 0u;
+        }
+    float bucket_min = wave_min(lane_min), bucket_max = wave_max(lane_max);
+    uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
+    {
+        const TeamSlot* s = team.exchange((double)zeros, __float_as_uint(bucket_min), __float_as_uint(bucket_max));
+        double z = 0.0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            bucket_min = fminf(bucket_min, __uint_as_float(s[w].a));
+            bucket_max = fmaxf(bucket_max, __uint_as_float(s[w].b));
+            z += s[w].sum;
+        }
+        zeros = (uint32_t)z;
+    }
+    bucket_min += 0.0f;  // -0 -> +0
+    bucket_max += 0.0f;
+    const uint32_t key_min = float_to_key(bucket_min), key_max = float_to_key(bucket_max);
+    const uint32_t mag_max = umax32(__float_as_uint(bucket_min) & 0x7FFFFFFFu, __float_as_uint(bucket_max) & 0x7FFFFFFFu);
+    const uint32_t t_max = mag_max >> SHIFT;
+    const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
+
+    if constexpr ((S > 2 && RULE != kEven) || PB) {
+        // ---- histogram: the returning LDS add hands every element its position inside its bin ------------
+        for (uint32_t i = tid; i < (uint32_t)B; i += THREADS) lds.bin_start[i] = 0u;
+        __syncthreads();
+        uint32_t slot[C][4];  // bin | position inside the bin << 16
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                const uint32_t bits = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
+                const uint32_t u = t > t_low ? umin32(t - t_low, (uint32_t)(HALF - 1)) : 0u;  // 0 .. HALF-1 (the clamp only acts on NaN)
+                const uint32_t bin = (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
+                slot[c][k] = 0u;
+                if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
+            }
+        __syncthreads();
+
+        // ---- exclusive prefix over the bin counts (wavefront 0; lane l owns bins l*PER .. l*PER+PER-1) ------
+        if (wave == 0u) {
+            constexpr uint32_t PER = B / 64;
+            uint32_t tot = 0;
+            for (uint32_t i = 0; i < PER; ++i) tot += lds.bin_start[lane * PER + i];
+            uint32_t run = wave_inclusive_scan_u32(tot, lane) - tot;
+            for (uint32_t i = 0; i < PER; ++i) {
+                const uint32_t count = lds.bin_start[lane * PER + i];
+                lds.bin_start[lane * PER + i] = run;
+                run += count;
+            }
+            if (lane == 63u) lds.bin_start[B] = run;  // = len
+        }
+        __syncthreads();
+
+        // ---- scatter the values into their bins -------------------------------------------------------
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                if (valid) {
+                    const uint32_t bin = slot[c][k] & 0xFFFFu, pos = slot[c][k] >> 16;
+                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                }
+            }
+        __syncthreads();
+
+        // ---- fp64 prefix of the grouped values per block of 64 positions (thread t sums block t) ----------
+        {
+            double part = 0.0;
+            for (uint32_t i = 0; i < 64u; ++i) {
+                const uint32_t position = tid * 64u + i;
+                const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
+                part += (double)x;
+            }
+            const double incl = wave_inclusive_scan_f64(part, lane);
+            const TeamSlot* s = team.exchange(readlane_f64(incl, 63), 0u, 0u);
+            double before = 0.0, total = 0.0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                if ((uint32_t)w < wave) before += s[w].sum;
+                total += s[w].sum;
+            }
+            lds.block_prefix[tid] = before + (incl - part);
+            if (tid == 0u) {
+                // the bottom level is only ever the left end of a solve, the top level the right end
+                lds.lvl_count_lt[0] = 0u;
+                lds.lvl_sum_lt[0] = 0.0;
+                lds.lvl_count_le[0] = 0u;
+                lds.lvl_sum_le[0] = 0.0;
+                lds.lvl_count_le[S - 1] = len;
+                lds.lvl_sum_le[S - 1] = total;
+                lds.lvl_count_lt[S - 1] = len;
+                lds.lvl_sum_lt[S - 1] = total;
+            }
+            if (tid < (uint32_t)S) {
+                lds.lvl_value[tid] = key_to_float(tid == (uint32_t)(S - 1) ? key_max : key_min);
+                lds.lvl_rank[tid] = 0u;
+            }
+        }
+        __syncthreads();
+
+        // ---- the level solves are serial: wavefront 0 ---------------------------------------------------------
+        if (wave == 0u) {
+            const float pb_level = orq_solve_levels<S, RULE>(
+                lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); }, len, zeros, sweeps, lane);
+            if (PB && lane == 0u) {
+                lds.lvl_value[0] = -pb_level;
+                lds.lvl_value[S - 1] = pb_level;
+            }
+        }
+        __syncthreads();
+    }
+
+    float lv[S];
+    if constexpr (RULE == kEven) {
+        const double largest = (double)__uint_as_float(mag_max);
+#pragma unroll
+        for (int k = 0; k < S; ++k) lv[k] = (float)(largest * (double)(2 * k - (S - 1)) / (double)(S - 1));
+    } else if constexpr (S == 2 && !PB) {
+        lv[0] = key_to_float(key_min);
+        lv[1] = key_to_float(key_max);
+    } else {
+#pragma unroll
+        for (int k = 0; k < S; ++k) lv[k] = lds.lvl_value[k];
+    }
+    if (tid == 0u) {
+#pragma unroll
+        for (int k = 0; k < S; ++k) levels[(size_t)bucket * S + k] = lv[k];
+    }
+
+    orq_encode<C, S, BITS, FULL>(v, lv, my_len, begin + first, seed, index_offset, codes32);
+}
+
+template <int W, int S, int BITS, int RULE>
+__global__ __launch_bounds__(W* kWave) void orq_team_kernel(const float* __restrict__ grad, size_t n,
+                                                            uint32_t bucket_size, uint32_t sweeps, float clip,
+                                                            uint32_t num_buckets, uint64_t seed, uint64_t index_offset,
+                                                            float* __restrict__ levels, uint32_t* __restrict__ codes32)
+{
+    __shared__ OrqTeamLds<W> lds;
+    const uint32_t bucket = blockIdx.x;
+    if (bucket >= num_buckets) return;
+    const size_t begin = (size_t)bucket * bucket_size;
+    const size_t rest = n - begin;
+    const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
+    if (len == (uint32_t)OrqTeamLds<W>::D)
+        orq_team_bucket<W, S, BITS, true, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+    else
+        orq_team_bucket<W, S, BITS, false, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+}
+
+// ----------------------------------------------------------------------------------------------
+// host side
+// ----------------------------------------------------------------------------------------------
+template <int C, int S, int BITS, int RULE = kOptimal>
+void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
+{
+    if (p->clip_factor > 0.0f)
+        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, true, RULE>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+                           p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
+                           static_cast<uint32_t*>(codes));
+    else
+        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, false, RULE>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+                           p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
+                           static_cast<uint32_t*>(codes));
+}
+
+template <int C, int RULE>
+void launch_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                         hipStream_t st)
+{
+    switch (p->bits) {  // 2^(bits-1) + 1 levels
+        case 2: launch_orq<C, 3, 2, RULE>(g, n, p, nb, lv, codes, st); break;
+        case 3: launch_orq<C, 5, 3, RULE>(g, n, p, nb, lv, codes, st); break;
+        default: launch_orq<C, 9, 4, RULE>(g, n, p, nb, lv, codes, st); break;
+    }
+}
+
+template <int C>
+void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                       hipStream_t st)
+{
+    switch (p->scheme) {
+        case OGQ_BINGRAD_PB: launch_orq<C, 2, 1, kPb>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_ORQ:
+            switch (p->bits) {
+                case 1: launch_orq<C, 2, 1>(g, n, p, nb, lv, codes, st); break;
+                case 2: launch_orq<C, 4, 2>(g, n, p, nb, lv, codes, st); break;
+                default: launch_orq<C, 8, 3>(g, n, p, nb, lv, codes, st); break;
+            }
+            break;
+        case OGQ_EVEN: launch_paper_counts<C, kEven>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_LINEAR: launch_paper_counts<C, kLinear>(g, n, p, nb, lv, codes, st); break;
+        default: launch_paper_counts<C, kOptimal>(g, n, p, nb, lv, codes, st); break;  // OGQ_ORQ_PAPER
+    }
+}
+
+// Buckets above 4096 elements: W wavefronts per bucket.
+template <int W, int S, int BITS, int RULE = kOptimal>
+void launch_orq_team(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
+{
+    hipLaunchKernelGGL((orq_team_kernel<W, S, BITS, RULE>), dim3(nb), dim3(W * kWave), 0, st, g, n, p->bucket_size,
+                       p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
+}
+
+template <int W, int RULE>
+void launch_team_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                              hipStream_t st)
+{
+    switch (p->bits) {  // 2^(bits-1) + 1 levels
+        case 2: launch_orq_team<W, 3, 2, RULE>(g, n, p, nb, lv, codes, st); break;
+        case 3: launch_orq_team<W, 5, 3, RULE>(g, n, p, nb, lv, codes, st); break;
+        default: launch_orq_team<W, 9, 4, RULE>(g, n, p, nb, lv, codes, st); break;
+    }
+}
+
+template <int W>
+void launch_orq_team_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
+                            hipStream_t st)
+{
+    switch (p->scheme) {
+        case OGQ_BINGRAD_PB: launch_orq_team<W, 2, 1, kPb>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_ORQ:
+            switch (p->bits) {
+                case 1: launch_orq_team<W, 2, 1>(g, n, p, nb, lv, codes, st); break;
+                case 2: launch_orq_team<W, 4, 2>(g, n, p, nb, lv, codes, st); break;
+                default: launch_orq_team<W, 8, 3>(g, n, p, nb, lv, codes, st); break;
+            }
+            break;
+        case OGQ_EVEN: launch_team_paper_counts<W, kEven>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_LINEAR: launch_team_paper_counts<W, kLinear>(g, n, p, nb, lv, codes, st); break;
+        default: launch_team_paper_counts<W, kOptimal>(g, n, p, nb, lv, codes, st); break;  // OGQ_ORQ_PAPER
+    }
+}
+
+}  // namespace ogq
+#endif  // OGQ_ROUNDING_KERNELS_H
