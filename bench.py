@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 WORKLOAD_NAMES = ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "pb2", "orq5", "orq3clip", "cfg2clip", "bin512", "sign2",
-                  "tern3", "linear5")
+                  "tern3", "linear5", "orq3d32k")
 
 
 def algorithmic_bytes(n: int, bucket_size: int, bits: int, workers: int, levels_per_bucket: int):
@@ -202,9 +202,9 @@ def main() -> int:
 
     two_level_means = wl.scheme in (synth.BINGRAD_B, synth.SCALED_SIGN)
     if not two_level_means:
-        quant_name = "orq_quantize_kernel"
+        quant_name = "orq_quantize_kernel" if d <= 4096 else "orq_team_kernel"
     elif d > 2048:
-        quant_name = "bingrad_pair_kernel"
+        quant_name = "bingrad_team_kernel"
     elif wl.clip_factor == 0 and 2048 % d == 0 and d < 2048 and (d <= 256 or n // 2048 >= 2048):
         quant_name = "bingrad_chunk_kernel"
     else:
