@@ -202,7 +202,7 @@ def main() -> int:
 
     two_level_means = wl.scheme in (synth.BINGRAD_B, synth.SCALED_SIGN)
     if not two_level_means:
-        quant_name = "orq_quantize_kernel" if d <= 4096 else "orq_team_kernel"
+        quant_name = "orq_quantize_kernel" if d <= 2048 else "orq_team_kernel"
     elif d > 2048:
         quant_name = "bingrad_team_kernel"
     elif wl.clip_factor == 0 and 2048 % d == 0 and d < 2048 and (d <= 256 or n // 2048 >= 2048):

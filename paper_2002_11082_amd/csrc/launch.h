@@ -17,8 +17,9 @@ uint32_t levels_per_bucket(uint32_t scheme, uint32_t bits);
 // BinGrad-b and Scaled SignSGD (bingrad.hip): picks the kernel for the bucket size and gradient length.
 void launch_two_level(const float* g, size_t n, const ogq_params_t* p, float* lv, void* codes, hipStream_t st);
 
-// The schemes with random rounding (rounding_part.hip, one object file per bucket capacity): _cN = one
-// wavefront per bucket of at most 256*N elements, _wN = N wavefronts per bucket of at most 4096*N elements.
+// The schemes with random rounding (rounding_part.hip, one object file per bucket capacity): _cN = buckets of
+// at most 256*N elements (one wavefront each, two for N = 16), _wN = N wavefronts per bucket of at most 4096*N
+// elements.
 // nb = number of buckets.
 typedef void RoundingLauncher(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                               hipStream_t st);

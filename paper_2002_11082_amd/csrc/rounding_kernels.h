@@ -263,7 +263,7 @@ __device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t r
     const uint32_t segment = (uint32_t)__popcll(__ballot(lds.bin_start[lane * PER] < rank)) - 1u;
     const bool below = lane < PER && lds.bin_start[segment * PER + (lane < PER ? lane : 0u)] < rank;
     const uint32_t bin = segment * PER + (uint32_t)__popcll(__ballot(below)) - 1u;
-    return pick_in_bin<64>(lds, bin, rank, lane);
+    return pick_in_bin<Lds::BLOCK>(lds, bin, rank, lane);
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -678,20 +678,22 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
 }
 
 // ----------------------------------------------------------------------------------------------
-// ORQ and the other random-rounding rules for buckets above 4096 elements (up to 32768): the W = 2, 4 or 8
-// wavefronts of a workgroup own one bucket, wavefront w holding bucket elements [4096 w, 4096 (w + 1)) in the
-// register layout of orq_bucket.  All of them build the grouping of the whole bucket in LDS (histogram, bin
+// ORQ and the other random-rounding rules with W = 2, 4 or 8 wavefronts of a workgroup owning one bucket (up
+// to 32768 elements), wavefront w holding bucket elements [256 C w, 256 C (w + 1)) in the register layout of
+// orq_bucket.  All of them build the grouping of the whole bucket in LDS (histogram, bin
 // starts, scatter, fp64 block prefix) with workgroup barriers in between; the level solves are serial and run
 // on wavefront 0 alone; then every wavefront encodes its own elements.
 // ----------------------------------------------------------------------------------------------
-template <int W>
+template <int W, int C>
 struct OrqTeamLds {
-    static constexpr int D = 4096 * W;
-    static constexpr int B = W >= 4 ? 2048 : 1024;   // bins
-    static constexpr int SHIFT = W >= 4 ? 17 : 18;   // magnitude bits dropped: exponent + 6 (5) mantissa bits
+    static constexpr int D = 256 * C * W;
+    // bins, and magnitude bits dropped by the bin index (what is kept: the exponent and 3 .. 6 mantissa bits)
+    static constexpr int B = D >= 16384 ? 2048 : D >= 8192 ? 1024 : D >= 4096 ? 512 : 256;
+    static constexpr int SHIFT = D >= 16384 ? 17 : D >= 8192 ? 18 : D >= 4096 ? 19 : 20;
+    static constexpr int BLOCK = 4 * C;  // positions per entry of the fp64 block prefix: one entry per thread
     uint32_t grouped[D + D / 32];
     uint32_t bin_start[B + 4];
-    double block_prefix[D / 64];  // fp64 sum of all positions before block i of 64 positions
+    double block_prefix[64 * W];  // fp64 sum of all positions before block i of BLOCK positions
     double lvl_sum_lt[10];
     double lvl_sum_le[10];
     float lvl_value[10];
@@ -701,24 +703,24 @@ struct OrqTeamLds {
     TeamSlot slots[2][W];
 };
 
-template <int W, int S, int BITS, bool FULL, int RULE>
-__device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W>& lds, const float* __restrict__ g, uint32_t len,
+template <int W, int C, int S, int BITS, bool FULL, int RULE>
+__device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const float* __restrict__ g, uint32_t len,
                                                 size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
                                                 uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
                                                 uint32_t* __restrict__ codes32)
 {
-    constexpr int C = 16;
-    constexpr int D = OrqTeamLds<W>::D;
-    constexpr int B = OrqTeamLds<W>::B;
+    constexpr uint32_t PER_WAVE = 256u * C;  // bucket elements per wavefront
+    constexpr int D = OrqTeamLds<W, C>::D;
+    constexpr int B = OrqTeamLds<W, C>::B;
     constexpr int HALF = B / 2;
-    constexpr int SHIFT = OrqTeamLds<W>::SHIFT;
+    constexpr int SHIFT = OrqTeamLds<W, C>::SHIFT;
     constexpr bool PB = RULE == kPb;
     constexpr uint32_t THREADS = 64u * W;
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wave = uniform_u32(tid >> 6);
-    const uint32_t first = 4096u * wave;  // first bucket element of this wavefront
-    const uint32_t my_len = len > first ? (len - first < 4096u ? len - first : 4096u) : 0u;
+    const uint32_t first = PER_WAVE * wave;  // first bucket element of this wavefront
+    const uint32_t my_len = len > first ? (len - first < PER_WAVE ? len - first : PER_WAVE) : 0u;
     WaveTeam<W> team{lds.slots, wave, 0u};
 
     float v[C][4];
@@ -825,11 +827,12 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W>& lds, const float*
             }
         __syncthreads();
 
-        // ---- fp64 prefix of the grouped values per block of 64 positions (thread t sums block t) ----------
+        // ---- fp64 prefix of the grouped values per block of 4C positions (thread t sums block t) ----------
         {
+            constexpr uint32_t BLOCK = OrqTeamLds<W, C>::BLOCK;
             double part = 0.0;
-            for (uint32_t i = 0; i < 64u; ++i) {
-                const uint32_t position = tid * 64u + i;
+            for (uint32_t i = 0; i < BLOCK; ++i) {
+                const uint32_t position = tid * BLOCK + i;
                 const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
                 part += (double)x;
             }
@@ -892,22 +895,22 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W>& lds, const float*
     orq_encode<C, S, BITS, FULL>(v, lv, my_len, begin + first, seed, index_offset, codes32);
 }
 
-template <int W, int S, int BITS, int RULE>
+template <int W, int C, int S, int BITS, int RULE>
 __global__ __launch_bounds__(W* kWave) void orq_team_kernel(const float* __restrict__ grad, size_t n,
                                                             uint32_t bucket_size, uint32_t sweeps, float clip,
                                                             uint32_t num_buckets, uint64_t seed, uint64_t index_offset,
                                                             float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
-    __shared__ OrqTeamLds<W> lds;
+    __shared__ OrqTeamLds<W, C> lds;
     const uint32_t bucket = blockIdx.x;
     if (bucket >= num_buckets) return;
     const size_t begin = (size_t)bucket * bucket_size;
     const size_t rest = n - begin;
     const uint32_t len = rest < bucket_size ? (uint32_t)rest : bucket_size;
-    if (len == (uint32_t)OrqTeamLds<W>::D)
-        orq_team_bucket<W, S, BITS, true, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+    if (len == (uint32_t)OrqTeamLds<W, C>::D)
+        orq_team_bucket<W, C, S, BITS, true, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
     else
-        orq_team_bucket<W, S, BITS, false, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
+        orq_team_bucket<W, C, S, BITS, false, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -957,40 +960,40 @@ void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t
 }
 
 // Buckets above 4096 elements: W wavefronts per bucket.
-template <int W, int S, int BITS, int RULE = kOptimal>
+template <int W, int C, int S, int BITS, int RULE = kOptimal>
 void launch_orq_team(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
-    hipLaunchKernelGGL((orq_team_kernel<W, S, BITS, RULE>), dim3(nb), dim3(W * kWave), 0, st, g, n, p->bucket_size,
+    hipLaunchKernelGGL((orq_team_kernel<W, C, S, BITS, RULE>), dim3(nb), dim3(W * kWave), 0, st, g, n, p->bucket_size,
                        p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
 }
 
-template <int W, int RULE>
+template <int W, int C, int RULE>
 void launch_team_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                               hipStream_t st)
 {
     switch (p->bits) {  // 2^(bits-1) + 1 levels
-        case 2: launch_orq_team<W, 3, 2, RULE>(g, n, p, nb, lv, codes, st); break;
-        case 3: launch_orq_team<W, 5, 3, RULE>(g, n, p, nb, lv, codes, st); break;
-        default: launch_orq_team<W, 9, 4, RULE>(g, n, p, nb, lv, codes, st); break;
+        case 2: launch_orq_team<W, C, 3, 2, RULE>(g, n, p, nb, lv, codes, st); break;
+        case 3: launch_orq_team<W, C, 5, 3, RULE>(g, n, p, nb, lv, codes, st); break;
+        default: launch_orq_team<W, C, 9, 4, RULE>(g, n, p, nb, lv, codes, st); break;
     }
 }
 
-template <int W>
+template <int W, int C>
 void launch_orq_team_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                             hipStream_t st)
 {
     switch (p->scheme) {
-        case OGQ_BINGRAD_PB: launch_orq_team<W, 2, 1, kPb>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_BINGRAD_PB: launch_orq_team<W, C, 2, 1, kPb>(g, n, p, nb, lv, codes, st); break;
         case OGQ_ORQ:
             switch (p->bits) {
-                case 1: launch_orq_team<W, 2, 1>(g, n, p, nb, lv, codes, st); break;
-                case 2: launch_orq_team<W, 4, 2>(g, n, p, nb, lv, codes, st); break;
-                default: launch_orq_team<W, 8, 3>(g, n, p, nb, lv, codes, st); break;
+                case 1: launch_orq_team<W, C, 2, 1>(g, n, p, nb, lv, codes, st); break;
+                case 2: launch_orq_team<W, C, 4, 2>(g, n, p, nb, lv, codes, st); break;
+                default: launch_orq_team<W, C, 8, 3>(g, n, p, nb, lv, codes, st); break;
             }
             break;
-        case OGQ_EVEN: launch_team_paper_counts<W, kEven>(g, n, p, nb, lv, codes, st); break;
-        case OGQ_LINEAR: launch_team_paper_counts<W, kLinear>(g, n, p, nb, lv, codes, st); break;
-        default: launch_team_paper_counts<W, kOptimal>(g, n, p, nb, lv, codes, st); break;  // OGQ_ORQ_PAPER
+        case OGQ_EVEN: launch_team_paper_counts<W, C, kEven>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_LINEAR: launch_team_paper_counts<W, C, kLinear>(g, n, p, nb, lv, codes, st); break;
+        default: launch_team_paper_counts<W, C, kOptimal>(g, n, p, nb, lv, codes, st); break;  // OGQ_ORQ_PAPER
     }
 }
 
