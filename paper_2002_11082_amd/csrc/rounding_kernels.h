@@ -85,25 +85,25 @@ constexpr GreedyOrder greedy_order()
 }
 
 // LDS of one bucket: D = element capacity, B = number of bins.
-template <int D_, int B_>
+template <int D_, int B_, int S_>
 struct OrqLds {
     static constexpr int D = D_, B = B_;
     // fp32 bit patterns (-0 stored as +0) grouped by bin, unsorted inside a bin.  Position i lives at
-    // word i + i/32, so that the 64 lanes reading consecutive blocks of D/64 positions hit distinct banks.
-    uint32_t grouped[D + D / 32];
+    // word i + i/64, so that the 64 lanes reading consecutive blocks of D/64 positions hit distinct banks.
+    uint32_t grouped[D + D / 64];
     uint32_t bin_start[B + 4];  // histogram, then first position of each bin; [B] = bucket length
     double block_prefix[64];    // fp64 sum of all positions before block l (block = D/64 positions)
     // per level k: value; #{v < value}; #{v <= value}; sum{v < value}; sum{v <= value}; the rank it
     // was picked at (0 = not picked by rank)
-    double lvl_sum_lt[10];
-    double lvl_sum_le[10];
-    float lvl_value[10];
-    uint32_t lvl_count_lt[10];
-    uint32_t lvl_count_le[10];
-    uint32_t lvl_rank[10];
+    double lvl_sum_lt[S_];
+    double lvl_sum_le[S_];
+    float lvl_value[S_];
+    uint32_t lvl_count_lt[S_];
+    uint32_t lvl_count_le[S_];
+    uint32_t lvl_rank[S_];
 };
 
-__device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 5); }
+__device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 6); }
 
 __device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __device__ __forceinline__ uint32_t umax32(uint32_t a, uint32_t b) { return a > b ? a : b; }
@@ -240,8 +240,8 @@ __device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint
 }
 
 // rank is 1-based, 1 <= rank <= bucket length.  my_start[t] = bin_start[lane * PER + t], kept in registers.
-template <int D, int B>
-__device__ __forceinline__ Picked pick_rank(const OrqLds<D, B>& lds, const uint32_t (&my_start)[B / 64],
+template <int D, int B, int S>
+__device__ __forceinline__ Picked pick_rank(const OrqLds<D, B, S>& lds, const uint32_t (&my_start)[B / 64],
                                             uint32_t rank, uint32_t lane)
 {
     constexpr int PER = B / 64;
@@ -481,7 +481,7 @@ struct OrqShape {
 // FULL: the bucket has exactly 256*C elements (no padding, no per-element validity tests).
 // S levels per bucket, BITS bits per level index (S = 2^BITS, or 2^(BITS-1) + 1 for the paper's counts).
 template <int C, int S, int BITS, bool FULL, bool CLIP, int RULE>
-__device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B>& lds, const float* __restrict__ g,
+__device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B, S>& lds, const float* __restrict__ g,
                                            uint32_t len, size_t begin, uint32_t bucket, uint32_t sweeps, float clip,
                                            uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
                                            uint32_t* __restrict__ codes32)
@@ -634,7 +634,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
 
         const uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
         pb_level = orq_solve_levels<S, RULE>(
-            lds, [&](uint32_t rank) { return pick_rank<D, B>(lds, my_start, rank, lane); }, len, zeros, sweeps, lane);
+            lds, [&](uint32_t rank) { return pick_rank<D, B, S>(lds, my_start, rank, lane); }, len, zeros, sweeps, lane);
     }
 
     // every lane holds its own copy of the levels (the selects of the encoder take vector sources)
@@ -665,7 +665,7 @@ __global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __rest
                                                              uint64_t index_offset, float* __restrict__ levels,
                                                              uint32_t* __restrict__ codes32)
 {
-    __shared__ OrqLds<OrqShape<C>::D, OrqShape<C>::B> lds;
+    __shared__ OrqLds<OrqShape<C>::D, OrqShape<C>::B, S> lds;
     const uint32_t bucket = blockIdx.x;
     if (bucket >= num_buckets) return;
     const size_t begin = (size_t)bucket * bucket_size;
@@ -691,7 +691,7 @@ struct OrqTeamLds {
     static constexpr int B = D >= 16384 ? 2048 : D >= 8192 ? 1024 : D >= 4096 ? 512 : 256;
     static constexpr int SHIFT = D >= 16384 ? 17 : D >= 8192 ? 18 : D >= 4096 ? 19 : 20;
     static constexpr int BLOCK = 4 * C;  // positions per entry of the fp64 block prefix: one entry per thread
-    uint32_t grouped[D + D / 32];
+    uint32_t grouped[D + D / 64];
     uint32_t bin_start[B + 4];
     double block_prefix[64 * W];  // fp64 sum of all positions before block i of BLOCK positions
     double lvl_sum_lt[10];
