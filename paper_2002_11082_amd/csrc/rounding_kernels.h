@@ -658,8 +658,10 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     orq_encode<C, S, BITS, FULL>(v, lv, len, begin, seed, index_offset, codes32);
 }
 
+// C = 8 (2048-element buckets): 16 buckets fit the LDS of a CU, so the kernel is held to the 128 registers
+// that let 4 wavefronts share a SIMD (the clipping variants would otherwise take ~138).
 template <int C, int S, int BITS, bool CLIP, int RULE>
-__global__ __launch_bounds__(kWave) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(C == 8 ? 4 : 1))) void orq_quantize_kernel(const float* __restrict__ grad, size_t n,
                                                              uint32_t bucket_size, uint32_t sweeps, float clip,
                                                              uint32_t num_buckets, uint64_t seed,
                                                              uint64_t index_offset, float* __restrict__ levels,
