@@ -152,15 +152,20 @@ __device__ __forceinline__ uint32_t bitonic_step(uint32_t x, uint32_t lane)
     return (ascending == lower) ? mn : mx;
 }
 
-__device__ __forceinline__ uint32_t wave_sort_u32(uint32_t x, uint32_t lane)
+// `count` lanes (the first ones) hold keys, the others 0xFFFFFFFF: with at most 16 (32) keys only the first
+// row (half) of the wavefront has to be sorted, which ends the network after 10 (15) of its 21 steps; the
+// direction of the last merge is ascending in the first row (half) either way.
+__device__ __forceinline__ uint32_t wave_sort_u32(uint32_t x, uint32_t lane, uint32_t count)
 {
     x = bitonic_step<2, 1>(x, lane);
     x = bitonic_step<4, 2>(x, lane);   x = bitonic_step<4, 1>(x, lane);
     x = bitonic_step<8, 4>(x, lane);   x = bitonic_step<8, 2>(x, lane);   x = bitonic_step<8, 1>(x, lane);
     x = bitonic_step<16, 8>(x, lane);  x = bitonic_step<16, 4>(x, lane);  x = bitonic_step<16, 2>(x, lane);
     x = bitonic_step<16, 1>(x, lane);
+    if (count <= 16u) return x;
     x = bitonic_step<32, 16>(x, lane); x = bitonic_step<32, 8>(x, lane);  x = bitonic_step<32, 4>(x, lane);
     x = bitonic_step<32, 2>(x, lane);  x = bitonic_step<32, 1>(x, lane);
+    if (count <= 32u) return x;
     x = bitonic_step<64, 32>(x, lane); x = bitonic_step<64, 16>(x, lane); x = bitonic_step<64, 8>(x, lane);
     x = bitonic_step<64, 4>(x, lane);  x = bitonic_step<64, 2>(x, lane);  x = bitonic_step<64, 1>(x, lane);
     return x;
@@ -195,7 +200,7 @@ __device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint
     if (count <= 64u) {
         const uint32_t mine =
             lane < count ? float_to_key(__uint_as_float(lds.grouped[skewed(first + lane)])) : 0xFFFFFFFFu;
-        const uint32_t sorted = wave_sort_u32(mine, lane);
+        const uint32_t sorted = wave_sort_u32(mine, lane, count);
         key = __builtin_amdgcn_readlane(sorted, r_in - 1u);
         const bool lt = sorted < key;
         const bool le = (sorted <= key) && (lane < count);
