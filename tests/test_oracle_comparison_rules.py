@@ -159,3 +159,23 @@ def test_bingrad_b_error_against_scaled_sign():
         assert e_b <= e_s * 1.01, name
         if name == "shifted":
             assert e_b < 0.97 * e_s
+
+
+def test_whole_gradient_driver_uses_the_rule_it_is_asked_for():
+    """Per-bucket level tables of the gradient-level driver equal the per-bucket functions, bucket by bucket,
+    the shorter last bucket included (hand values for the first bucket of the evenly spaced and Linear rules)."""
+    rng = np.random.default_rng(5)
+    d, n = 64, 64 * 3 + 17
+    x = rng.normal(0, 1, n).astype(np.float32)
+    x[:64] = np.arange(-32, 32, dtype=np.float32)          # first bucket: -32 .. 31
+    for scheme, bits, per_bucket in ((oracle.EVEN, 3, lambda b: oracle.even_levels_bucket(b, 5)),
+                                     (oracle.LINEAR, 3, lambda b: oracle.linear_levels_bucket(b, 5)),
+                                     (oracle.SCALED_SIGN, 1, oracle.scaled_sign_bucket)):
+        lv, codes, _ = oracle.quantize_codes(x, d, bits, scheme, seed=1)
+        s = oracle.levels_per_bucket(scheme, bits)
+        for b in range(4):
+            assert lv[b * s:(b + 1) * s].tolist() == per_bucket(x[b * d:(b + 1) * d]).tolist(), (scheme, b)
+    lv, _, _ = oracle.quantize_codes(x, d, 3, oracle.EVEN)
+    assert lv[:5].tolist() == [-32.0, -16.0, 0.0, 16.0, 32.0]
+    lv, _, _ = oracle.quantize_codes(x, d, 3, oracle.LINEAR)
+    assert lv[:5].tolist() == [-32.0, -17.0, -1.0, 15.0, 31.0]   # ranks floor(k * 63 / 4) = 0, 15, 31, 47, 63
