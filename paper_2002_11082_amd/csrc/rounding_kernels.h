@@ -120,24 +120,45 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
 
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) { return ~wave_max_u32(~x); }
 
-// Inclusive scans over the lanes in ascending lane order.
-__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t x, uint32_t lane)
+// Inclusive scans over the lanes in ascending lane order, in registers: four shifts inside every row of 16
+// lanes (a lane without a source adds 0), then the last lane of row 0 / 2 is added to row 1 / 3 and lane 31
+// to the upper half (DPP row_shr, row_bcast:15, row_bcast:31).
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr8 = 0x118, kDppRowBcast15 = 0x142,
+              kDppRowBcast31 = 0x143;
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero_u32(uint32_t x)
 {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t y = (uint32_t)__shfl_up((int)x, off, kWave);
-        x += (lane >= (uint32_t)off) ? y : 0u;
-    }
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xF, false);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_or_zero_f64(double x)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = dpp_or_zero_u32<CTRL, ROW_MASK>((uint32_t)u), hi = dpp_or_zero_u32<CTRL, ROW_MASK>((uint32_t)(u >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t x)
+{
+    x += dpp_or_zero_u32<kDppRowShr1, 0xF>(x);
+    x += dpp_or_zero_u32<kDppRowShr2, 0xF>(x);
+    x += dpp_or_zero_u32<kDppRowShr4, 0xF>(x);
+    x += dpp_or_zero_u32<kDppRowShr8, 0xF>(x);
+    x += dpp_or_zero_u32<kDppRowBcast15, 0xA>(x);
+    x += dpp_or_zero_u32<kDppRowBcast31, 0xC>(x);
     return x;
 }
 
-__device__ __forceinline__ double wave_inclusive_scan_f64(double x, uint32_t lane)
+__device__ __forceinline__ double wave_inclusive_scan_f64(double x)
 {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const double y = __shfl_up(x, off, kWave);
-        x += (lane >= (uint32_t)off) ? y : 0.0;
-    }
+    x += dpp_or_zero_f64<kDppRowShr1, 0xF>(x);
+    x += dpp_or_zero_f64<kDppRowShr2, 0xF>(x);
+    x += dpp_or_zero_f64<kDppRowShr4, 0xF>(x);
+    x += dpp_or_zero_f64<kDppRowShr8, 0xF>(x);
+    x += dpp_or_zero_f64<kDppRowBcast15, 0xA>(x);
+    x += dpp_or_zero_f64<kDppRowBcast31, 0xC>(x);
     return x;
 }
 
@@ -576,7 +597,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
                 cnt[t] = lds.bin_start[lane * PER + t];
                 tot += cnt[t];
             }
-            uint32_t run = wave_inclusive_scan_u32(tot, lane) - tot;
+            uint32_t run = wave_inclusive_scan_u32(tot) - tot;
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int t = 0; t < PER; ++t) {
@@ -613,7 +634,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
                 const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
                 part += (double)x;
             }
-            const double incl = wave_inclusive_scan_f64(part, lane);
+            const double incl = wave_inclusive_scan_f64(part);
             lds.block_prefix[lane] = incl - part;
             if (lane == 63u) {
                 // the top level is only ever the right end of a solve
@@ -811,7 +832,7 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
             constexpr uint32_t PER = B / 64;
             uint32_t tot = 0;
             for (uint32_t i = 0; i < PER; ++i) tot += lds.bin_start[lane * PER + i];
-            uint32_t run = wave_inclusive_scan_u32(tot, lane) - tot;
+            uint32_t run = wave_inclusive_scan_u32(tot) - tot;
             for (uint32_t i = 0; i < PER; ++i) {
                 const uint32_t count = lds.bin_start[lane * PER + i];
                 lds.bin_start[lane * PER + i] = run;
@@ -843,7 +864,7 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
                 const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
                 part += (double)x;
             }
-            const double incl = wave_inclusive_scan_f64(part, lane);
+            const double incl = wave_inclusive_scan_f64(part);
             const TeamSlot* s = team.exchange(readlane_f64(incl, 63), 0u, 0u);
             double before = 0.0, total = 0.0;
 #pragma unroll
