@@ -352,6 +352,34 @@ def test_random_shapes_and_parameters():
                               clip_factor=clip, tag=f"random-{trial}")
 
 
+def test_non_finite_values_stay_inside_their_bucket():
+    """NaN and infinities give unspecified levels and codes for their own bucket only: every call returns, and the
+    buckets without them still match the oracle (every kernel family and bucket-size class)."""
+    rng = np.random.default_rng(99)
+    cases = [(ogq.BINGRAD_B, 1, 512, 2100 * 2048 + 700), (ogq.BINGRAD_B, 1, 2048, 40 * 2048 + 5),
+             (ogq.BINGRAD_B, 1, 8192, 9 * 8192), (ogq.SCALED_SIGN, 1, 256, 30 * 2048 + 64),
+             (ogq.ORQ, 2, 2048, 40 * 2048 + 5), (ogq.ORQ, 3, 4096, 12 * 4096), (ogq.ORQ_PAPER, 2, 16384, 5 * 16384 + 9),
+             (ogq.BINGRAD_PB, 1, 1024, 33 * 1024), (ogq.EVEN, 2, 512, 70 * 512), (ogq.LINEAR, 3, 2048, 21 * 2048)]
+    for scheme, bits, d, n in cases:
+        g = (rng.standard_t(3, n) * 1e-3).astype(np.float32)
+        nb = (n + d - 1) // d
+        poisoned = sorted(set(int(b) for b in rng.choice(nb, size=min(6, nb // 2), replace=False)))
+        for i, b in enumerate(poisoned):
+            lo, hi = b * d, min((b + 1) * d, n)
+            if i % 3 == 2:
+                g[lo:hi] = np.nan                          # a bucket of nothing but NaN
+            else:
+                where = rng.choice(hi - lo, size=min(5, hi - lo), replace=False) + lo
+                g[where] = [np.nan, np.inf, -np.inf, np.nan, np.inf][:where.size] if i % 3 == 0 else np.inf
+        clean = [b for b in range(nb) if b not in poisoned]
+        for clip in (0.0, 2.5):
+            lv, codes, rep = parity.check_quantize(g, d, bits, scheme, 2, seed=4, buckets=clean, clip_factor=clip,
+                                                   tag=f"nonfinite-s{scheme}b{bits}-d{d}-clip{clip}")
+            out = ogq.ogq_dequantize_average([codes], [lv], n, ogq.make_params(d, bits, scheme))
+            torch.cuda.synchronize()
+            assert out.shape[0] >= n
+
+
 def test_empty_input_is_a_noop():
     p = ogq.make_params(512, 1, ogq.BINGRAD_B)
     x = torch.zeros(4, device=DEV)
