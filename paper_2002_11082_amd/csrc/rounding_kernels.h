@@ -88,7 +88,7 @@ constexpr GreedyOrder greedy_order()
 template <int D_, int B_, int S_>
 struct OrqLds {
     static constexpr int D = D_, B = B_;
-    // fp32 bit patterns (-0 stored as +0) grouped by bin, unsorted inside a bin.  Position i lives at
+    // fp32 bit patterns grouped by bin (-0 lies with +0), unsorted inside a bin.  Position i lives at
     // word i + i/64, so that the 64 lanes reading consecutive blocks of D/64 positions hit distinct banks.
     uint32_t grouped[D + D / 64];
     uint32_t bin_start[B + 4];  // histogram, then first position of each bin; [B] = bucket length
@@ -107,6 +107,22 @@ __device__ __forceinline__ uint32_t skewed(uint32_t position) { return position 
 
 __device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __device__ __forceinline__ uint32_t umax32(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// Bin of a value (with -0 already turned into +0): the HALF bins of either sign cover 16 binades below the
+// largest magnitude of the bucket (t_low = its lowest regular bin index); everything smaller shares the two
+// centre bins HALF - 1 and HALF.  The upper clamp only acts on NaN.
+template <int HALF, int SHIFT>
+__device__ __forceinline__ uint32_t value_bin(float canonical, uint32_t t_low)
+{
+    const uint32_t bits = __float_as_uint(canonical);
+    const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
+    const uint32_t u = umin32(__builtin_elementwise_sub_sat(t, t_low), (uint32_t)(HALF - 1));  // 0 .. HALF-1
+    const uint32_t negative = (uint32_t)((int32_t)bits >> 31);                                 // 0 or ~0
+    return (uint32_t)HALF + (u ^ negative);  // HALF + u, or HALF - 1 - u for a negative value
+}
+
+// Sort key of a value as stored in the grouped array (bit pattern of the element; -0 counts as +0).
+__device__ __forceinline__ uint32_t stored_key(uint32_t stored) { return float_to_key(__uint_as_float(stored) + 0.0f); }
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
 {
@@ -220,7 +236,7 @@ __device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint
     double s_lt;
     if (count <= 64u) {
         const uint32_t mine =
-            lane < count ? float_to_key(__uint_as_float(lds.grouped[skewed(first + lane)])) : 0xFFFFFFFFu;
+            lane < count ? stored_key(lds.grouped[skewed(first + lane)]) : 0xFFFFFFFFu;
         const uint32_t sorted = wave_sort_u32(mine, lane, count);
         key = __builtin_amdgcn_readlane(sorted, r_in - 1u);
         const bool lt = sorted < key;
@@ -236,7 +252,7 @@ __device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint
             uint32_t below = 0;
             for (uint32_t base = 0; base < count; base += 64u) {
                 const uint32_t i = base + lane;
-                const uint32_t k = i < count ? float_to_key(__uint_as_float(lds.grouped[skewed(first + i)])) : 0xFFFFFFFFu;
+                const uint32_t k = i < count ? stored_key(lds.grouped[skewed(first + i)]) : 0xFFFFFFFFu;
                 below += (uint32_t)__popcll(__ballot(k < cand));
             }
             if (below < r_in) prefix = cand;
@@ -247,7 +263,7 @@ __device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint
         double part = (double)head;
         for (uint32_t base = 0; base < count; base += 64u) {
             const uint32_t i = base + lane;
-            const float x = i < count ? __uint_as_float(lds.grouped[skewed(first + i)]) : 0.0f;
+            const float x = i < count ? __uint_as_float(lds.grouped[skewed(first + i)]) + 0.0f : 0.0f;
             const uint32_t k = i < count ? float_to_key(x) : 0xFFFFFFFFu;
             const bool lt = k < key;
             c_lt += (uint32_t)__popcll(__ballot(lt));
@@ -577,10 +593,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const bool valid = full || (256u * c + 4u * lane + k < len);
-                const uint32_t bits = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
-                const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
-                const uint32_t u = t > t_low ? umin32(t - t_low, (uint32_t)(HALF - 1)) : 0u;  // 0 .. HALF-1 (the clamp only acts on NaN)
-                const uint32_t bin = (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
+                const uint32_t bin = value_bin<HALF, SHIFT>(recompute_from(v[c][k]) + 0.0f, t_low);
                 slot[c][k] = 0u;
                 if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
             }
@@ -618,7 +631,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
                 const bool valid = full || (256u * c + 4u * lane + k < len);
                 if (valid) {
                     const uint32_t bin = slot[c][k] & 0xFFFFu, pos = slot[c][k] >> 16;
-                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(v[c][k]);
                 }
             }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -818,10 +831,7 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
-                const uint32_t bits = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
-                const uint32_t t = (bits & 0x7FFFFFFFu) >> SHIFT;
-                const uint32_t u = t > t_low ? umin32(t - t_low, (uint32_t)(HALF - 1)) : 0u;  // 0 .. HALF-1 (the clamp only acts on NaN)
-                const uint32_t bin = (bits >> 31) ? (uint32_t)(HALF - 1) - u : (uint32_t)HALF + u;
+                const uint32_t bin = value_bin<HALF, SHIFT>(recompute_from(v[c][k]) + 0.0f, t_low);
                 slot[c][k] = 0u;
                 if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
             }
@@ -850,7 +860,7 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
                 const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
                 if (valid) {
                     const uint32_t bin = slot[c][k] & 0xFFFFu, pos = slot[c][k] >> 16;
-                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(recompute_from(v[c][k]) + 0.0f);
+                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(v[c][k]);
                 }
             }
         __syncthreads();
