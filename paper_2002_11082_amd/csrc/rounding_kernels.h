@@ -88,6 +88,7 @@ constexpr GreedyOrder greedy_order()
 template <int D_, int B_, int S_>
 struct OrqLds {
     static constexpr int D = D_, B = B_;
+    static constexpr int BLOCK = D_ / 64;  // positions per entry of the fp64 block prefix
     // fp32 bit patterns grouped by bin (-0 lies with +0), unsorted inside a bin.  Position i lives at
     // word i + i/64, so that the 64 lanes reading consecutive blocks of D/64 positions hit distinct banks.
     uint32_t grouped[D + D / 64];
@@ -404,13 +405,25 @@ __device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (
 //   kLinear: Linear-s (Section 5): the order statistics at the fractions k/(S-1) of the sorted bucket.
 enum LevelRule { kOptimal = 0, kPb = 1, kEven = 2, kLinear = 3 };
 
+// fp64 sum of the grouped positions [0, position), position < bucket length: the prefix of its block plus the
+// block's positions before it.
+template <class Lds>
+__device__ __forceinline__ double sum_before_position(const Lds& lds, uint32_t position, uint32_t lane)
+{
+    constexpr uint32_t BLOCK = Lds::BLOCK;
+    const uint32_t block = position / BLOCK;
+    const uint32_t block_first = block * BLOCK;
+    const float head = lane < position - block_first ? __uint_as_float(lds.grouped[skewed(block_first + lane)]) : 0.0f;
+    return uniform_f64(lds.block_prefix[block]) + wave_sum((double)head);
+}
+
 // The level solves of one bucket, run by one wavefront once the bucket is grouped in LDS and the level
 // records of the two ends are set.  pick(rank) returns the element of that 1-based rank (Picked); `zeros` is the
 // number of zeros in the bucket (BinGrad-pb only).  Interior levels end up in lds.lvl_value; returns b_1 for
 // BinGrad-pb.
-template <int S, int RULE, class Lds, class PickFn>
-__device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, uint32_t len, uint32_t zeros, uint32_t sweeps,
-                                                  uint32_t lane)
+template <int S, int RULE, class Lds, class PickFn, class EdgeFn>
+__device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, EdgeFn lower_edge_of_bin, uint32_t len,
+                                                  uint32_t zeros, uint32_t sweeps, uint32_t lane)
 {
     constexpr bool PB = RULE == kPb;
     float pb_level = 0.0f;
@@ -422,7 +435,24 @@ __device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, uint32_
         const uint32_t positives = len - not_positive;
         const double total = uniform_f64(lds.lvl_sum_le[S - 1]);
         if (positives > 0u) {
-            uint32_t lo = not_positive + 1u, hi = len;  // 1-based ranks; the largest value always has gap >= 0
+            // First the bin: every element of a positive bin j lies below the lower edge e of bin j + 1, so its
+            // gap is below gap(e) = e * #{v > 0} - (sum of the bins above j); the wanted value sits in the first bin
+            // j whose gap(e) is not negative, or is the first element after it.  One block-prefix look-up per step.
+            uint32_t bin_lo = (uint32_t)(Lds::B / 2), bin_hi = (uint32_t)Lds::B - 1u;
+            while (bin_lo < bin_hi) {
+                const uint32_t mid = (bin_lo + bin_hi) >> 1;
+                const uint32_t above = uniform_u32(lds.bin_start[mid + 1u]);  // first position of the bins above mid
+                const double sum_above = above < len ? total - sum_before_position(lds, above, lane) : 0.0;
+                const double gap = (double)lower_edge_of_bin(mid + 1u) * (double)positives - sum_above;
+                if (gap >= 0.0) bin_hi = mid;
+                else bin_lo = mid + 1u;
+            }
+            const uint32_t first_of_bin = uniform_u32(lds.bin_start[bin_lo]);
+            const uint32_t first_above = uniform_u32(lds.bin_start[bin_lo + 1u]);
+            // then the rank inside it (1-based ranks; the first element above the bin, like the largest value of
+            // the bucket, always has gap >= 0)
+            const uint32_t hi_rank = umin32(len, first_above + 1u);
+            uint32_t lo = umin32(umax32(not_positive, first_of_bin) + 1u, hi_rank), hi = hi_rank;
             while (lo < hi) {
                 const uint32_t mid = (lo + hi) >> 1;
                 const Picked p = pick(mid);
@@ -673,7 +703,8 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
 
         const uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
         pb_level = orq_solve_levels<S, RULE>(
-            lds, [&](uint32_t rank) { return pick_rank<D, B, S>(lds, my_start, rank, lane); }, len, zeros, sweeps, lane);
+            lds, [&](uint32_t rank) { return pick_rank<D, B, S>(lds, my_start, rank, lane); },
+            [&](uint32_t bin) { return __uint_as_float((t_low + (bin - (uint32_t)HALF)) << SHIFT); }, len, zeros, sweeps, lane);
     }
 
     // every lane holds its own copy of the levels (the selects of the encoder take vector sources)
@@ -904,7 +935,9 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
         // ---- the level solves are serial: wavefront 0 ---------------------------------------------------------
         if (wave == 0u) {
             const float pb_level = orq_solve_levels<S, RULE>(
-                lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); }, len, zeros, sweeps, lane);
+                lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); },
+                [&](uint32_t bin) { return __uint_as_float((t_low + (bin - (uint32_t)HALF)) << SHIFT); }, len, zeros, sweeps,
+                lane);
             if (PB && lane == 0u) {
                 lds.lvl_value[0] = -pb_level;
                 lds.lvl_value[S - 1] = pb_level;
