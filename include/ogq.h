@@ -124,14 +124,16 @@ size_t ogq_codes_bytes(size_t n, const ogq_params_t* params);
  *                  BINGRAD_B: {b_{-1}, b_1} = means of the elements below / not below the
  *                  threshold b0 (b0 = fp32 bucket mean, then level_iters midpoint updates);
  *                  a constant bucket gives two equal levels.
- *                  ORQ: level 0 = bucket minimum, level s-1 = bucket maximum (Corollary 1),
+ *                  ORQ, ORQ_PAPER: level 0 = bucket minimum, level s-1 = bucket maximum (Corollary 1),
  *                  interior levels are bucket values solving the discrete optimal condition
  *                  (second remark after Theorem 1) between their neighbours.
+ *                  The other schemes: see ogq_scheme_t.
  *   d_codes   out  codes_bytes bytes, device.  Bit-plane layout: element i
  *                  belongs to group i/64, lane i%64; bit `lane` of the little-endian 64-bit
  *                  word (group*bits + p) is bit p of the element's level index.  Pad bits of
  *                  the last group are written as 0.
- *                  BINGRAD_B: index = (v >= b0).  ORQ: k = last level not above v (at most
+ *                  BINGRAD_B: index = (v >= b0).  SCALED_SIGN: index = (v >= 0).  Every other scheme
+ *                  (random rounding): k = last level not above v (at most
  *                  s-2), index = k + [u * (b_{k+1} - b_k) < v - b_k] in fp32, where u is the top
  *                  24 bits of word (j mod 4) of Philox4x32-10(counter = (lo32(j/4), hi32(j/4),
  *                  0, 0), key = (lo32(seed), hi32(seed))) times 2^-24, j = index_offset + i.

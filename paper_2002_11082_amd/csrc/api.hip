@@ -1,15 +1,18 @@
-// libogq: per-bucket optimal gradient quantization for MI355X (gfx950, wave64).
+// libogq: per-bucket optimal gradient quantization for MI355X (gfx950, wave64): the C ABI declared in ogq.h.
 //
 // Method: "Optimal Gradient Quantization Condition for Communication-Efficient Distributed
-// Training" (arXiv 2002.11082).  One wavefront owns one bucket from the HBM load to the packed
-// store, so the gradient is read exactly once:
-//   BinGrad-b (Section 3.2): fp64 wave reductions for the mean and the two conditional means,
-//     the code bit of 64 consecutive elements is the ballot of (v >= b0).
-//   ORQ (Theorem 1, its discrete remark, Corollary 1, Algorithm 1; random rounding of
-//     Section 3.1): every level solve is a range sum plus an exact rank selection over the
-//     register-resident bucket; Philox4x32-10 draws keyed by (seed, global element index).
-//   Decode-average (server step of Algorithm 2): the packed 64-bit words are used directly as
-//     lane masks of v_cndmask selects over the bucket's level table.
+// Training" (arXiv 2002.11082).  A bucket stays with one wavefront (several small buckets share one, a large
+// bucket takes the wavefronts of one workgroup) from the HBM load to the packed store, so the gradient is read
+// exactly once:
+//   bingrad.hip            BinGrad-b (Section 3.2) and Scaled SignSGD: fp64 wave reductions for the mean and the
+//                          two conditional means; the code bits of 64 consecutive elements are a lane mask.
+//   rounding_kernels.h     ORQ (Theorem 1, its discrete remark, Corollary 1, Algorithm 1; random rounding of
+//                          Section 3.1), BinGrad-pb and the evenly spaced / Linear-s comparison rules: every
+//                          level solve is a range sum plus an exact rank selection over the bucket grouped in
+//                          LDS; Philox4x32-10 draws keyed by (seed, global element index).
+//   decode.hip             decode-average (server step of Algorithm 2): the packed 64-bit words are used
+//                          directly as lane masks of v_cndmask selects over the bucket's level table.
+// This file validates the arguments and picks the launcher (launch.h).
 //
 // Compile with -ffp-contract=off: the rounding decision of ORQ is specified op by op in fp32.
 #include <hip/hip_runtime.h>
