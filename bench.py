@@ -234,7 +234,8 @@ def main() -> int:
     valu_per_wave = read_note("valu_instructions.txt", f"{args.workload}:{quant_name}")
     alu = None
     if valu_per_wave is not None and not two_level_means:
-        lane_ops = valu_per_wave * 64 * ((n + d - 1) // d)
+        waves_per_bucket = 1 if d <= 2048 else 2 if d <= 8192 else 4 if d <= 16384 else 8
+        lane_ops = valu_per_wave * 64 * waves_per_bucket * ((n + d - 1) // d)
         achieved = lane_ops / (q_avg * 1e-3) / 1e12
         alu = {"bound": "alu", "kernel": quant_name, "achieved": round(achieved, 2), "peak": 78.6,
                "unit": "T lane-op/s", "frac": round(achieved / 78.6, 4), "valu_instructions_per_wavefront": valu_per_wave}
