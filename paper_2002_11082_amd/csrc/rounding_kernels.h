@@ -405,6 +405,14 @@ __device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (
 //   kLinear: Linear-s (Section 5): the order statistics at the fractions k/(S-1) of the sorted bucket.
 enum LevelRule { kOptimal = 0, kPb = 1, kEven = 2, kLinear = 3 };
 
+// Lane `at` (wave-uniform) of a 64-bit value.
+__device__ __forceinline__ double lane_entry_f64(double x, uint32_t at)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)u, at), hi = __builtin_amdgcn_readlane((uint32_t)(u >> 32), at);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
 // fp64 sum of the grouped positions [0, position), position < bucket length: the prefix of its block plus the
 // block's positions before it.
 template <class Lds>
@@ -449,25 +457,67 @@ __device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, EdgeFn 
             }
             const uint32_t first_of_bin = uniform_u32(lds.bin_start[bin_lo]);
             const uint32_t first_above = uniform_u32(lds.bin_start[bin_lo + 1u]);
-            // then the rank inside it (1-based ranks; the first element above the bin, like the largest value of
-            // the bucket, always has gap >= 0)
-            const uint32_t hi_rank = umin32(len, first_above + 1u);
-            uint32_t lo = umin32(umax32(not_positive, first_of_bin) + 1u, hi_rank), hi = hi_rank;
-            while (lo < hi) {
-                const uint32_t mid = (lo + hi) >> 1;
-                const Picked p = pick(mid);
-                const double gap = (double)key_to_float(p.key) * (double)positives - (total - p.sum_lt);
-                if (gap >= 0.0) hi = mid;
-                else lo = mid + 1u;
+            // Then the value inside it.  A bin of at most 64 elements is sorted once and every distinct positive value
+            // of it gets its gap in its own lane (the sum of the strictly smaller elements is an exclusive scan at the
+            // first lane that holds the value); larger bins, and the case that the wanted value is the first one
+            // above the bin, take the bisection over ranks below.
+            const uint32_t count = first_above - first_of_bin;
+            bool done = false;
+            if (count > 0u && count <= 64u) {
+                const uint32_t mine = lane < count ? stored_key(lds.grouped[skewed(first_of_bin + lane)]) : 0xFFFFFFFFu;
+                const uint32_t sorted = wave_sort_u32(mine, lane, count);
+                const float value = lane < count ? key_to_float(sorted) : 0.0f;
+                const double below_bin = sum_before_position(lds, first_of_bin, lane);
+                const double smaller = below_bin + (wave_inclusive_scan_f64((double)value) - (double)value);
+                const uint32_t previous = (uint32_t)__shfl_up((int)sorted, 1, kWave);
+                const bool candidate = lane < count && value > 0.0f && (lane == 0u || previous != sorted);
+                const double gap = (double)value * (double)positives - (total - smaller);
+                const uint64_t not_negative = __ballot(candidate && gap >= 0.0);
+                if (not_negative != 0) {
+                    const uint32_t at = (uint32_t)__builtin_ctzll(not_negative);  // first lane of the wanted value
+                    const uint32_t up_key = __builtin_amdgcn_readlane(sorted, at);
+                    const double gap_up = lane_entry_f64(gap, at);
+                    pb_level = key_to_float(up_key);
+                    const uint32_t count_lt = first_of_bin + at;  // elements of the bucket below the wanted value
+                    if (count_lt > not_positive) {  // a smaller positive value exists
+                        float down;
+                        double gap_down;
+                        if (at > 0u) {
+                            const uint32_t down_key = __builtin_amdgcn_readlane(sorted, at - 1u);
+                            const uint32_t down_at = (uint32_t)__popcll(__ballot(sorted < down_key));  // its first lane
+                            down = key_to_float(down_key);
+                            gap_down = lane_entry_f64(gap, down_at);
+                        } else {
+                            const Picked below = pick(count_lt);
+                            down = key_to_float(below.key);
+                            gap_down = (double)down * (double)positives - (total - below.sum_lt);
+                        }
+                        if (fabs(gap_down) <= fabs(gap_up)) pb_level = down;  // ties take the smaller value
+                    }
+                    done = true;
+                }
             }
-            const Picked up = pick(lo);
-            const double gap_up = (double)key_to_float(up.key) * (double)positives - (total - up.sum_lt);
-            pb_level = key_to_float(up.key);
-            if (up.count_lt > not_positive) {  // a smaller positive value exists: rank count_lt is the next one down
-                const Picked down = pick(up.count_lt);
-                const double gap_down =
-                    (double)key_to_float(down.key) * (double)positives - (total - down.sum_lt);
-                if (fabs(gap_down) <= fabs(gap_up)) pb_level = key_to_float(down.key);  // ties take the smaller value
+            if (!done) {
+                // 1-based ranks; the first element above the bin, like the largest value of the bucket, always has
+                // gap >= 0
+                const uint32_t hi_rank = umin32(len, first_above + 1u);
+                uint32_t lo = umin32(umax32(not_positive, first_of_bin) + 1u, hi_rank), hi = hi_rank;
+                while (lo < hi) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    const Picked p = pick(mid);
+                    const double gap = (double)key_to_float(p.key) * (double)positives - (total - p.sum_lt);
+                    if (gap >= 0.0) hi = mid;
+                    else lo = mid + 1u;
+                }
+                const Picked up = pick(lo);
+                const double gap_up = (double)key_to_float(up.key) * (double)positives - (total - up.sum_lt);
+                pb_level = key_to_float(up.key);
+                if (up.count_lt > not_positive) {  // a smaller positive value exists: rank count_lt is the next one down
+                    const Picked down = pick(up.count_lt);
+                    const double gap_down =
+                        (double)key_to_float(down.key) * (double)positives - (total - down.sum_lt);
+                    if (fabs(gap_down) <= fabs(gap_up)) pb_level = key_to_float(down.key);  // ties take the smaller value
+                }
             }
         }
     }
