@@ -832,7 +832,6 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
                                                 uint32_t* __restrict__ codes32)
 {
     constexpr uint32_t PER_WAVE = 256u * C;  // bucket elements per wavefront
-    constexpr int D = OrqTeamLds<W, C>::D;
     constexpr int B = OrqTeamLds<W, C>::B;
     constexpr int HALF = B / 2;
     constexpr int SHIFT = OrqTeamLds<W, C>::SHIFT;
