@@ -380,6 +380,45 @@ def test_non_finite_values_stay_inside_their_bucket():
             assert out.shape[0] >= n
 
 
+def test_calls_can_be_captured_in_a_graph():
+    """The entry points only enqueue kernels, so a quantize + decode-average pair can be captured once and replayed
+    on new inputs: every replay must give what the eager calls give (several kernel families, a gradient that takes
+    two launches, several replays with other work in between)."""
+    rng = np.random.default_rng(31)
+    cases = [(ogq.BINGRAD_B, 1, 512, 2100 * 2048 + 700, 0), (ogq.ORQ, 2, 2048, 9 * 2048 + 100, 2),
+             (ogq.ORQ_PAPER, 2, 8192, 3 * 8192 + 5, 0)]
+    for scheme, bits, d, n, iters in cases:
+        params = ogq.make_params(d, bits, scheme, iters, seed=17)
+        g_dev = torch.empty(n, dtype=torch.float32, device=DEV)
+        lv = torch.zeros(ogq.ogq_levels_count(n, params) + 4, dtype=torch.float32, device=DEV)
+        codes = torch.zeros(ogq.ogq_codes_bytes(n, params) // 8 + 2, dtype=torch.int64, device=DEV)
+        out = torch.zeros(n, dtype=torch.float32, device=DEV)
+        inputs = [(rng.standard_t(3, n) * 1e-3).astype(np.float32) for _ in range(3)]
+        g_dev.copy_(torch.from_numpy(inputs[0]))
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):  # warm-up outside the capture
+            ogq.ogq_quantize(g_dev, params, lv, codes)
+            ogq.ogq_dequantize_average([codes], [lv], n, params, out)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ogq.ogq_quantize(g_dev, params, lv, codes)
+            ogq.ogq_dequantize_average([codes], [lv], n, params, out)
+        for x in inputs[::-1]:
+            g_dev.copy_(torch.from_numpy(x))
+            graph.replay()
+            torch.cuda.synchronize()
+            replayed = (lv.clone(), codes.clone(), out.clone())
+            lv_e, codes_e = ogq.ogq_quantize(torch.from_numpy(x).to(DEV), params)   # eager, fresh buffers
+            out_e = ogq.ogq_dequantize_average([codes_e], [lv_e], n, params)
+            torch.cuda.synchronize()
+            nl, nw = ogq.ogq_levels_count(n, params), ogq.ogq_codes_bytes(n, params) // 8
+            assert torch.equal(replayed[0][:nl], lv_e[:nl]) and torch.equal(replayed[1][:nw], codes_e[:nw])
+            assert torch.equal(replayed[2], out_e[:n])
+
+
 def test_empty_input_is_a_noop():
     p = ogq.make_params(512, 1, ogq.BINGRAD_B)
     x = torch.zeros(4, device=DEV)
