@@ -413,6 +413,116 @@ __device__ __forceinline__ double lane_entry_f64(double x, uint32_t at)
     return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
 }
 
+// One level solve (discrete optimal condition, second remark after Theorem 1): level k between the current
+// levels l and r, whose records (and k's) are in lds.lvl_*.  Run by one whole wavefront.
+template <class Lds, class PickFn>
+__device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k, uint32_t l, uint32_t r, uint32_t len,
+                                              uint32_t lane)
+{
+    const float L = uniform_f32(lds.lvl_value[l]);
+    const float R = uniform_f32(lds.lvl_value[r]);
+    const uint32_t cnt_lt_L = uniform_u32(lds.lvl_count_lt[l]);
+    const uint32_t cnt_le_R = uniform_u32(lds.lvl_count_le[r]);
+    const double sum_lt_L = uniform_f64(lds.lvl_sum_lt[l]);
+    const double sum_le_R = uniform_f64(lds.lvl_sum_le[r]);
+    bool copy_left = !(L < R);
+    Picked p;
+    uint32_t rank = 0;
+    if (!copy_left) {
+        // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
+        const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
+        const double T = Ssum / ((double)R - (double)L);
+        double m = floor(T);
+        if (!(m >= 0.0)) m = 0.0;
+        rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
+        rank = rank < 1u ? 1u : (rank > len ? len : rank);
+        if (rank == uniform_u32(lds.lvl_rank[k])) return;  // same element as last time
+        p = pick(rank);
+        if (key_to_float(p.key) < L) copy_left = true;
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (lane == 0u) {
+        if (copy_left) {
+            // the level coincides with the left end (L == R, or rounding put it below L)
+            lds.lvl_value[k] = L;
+            lds.lvl_count_lt[k] = cnt_lt_L;
+            lds.lvl_sum_lt[k] = sum_lt_L;
+            lds.lvl_count_le[k] = (L < R) ? uniform_u32(lds.lvl_count_le[l]) : cnt_le_R;
+            lds.lvl_sum_le[k] = (L < R) ? uniform_f64(lds.lvl_sum_le[l]) : sum_le_R;
+            lds.lvl_rank[k] = 0u;
+        } else {
+            lds.lvl_value[k] = key_to_float(p.key);
+            lds.lvl_count_lt[k] = p.count_lt;
+            lds.lvl_count_le[k] = p.count_le;
+            lds.lvl_sum_lt[k] = p.sum_lt;
+            lds.lvl_sum_le[k] = p.sum_le;
+            lds.lvl_rank[k] = rank;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Schedule of the level solves over the first two wavefronts of a team (Algorithm 1 and the re-solve sweeps;
+// the results are those of the serial order).  Greedy: after the root, the solves of the left half only touch levels
+// up to the root and those of the right half only levels from the root on, so wavefront 0 takes the left and
+// wavefront 1 the right half, step by step.  Sweeps, two at a time: wavefront 0 runs sweep s, wavefront 1 sweep
+// s + 1 two levels behind it (level k of a sweep needs level k - 1 of the same sweep and level k + 1 of the sweep
+// before).  Every wavefront of the workgroup must call this; a workgroup barrier ends every step.
+struct TeamGreedy {
+    uint16_t entry[2][8];  // k | l << 4 | r << 8 per wavefront and step; 0 = idle
+    int steps;
+};
+
+template <int S>
+constexpr TeamGreedy team_greedy()
+{
+    const GreedyOrder o = greedy_order<S>();
+    TeamGreedy g{{{0, 0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0, 0}}, 0};
+    int next[2] = {1, 1};
+    int root = 0;
+    for (int i = 0; i < o.count; ++i) {
+        const uint32_t e = (uint32_t)(o.packed[i / 5] >> (12 * (i % 5))) & 0xFFFu;
+        const int k = (int)(e & 15u);
+        if (i == 0) {
+            root = k;
+            g.entry[0][0] = (uint16_t)e;
+        } else {
+            const int w = k < root ? 0 : 1;
+            g.entry[w][next[w]++] = (uint16_t)e;
+        }
+    }
+    g.steps = o.count == 0 ? 0 : (next[0] > next[1] ? next[0] : next[1]);
+    return g;
+}
+
+// The greedy steps are unrolled (their level indices are compile-time constants: measured 7 % faster on 8 levels
+// than one loop over a packed table).
+template <int S, class Lds, class PickFn>
+__device__ __forceinline__ void orq_team_solve(Lds& lds, PickFn pick, uint32_t wave, uint32_t len, uint32_t sweeps,
+                                               uint32_t lane)
+{
+    constexpr TeamGreedy greedy = team_greedy<S>();
+    constexpr uint32_t INTERIOR = S - 2;
+#pragma unroll
+    for (int step = 0; step < greedy.steps; ++step) {
+        if (wave < 2u) {
+            const uint32_t e = wave == 0u ? greedy.entry[0][step] : greedy.entry[1][step];
+            if (e != 0u) orq_solve_one(lds, pick, e & 15u, (e >> 4) & 15u, (e >> 8) & 15u, len, lane);
+        }
+        __syncthreads();
+    }
+    for (uint32_t s = 0; s < sweeps; s += 2u) {
+        const bool pair = s + 1u < sweeps;
+        const uint32_t steps = INTERIOR + (pair ? 2u : 0u);
+        for (uint32_t t = 0; t < steps; ++t) {
+            if (wave == 0u && t < INTERIOR) orq_solve_one(lds, pick, t + 1u, t, t + 2u, len, lane);
+            if (wave == 1u && pair && t >= 2u) orq_solve_one(lds, pick, t - 1u, t - 2u, t, len, lane);
+            __syncthreads();
+        }
+    }
+}
+
 // fp64 sum of the grouped positions [0, position), position < bucket length: the prefix of its block plus the
 // block's positions before it.
 template <class Lds>
@@ -546,48 +656,7 @@ __device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, EdgeFn 
             k = 1u + (step - order.count) % (S - 2);
             l = k - 1u; r = k + 1u;
         }
-        const float L = uniform_f32(lds.lvl_value[l]);
-        const float R = uniform_f32(lds.lvl_value[r]);
-        const uint32_t cnt_lt_L = uniform_u32(lds.lvl_count_lt[l]);
-        const uint32_t cnt_le_R = uniform_u32(lds.lvl_count_le[r]);
-        const double sum_lt_L = uniform_f64(lds.lvl_sum_lt[l]);
-        const double sum_le_R = uniform_f64(lds.lvl_sum_le[r]);
-        bool copy_left = !(L < R);
-        Picked p;
-        uint32_t rank = 0;
-        if (!copy_left) {
-            // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
-            const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
-            const double T = Ssum / ((double)R - (double)L);
-            double m = floor(T);
-            if (!(m >= 0.0)) m = 0.0;
-            rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
-            rank = rank < 1u ? 1u : (rank > len ? len : rank);
-            if (rank == uniform_u32(lds.lvl_rank[k])) continue;  // same element as last time
-            p = pick(rank);
-            if (key_to_float(p.key) < L) copy_left = true;
-        }
-        __builtin_amdgcn_wave_barrier();
-        if (lane == 0u) {
-            if (copy_left) {
-                // the level coincides with the left end (L == R, or rounding put it below L)
-                lds.lvl_value[k] = L;
-                lds.lvl_count_lt[k] = cnt_lt_L;
-                lds.lvl_sum_lt[k] = sum_lt_L;
-                lds.lvl_count_le[k] = (L < R) ? uniform_u32(lds.lvl_count_le[l]) : cnt_le_R;
-                lds.lvl_sum_le[k] = (L < R) ? uniform_f64(lds.lvl_sum_le[l]) : sum_le_R;
-                lds.lvl_rank[k] = 0u;
-            } else {
-                lds.lvl_value[k] = key_to_float(p.key);
-                lds.lvl_count_lt[k] = p.count_lt;
-                lds.lvl_count_le[k] = p.count_le;
-                lds.lvl_sum_lt[k] = p.sum_lt;
-                lds.lvl_sum_le[k] = p.sum_le;
-                lds.lvl_rank[k] = rank;
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        orq_solve_one(lds, pick, k, l, r, len, lane);
     }
     }
     return pb_level;
@@ -981,18 +1050,24 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
         }
         __syncthreads();
 
-        // ---- the level solves are serial: wavefront 0 ---------------------------------------------------------
-        if (wave == 0u) {
-            const float pb_level = orq_solve_levels<S, RULE>(
-                lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); },
-                [&](uint32_t bin) { return __uint_as_float((t_low + (bin - (uint32_t)HALF)) << SHIFT); }, len, zeros, sweeps,
-                lane);
-            if (PB && lane == 0u) {
-                lds.lvl_value[0] = -pb_level;
-                lds.lvl_value[S - 1] = pb_level;
+        if constexpr (RULE == kOptimal && S > 2) {
+            // ---- the level solves, spread over the first two wavefronts ------------------------------------------
+            orq_team_solve<S>(lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); }, wave, len, sweeps,
+                              lane);
+        } else {
+            // ---- the other rules' solves are serial: wavefront 0 ---------------------------------------------------
+            if (wave == 0u) {
+                const float pb_level = orq_solve_levels<S, RULE>(
+                    lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); },
+                    [&](uint32_t bin) { return __uint_as_float((t_low + (bin - (uint32_t)HALF)) << SHIFT); }, len, zeros, sweeps,
+                    lane);
+                if (PB && lane == 0u) {
+                    lds.lvl_value[0] = -pb_level;
+                    lds.lvl_value[S - 1] = pb_level;
+                }
             }
+            __syncthreads();
         }
-        __syncthreads();
     }
 
     float lv[S];
