@@ -123,16 +123,32 @@ def _stream_of(t) -> int:
     return torch.cuda.current_stream(t.device).cuda_stream
 
 
+def _require(ok: bool, what: str) -> None:
+    if not ok:
+        raise ValueError(what)
+
+
+def _holds(t, dtype, elements: int, what: str) -> None:
+    """A contiguous CUDA tensor of `dtype` with at least `elements` elements (the kernels trust these sizes)."""
+    _require(t.is_cuda and t.dtype == dtype and t.is_contiguous(), f"{what}: expected a contiguous CUDA tensor of {dtype}")
+    _require(t.numel() >= elements, f"{what}: {t.numel()} elements, at least {elements} needed")
+
+
 def ogq_quantize(grad, params: Params, levels=None, codes=None):
     """grad: 1-D contiguous float32 CUDA tensor.  Returns (levels float32[levels_count],
     codes int64[codes_bytes/8]) on the same device, enqueued on torch's current stream."""
     import torch
-    assert grad.is_cuda and grad.dtype == torch.float32 and grad.dim() == 1 and grad.is_contiguous()
+    _require(grad.dim() == 1, "grad: expected a 1-D tensor")
+    _holds(grad, torch.float32, 0, "grad")
     n = grad.numel()
+    n_levels, n_words = ogq_levels_count(n, params), ogq_codes_bytes(n, params) // 8
     if levels is None:
-        levels = torch.empty(max(ogq_levels_count(n, params), 4), dtype=torch.float32, device=grad.device)
+        levels = torch.empty(max(n_levels, 4), dtype=torch.float32, device=grad.device)
     if codes is None:
-        codes = torch.empty(max(ogq_codes_bytes(n, params) // 8, 2), dtype=torch.int64, device=grad.device)
+        codes = torch.empty(max(n_words, 2), dtype=torch.int64, device=grad.device)
+    _holds(levels, torch.float32, n_levels, "levels")
+    _holds(codes, torch.int64, n_words, "codes")
+    _require(levels.device == grad.device and codes.device == grad.device, "levels / codes: not on grad's device")
     _check(ogq_quantize_raw(grad.data_ptr(), n, params, levels.data_ptr(), codes.data_ptr(), _stream_of(grad)))
     return levels, codes
 
@@ -141,9 +157,17 @@ def ogq_dequantize_average(codes_list, levels_list, n: int, params: Params, out=
     """codes_list / levels_list: one CUDA tensor per worker as returned by ogq_quantize.
     Returns float32[n]."""
     import torch
+    _require(len(codes_list) == len(levels_list) and len(codes_list) > 0, "one codes and one levels tensor per worker")
     dev = codes_list[0].device
+    n_levels, n_words = ogq_levels_count(n, params), ogq_codes_bytes(n, params) // 8
+    for w, (c, l) in enumerate(zip(codes_list, levels_list)):
+        _holds(c, torch.int64, n_words, f"codes of worker {w}")
+        _holds(l, torch.float32, n_levels, f"levels of worker {w}")
+        _require(c.device == dev and l.device == dev, f"worker {w}: tensors on different devices")
     if out is None:
         out = torch.empty(max(n, 4), dtype=torch.float32, device=dev)[:n]
+    _holds(out, torch.float32, n, "out")
+    _require(out.device == dev, "out: not on the workers' device")
     _check(ogq_dequantize_average_raw([c.data_ptr() for c in codes_list], [l.data_ptr() for l in levels_list], n,
                                       params, out.data_ptr(), _stream_of(out)))
     return out

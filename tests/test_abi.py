@@ -109,3 +109,19 @@ def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         binding.lib()
+
+
+def test_tensor_wrappers_refuse_tensors_the_kernels_could_not_trust():
+    """Host tensors, wrong dtypes and mismatched worker lists are turned into errors before any pointer is taken."""
+    import torch
+    p = ogq.make_params(2048, 1, ogq.BINGRAD_B)
+    with pytest.raises(ValueError):
+        ogq.ogq_quantize(torch.zeros(4096), p)                         # host memory
+    with pytest.raises(ValueError):
+        ogq.ogq_quantize(torch.zeros(2, 2048), p)                      # not 1-D
+    with pytest.raises(ValueError):
+        ogq.ogq_dequantize_average([], [], 4096, p)                    # no workers
+    with pytest.raises(ValueError):
+        ogq.ogq_dequantize_average([torch.zeros(64, dtype=torch.int64)], [], 4096, p)
+    with pytest.raises(ValueError):
+        ogq.ogq_dequantize_average([torch.zeros(64, dtype=torch.int64)], [torch.zeros(4)], 4096, p)  # host memory
