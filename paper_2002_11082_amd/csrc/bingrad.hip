@@ -5,6 +5,13 @@
 
 namespace ogq {
 
+// x unchanged, but opaque to the optimizer: what is derived from it is computed again instead of kept in registers.
+__device__ __forceinline__ float reread(float x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 // ----------------------------------------------------------------------------------------------
 // BinGrad-b quantize.  Lane l register j holds bucket element 64*j + l, so a ballot over
 // register j is the packed code word j of the bucket.
@@ -68,11 +75,13 @@ __device__ __forceinline__ void bingrad_bucket(Team team, uint32_t first_element
 #pragma unroll
         for (int j = 0; j < E; ++j) {
             const bool valid = FULL || (first + 64u * j < len);
-            const bool lo = valid && (v[j] < b0);
+            // (with 64 registers of data the fp64 copies the compiler would keep from the first pass do not fit)
+            const float x = E > 32 ? reread(v[j]) : v[j];
+            const bool lo = valid && (x < b0);
             const uint64_t lo_mask = __ballot(lo);
             const uint64_t hi_mask = FULL ? ~lo_mask : __ballot(valid && !lo);
             below += lo ? 1u : 0u;
-            s_lo += (double)(lo ? v[j] : 0.0f);
+            s_lo += (double)(lo ? x : 0.0f);
             word_lo = writelane(word_lo, (uint32_t)hi_mask, j);
             word_hi = writelane(word_hi, (uint32_t)(hi_mask >> 32), j);
         }
@@ -138,9 +147,11 @@ __global__ __launch_bounds__(kWave* kBinGradWaves) __attribute__((amdgpu_waves_p
     else bingrad_bucket<E, false, CLIP, SIGN>(OneWave{}, 0u, g, len, iters, clip, lv, w);
 }
 
-// Buckets of more than 2048 elements: the W = 2, 4, 8 or 16 wavefronts of a workgroup hold one bucket, 32
-// registers per lane each as for a 2048-element bucket, and combine their sums and counts through LDS.
-template <int W, bool CLIP, bool SIGN>
+// Buckets of more than 2048 elements: the W = 2, 4, 8 or 16 wavefronts of a workgroup hold one bucket, E = 32
+// registers per lane each as for a 2048-element bucket, and combine their sums and counts through LDS.  Above
+// 8192 elements E = 64 (without clipping), so that a workgroup is at most 8 wavefronts and two buckets share a
+// compute unit: the loads of one overlap the passes of the other.
+template <int W, int E, bool CLIP, bool SIGN>
 __global__ __launch_bounds__(W* kWave) __attribute__((amdgpu_waves_per_eu(4, 4))) void bingrad_team_kernel(
     const float* __restrict__ grad, size_t n, uint32_t bucket_size, uint32_t iters, float clip, uint32_t num_buckets,
     float* __restrict__ levels, uint64_t* __restrict__ codes)
@@ -156,8 +167,11 @@ __global__ __launch_bounds__(W* kWave) __attribute__((amdgpu_waves_per_eu(4, 4))
     uint64_t* w = codes + begin / 64;
     const uint32_t wave = uniform_u32(threadIdx.x >> 6);
     const WaveTeam<W> team{slots, wave, 0u};
-    if (len == 2048u * W) bingrad_bucket<32, true, CLIP, SIGN>(team, 2048u * wave, g, len, iters, clip, lv, w);
-    else bingrad_bucket<32, false, CLIP, SIGN>(team, 2048u * wave, g, len, iters, clip, lv, w);
+    constexpr uint32_t PER_WAVE = 64u * E;
+    // A wavefront whose 64 E elements all lie inside the bucket skips the per-element bounds tests.  Both variants
+    // reach the same combines in the same order (every branch around one depends on combined values only).
+    if (PER_WAVE * (wave + 1u) <= len) bingrad_bucket<E, true, CLIP, SIGN>(team, PER_WAVE * wave, g, len, iters, clip, lv, w);
+    else bingrad_bucket<E, false, CLIP, SIGN>(team, PER_WAVE * wave, g, len, iters, clip, lv, w);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -446,22 +460,24 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
 #undef OGQ_LAUNCH
 }
 
-template <int W>
+template <int W, int E = 32>
 void launch_bingrad_team(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                          hipStream_t st)
 {
     const dim3 grid(nb), block(W * kWave);
     const bool clip = p->clip_factor > 0.0f, sign = p->scheme == OGQ_SCALED_SIGN;
 #define OGQ_LAUNCH(CLIP, SIGN)                                                                               \
-    hipLaunchKernelGGL((bingrad_team_kernel<W, CLIP, SIGN>), grid, block, 0, st, g, n, p->bucket_size,      \
+    hipLaunchKernelGGL((bingrad_team_kernel<W, E, CLIP, SIGN>), grid, block, 0, st, g, n, p->bucket_size,   \
                        p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes))
-    if (sign) {
-        if (clip) OGQ_LAUNCH(true, true);
-        else OGQ_LAUNCH(false, true);
-    } else {
-        if (clip) OGQ_LAUNCH(true, false);
-        else OGQ_LAUNCH(false, false);
+    if constexpr (E <= 32) {  // 64 registers of data leave no room for the clipping passes: the caller picks E = 32
+        if (clip) {
+            if (sign) OGQ_LAUNCH(true, true);
+            else OGQ_LAUNCH(true, false);
+            return;
+        }
     }
+    if (sign) OGQ_LAUNCH(false, true);
+    else OGQ_LAUNCH(false, false);
 #undef OGQ_LAUNCH
 }
 
@@ -516,8 +532,12 @@ void launch_two_level(const float* g, size_t n, const ogq_params_t* p, float* lv
     else if (regs <= 32) launch_bingrad<32>(g, n, p, nb, lv, codes, st);
     else if (regs <= 64) launch_bingrad_team<2>(g, n, p, nb, lv, codes, st);
     else if (regs <= 128) launch_bingrad_team<4>(g, n, p, nb, lv, codes, st);
-    else if (regs <= 256) launch_bingrad_team<8>(g, n, p, nb, lv, codes, st);
-    else launch_bingrad_team<16>(g, n, p, nb, lv, codes, st);
+    else if (p->clip_factor > 0.0f) {
+        // the clipping passes need the registers a second 2048 elements per wavefront would take
+        if (regs <= 256) launch_bingrad_team<8>(g, n, p, nb, lv, codes, st);
+        else launch_bingrad_team<16>(g, n, p, nb, lv, codes, st);
+    } else if (regs <= 256) launch_bingrad_team<4, 64>(g, n, p, nb, lv, codes, st);
+    else launch_bingrad_team<8, 64>(g, n, p, nb, lv, codes, st);
 }
 
 }  // namespace ogq

@@ -181,6 +181,7 @@ __device__ __forceinline__ double uniform_f64(double x)
 // wave-wide result becomes a bucket-wide one.
 // ----------------------------------------------------------------------------------------------
 struct OneWave {
+    static constexpr int kSize = 1;
     __device__ __forceinline__ double sum(double x) { return x; }
     __device__ __forceinline__ void sum_and_max(double&, float&) {}
     __device__ __forceinline__ void sum_and_count(double&, uint32_t&) {}
@@ -196,6 +197,7 @@ struct TeamSlot {
 
 template <int W>
 struct WaveTeam {
+    static constexpr int kSize = W;
     TeamSlot (*slots)[W];  // [2][W] in LDS: [call parity][wavefront]
     uint32_t wave;
     uint32_t calls;
