@@ -419,6 +419,56 @@ def test_calls_can_be_captured_in_a_graph():
             assert torch.equal(replayed[2], out_e[:n])
 
 
+@pytest.mark.parametrize("scheme,bits,d,iters", [(ogq.BINGRAD_B, 1, 2048, 1), (ogq.BINGRAD_B, 1, 512, 0), (ogq.ORQ, 2, 2048, 2),
+                                                  (ogq.ORQ_PAPER, 2, 8192, 0)])
+def test_gradient_longer_than_2_pow_32_elements(scheme, bits, d, iters):
+    """Element and word indices beyond 32 bits: a gradient of 2^32 + 5 d + 77 elements (17 GB), built on the device
+    from a seeded host block that is repeated with a different scale per repetition, so that buckets 2^32 elements
+    apart differ.  Buckets at both ends, on both sides of element 2^32 and the short last bucket are checked
+    against the oracle (levels, codes, decoded values), which gets the bucket contents read back from the device."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 48 * 2 ** 30:
+        pytest.skip("needs 48 GB of free device memory")
+    block = 1 << 24
+    n = (1 << 32) + 5 * d + 77
+    base = torch.from_numpy(synth.laplace_heavy_tail(block, 5e-4, 77)).to(DEV)
+    g = torch.empty(n, dtype=torch.float32, device=DEV)
+    for t, lo in enumerate(range(0, n, block)):
+        hi = min(lo + block, n)
+        torch.mul(base[:hi - lo], 1.0 + t / 1024.0, out=g[lo:hi])
+    seed, offset = 11, 64 * 3
+    params = ogq.make_params(d, bits, scheme, iters, seed, offset)
+    s = ogq.ogq_levels_per_bucket(params)
+    print(f"[parity] beyond-2^32 n={n} d={d} bits={bits} scheme={scheme} iters={iters}", flush=True)
+    levels, codes = ogq.ogq_quantize(g, params)
+    out = ogq.ogq_dequantize_average([codes], [levels], n, params)
+    torch.cuda.synchronize()
+    nb = (n + d - 1) // d
+    assert ogq.ogq_num_buckets(n, params) == nb and n % d != 0
+    edge = (1 << 32) // d
+    picks = sorted({0, 1, edge - 2, edge - 1, edge, edge + 1, nb - 3, nb - 2, nb - 1, nb // 3, edge // 2 + 7})
+    for b in picks:
+        lo, hi = b * d, min((b + 1) * d, n)
+        x = g[lo:hi].cpu().numpy()
+        lv_ref, codes_ref, _ = oracle.quantize_codes(x, d, bits, scheme, iters, seed, offset + lo)
+        lv_gpu = levels[b * s:(b + 1) * s].cpu().numpy()
+        words = codes[lo // 64 * bits:(hi + 63) // 64 * bits].cpu().numpy().view(np.uint64)
+        assert np.array_equal(lv_gpu, lv_ref), (b, lv_gpu, lv_ref)
+        assert np.array_equal(parity.unpack_words(words, hi - lo, bits), codes_ref), b
+        l, w = oracle.quantize(x, d, bits, scheme, iters, seed, offset + lo)
+        assert np.array_equal(out[lo:hi].cpu().numpy(), oracle.dequantize_average([w], [l], hi - lo, d, bits, s)), b
+    # every decoded value is one of its bucket's levels (whole array, compared on the device)
+    full = n // d
+    table = levels[:full * s].view(full, s)
+    view = out[:full * d].view(full, d)
+    hit = torch.zeros_like(view, dtype=torch.bool)
+    for k in range(s):
+        hit |= view == table[:, k:k + 1]
+    assert bool(hit.all())
+    del g, out, hit, levels, codes
+    torch.cuda.empty_cache()
+
+
 def test_empty_input_is_a_noop():
     p = ogq.make_params(512, 1, ogq.BINGRAD_B)
     x = torch.zeros(4, device=DEV)
