@@ -10,7 +10,8 @@ buffers (>= 1 GB in total) so that the 256 MB last-level cache cannot serve repe
 Prints ONE JSON line.  `value` is the fp32-gradient throughput of the whole step (4*n*workers
 bytes per step / time per step); `roofline` prices the dominant kernel's algorithmic bytes per
 launch against the HBM peak using HIP-event timings taken inside the timed region;
-`cpu_baseline` is the plain CPU oracle timed on the host cores (a reported baseline only).
+`cpu_baseline` is the plain CPU oracle timed on the host cores, with OpenMP over buckets and on one
+thread (a reported baseline only).
 """
 from __future__ import annotations
 
@@ -278,12 +279,23 @@ def main() -> int:
                                       ogq.ogq_levels_per_bucket(params[0]))
             t_cpu += time.perf_counter() - c0
             reps_cpu += 1
+        # the same oracle on one thread, on a shorter prefix of worker 0's gradient
+        one_n = min(sample_n, 2_097_152)
+        one_n -= one_n % d
+        oracle.set_threads(1)
+        c0 = time.perf_counter()
+        q1 = oracle.quantize(g0[0][:one_n], d, bits, wl.scheme, wl.level_iters, wl.philox_seed(0), 0, wl.clip_factor)
+        oracle.dequantize_average([q1[1]], [q1[0]], one_n, d, bits, ogq.ogq_levels_per_bucket(params[0]))
+        t_one = time.perf_counter() - c0
+        oracle.set_threads(threads)
         result["cpu_baseline"] = {
             "value": round(4 * sample_n * W * reps_cpu / t_cpu / 1e9, 3),
             "unit": "GB/s of fp32 gradient through quantize+pack+decode-average",
             "cores": threads, "kind": "oracle",
             "sample": f"first {sample_n} elements of each worker's gradient of {wl.name}, {reps_cpu} repetitions, "
                       f"{t_cpu:.1f} s, OpenMP over buckets",
+            "single_thread_value": round(4 * one_n / t_one / 1e9, 4),
+            "single_thread_sample": f"first {one_n} elements of worker 0's gradient, one pass, {t_one:.2f} s",
         }
     print(json.dumps(result))
     return 0
