@@ -246,17 +246,53 @@ __device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint
         c_le = (uint32_t)__popcll(__ballot(le));
         s_lt = wave_sum((double)head + (lt ? (double)key_to_float(sorted) : 0.0));
     } else {
-        // a crowded bin (many equal or nearly equal values): bisection on the key over all its chunks
-        uint32_t prefix = 0;
-        for (int bit = 31; bit >= 0; --bit) {
-            const uint32_t cand = prefix | (1u << bit);
-            uint32_t below = 0;
+        // A crowded bin (many equal or nearly equal values): bisection on the key, over the bits in which the bin's
+        // smallest and largest key differ (none when all its values are equal).  Up to 256 keys stay in registers.
+        constexpr int HELD = 4;
+        const bool held = count <= 64u * HELD;
+        uint32_t mine[HELD];
+        uint32_t smallest = 0xFFFFFFFFu, largest = 0u;
+        if (held) {
+#pragma unroll
+            for (int c = 0; c < HELD; ++c) {
+                const uint32_t i = 64u * c + lane;
+                const bool valid = i < count;
+                mine[c] = valid ? stored_key(lds.grouped[skewed(first + (valid ? i : 0u))]) : 0xFFFFFFFFu;
+                smallest = umin32(smallest, mine[c]);
+                largest = umax32(largest, valid ? mine[c] : 0u);
+            }
+        } else {
             for (uint32_t base = 0; base < count; base += 64u) {
                 const uint32_t i = base + lane;
-                const uint32_t k = i < count ? stored_key(lds.grouped[skewed(first + i)]) : 0xFFFFFFFFu;
-                below += (uint32_t)__popcll(__ballot(k < cand));
+                if (i < count) {
+                    const uint32_t k = stored_key(lds.grouped[skewed(first + i)]);
+                    smallest = umin32(smallest, k);
+                    largest = umax32(largest, k);
+                }
             }
-            if (below < r_in) prefix = cand;
+        }
+        smallest = wave_min_u32(smallest);
+        largest = wave_max_u32(largest);
+        const uint32_t differing = smallest ^ largest;
+        uint32_t prefix = smallest;
+        if (differing != 0u) {
+            const int top = 31 - __builtin_clz(differing);
+            prefix = top == 31 ? 0u : smallest & ~((2u << top) - 1u);  // the bits above `top` are common to all keys
+            for (int bit = top; bit >= 0; --bit) {
+                const uint32_t cand = prefix | (1u << bit);
+                uint32_t below = 0;
+                if (held) {
+#pragma unroll
+                    for (int c = 0; c < HELD; ++c) below += (uint32_t)__popcll(__ballot(mine[c] < cand));
+                } else {
+                    for (uint32_t base = 0; base < count; base += 64u) {
+                        const uint32_t i = base + lane;
+                        const uint32_t k = i < count ? stored_key(lds.grouped[skewed(first + i)]) : 0xFFFFFFFFu;
+                        below += (uint32_t)__popcll(__ballot(k < cand));
+                    }
+                }
+                if (below < r_in) prefix = cand;
+            }
         }
         key = prefix;
         c_lt = 0;
@@ -557,6 +593,31 @@ __device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, EdgeFn 
             // gap is below gap(e) = e * #{v > 0} - (sum of the bins above j); the wanted value sits in the first bin
             // j whose gap(e) is not negative, or is the first element after it.  One block-prefix look-up per step.
             uint32_t bin_lo = (uint32_t)(Lds::B / 2), bin_hi = (uint32_t)Lds::B - 1u;
+            // All positive bins at once, one per lane: the sum before a position lies between the prefixes of the
+            // block it falls into and of the next block (positive bins hold positive values), which brackets
+            // gap(e) from both sides and decides its sign for every bin except the few whose first position shares
+            // a block with the sign change; the bisection then runs over those only.  (A block that begins among the
+            // negative values gives no lower bracket.)
+            const uint32_t first_not_negative = uniform_u32(lds.bin_start[Lds::B / 2]);
+            for (uint32_t bin0 = (uint32_t)(Lds::B / 2); bin0 < (uint32_t)Lds::B; bin0 += kWave) {
+                const uint32_t bin = bin0 + lane;
+                const uint32_t above = lds.bin_start[bin + 1u];
+                const uint32_t block = above / (uint32_t)Lds::BLOCK;
+                const bool inside = above < len;  // otherwise nothing lies above the bin: gap(e) >= 0
+                const double before_lo = inside ? lds.block_prefix[block] : total;
+                const double before_hi =
+                    inside && (block + 1u) * (uint32_t)Lds::BLOCK < len ? lds.block_prefix[block + 1u] : total;
+                const double scaled_edge = (double)lower_edge_of_bin(bin + 1u) * (double)positives;
+                const bool bracketed_below = !inside || block * (uint32_t)Lds::BLOCK >= first_not_negative;
+                const uint64_t surely_not_negative =
+                    __ballot(bracketed_below && scaled_edge - (total - before_lo) >= 0.0);
+                const uint64_t surely_negative = __ballot(scaled_edge - (total - before_hi) < 0.0);
+                if (surely_negative != 0)
+                    bin_lo = umax32(bin_lo, bin0 + 64u - (uint32_t)__builtin_clzll(surely_negative));
+                if (surely_not_negative != 0)
+                    bin_hi = umin32(bin_hi, bin0 + (uint32_t)__builtin_ctzll(surely_not_negative));
+            }
+            if (bin_lo > bin_hi) bin_lo = bin_hi;  // only rounding can make the two bounds cross
             while (bin_lo < bin_hi) {
                 const uint32_t mid = (bin_lo + bin_hi) >> 1;
                 const uint32_t above = uniform_u32(lds.bin_start[mid + 1u]);  // first position of the bins above mid
