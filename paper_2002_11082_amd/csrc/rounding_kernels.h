@@ -788,7 +788,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     const uint32_t key_min = float_to_key(bucket_min), key_max = float_to_key(bucket_max);
     const uint32_t mag_max = umax32(__float_as_uint(bucket_min) & 0x7FFFFFFFu, __float_as_uint(bucket_max) & 0x7FFFFFFFu);
     const uint32_t t_max = mag_max >> SHIFT;
-    const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
+    const uint32_t t_low = __builtin_elementwise_sub_sat(t_max, (uint32_t)(HALF - 1));
 
     float pb_level = 0.0f;
     if constexpr ((S > 2 && RULE != kEven) || PB) {
@@ -833,17 +833,26 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
-        // ---- scatter the values into their bins ---------------------------------------------------
+        // ---- scatter the values into their bins: the bin starts of a group of elements are all read before the
+        //      group's values are written (a read behind a write to the same LDS object would wait for it) ------
+        constexpr int GROUP = C < 4 ? C : 4;
 #pragma unroll
-        for (int c = 0; c < C; ++c)
+        for (int c0 = 0; c0 < C; c0 += GROUP) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const bool valid = full || (256u * c + 4u * lane + k < len);
-                if (valid) {
-                    const uint32_t bin = slot[c][k] & 0xFFFFu, pos = slot[c][k] >> 16;
-                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(v[c][k]);
+            for (int c = c0; c < c0 + GROUP; ++c)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const bool valid = full || (256u * c + 4u * lane + k < len);
+                    if (valid) slot[c][k] = lds.bin_start[slot[c][k] & 0xFFFFu] + (slot[c][k] >> 16);
                 }
-            }
+#pragma unroll
+            for (int c = c0; c < c0 + GROUP; ++c)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const bool valid = full || (256u * c + 4u * lane + k < len);
+                    if (valid) lds.grouped[skewed(slot[c][k])] = __float_as_uint(v[c][k]);
+                }
+        }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
@@ -1029,7 +1038,7 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
     const uint32_t key_min = float_to_key(bucket_min), key_max = float_to_key(bucket_max);
     const uint32_t mag_max = umax32(__float_as_uint(bucket_min) & 0x7FFFFFFFu, __float_as_uint(bucket_max) & 0x7FFFFFFFu);
     const uint32_t t_max = mag_max >> SHIFT;
-    const uint32_t t_low = t_max > (uint32_t)(HALF - 1) ? t_max - (uint32_t)(HALF - 1) : 0u;
+    const uint32_t t_low = __builtin_elementwise_sub_sat(t_max, (uint32_t)(HALF - 1));
 
     if constexpr ((S > 2 && RULE != kEven) || PB) {
         // ---- histogram: the returning LDS add hands every element its position inside its bin ------------
@@ -1062,17 +1071,25 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
         }
         __syncthreads();
 
-        // ---- scatter the values into their bins -------------------------------------------------------
+        // ---- scatter the values into their bins (bin starts of a group of elements read before its writes) ------
+        constexpr int GROUP = C < 4 ? C : 4;
 #pragma unroll
-        for (int c = 0; c < C; ++c)
+        for (int c0 = 0; c0 < C; c0 += GROUP) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
-                if (valid) {
-                    const uint32_t bin = slot[c][k] & 0xFFFFu, pos = slot[c][k] >> 16;
-                    lds.grouped[skewed(lds.bin_start[bin] + pos)] = __float_as_uint(v[c][k]);
+            for (int c = c0; c < c0 + GROUP; ++c)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                    if (valid) slot[c][k] = lds.bin_start[slot[c][k] & 0xFFFFu] + (slot[c][k] >> 16);
                 }
-            }
+#pragma unroll
+            for (int c = c0; c < c0 + GROUP; ++c)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                    if (valid) lds.grouped[skewed(slot[c][k])] = __float_as_uint(v[c][k]);
+                }
+        }
         __syncthreads();
 
         // ---- fp64 prefix of the grouped values per block of 4C positions (thread t sums block t) ----------
