@@ -324,11 +324,11 @@ __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B, S>& lds, const ui
                                             uint32_t rank, uint32_t lane)
 {
     constexpr int PER = B / 64;
-    // the bin holding the rank: the last bin whose first position is below the rank
+    // the bin holding the rank: the last bin whose first position is below the rank (counted on the scalar unit)
     uint32_t starts_below = 0;
 #pragma unroll
-    for (int t = 0; t < PER; ++t) starts_below += (my_start[t] < rank) ? 1u : 0u;
-    const uint32_t bin = wave_sum_u32(starts_below) - 1u;  // bin_start[0] = 0 < rank: at least one
+    for (int t = 0; t < PER; ++t) starts_below += (uint32_t)__popcll(__ballot(my_start[t] < rank));
+    const uint32_t bin = starts_below - 1u;  // bin_start[0] = 0 < rank: at least one
     return pick_in_bin<D / 64>(lds, bin, rank, lane);
 }
 
