@@ -461,6 +461,7 @@ __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k,
     const uint32_t cnt_le_R = uniform_u32(lds.lvl_count_le[r]);
     const double sum_lt_L = uniform_f64(lds.lvl_sum_lt[l]);
     const double sum_le_R = uniform_f64(lds.lvl_sum_le[r]);
+    const uint32_t last_rank = uniform_u32(lds.lvl_rank[k]);  // read with the others: one wait for all of them
     bool copy_left = !(L < R);
     Picked p;
     uint32_t rank = 0;
@@ -472,7 +473,7 @@ __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k,
         if (!(m >= 0.0)) m = 0.0;
         rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
         rank = rank < 1u ? 1u : (rank > len ? len : rank);
-        if (rank == uniform_u32(lds.lvl_rank[k])) return;  // same element as last time
+        if (rank == last_rank) return;  // same element as last time
         p = pick(rank);
         if (key_to_float(p.key) < L) copy_left = true;
     }
