@@ -217,14 +217,12 @@ struct Picked {
     double sum_lt, sum_le;
 };
 
-// The element of 1-based rank `rank`, which lies in bin `bin`.  BLOCK = positions per entry of the fp64
-// block prefix (at most 64).
+// The element of 1-based rank `rank`, which lies in the bin that holds positions [first, first + count).  BLOCK =
+// positions per entry of the fp64 block prefix (at most 64).
 template <int BLOCK, class Lds>
-__device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint32_t rank, uint32_t lane)
+__device__ __forceinline__ Picked pick_in_span(const Lds& lds, uint32_t first, uint32_t count, uint32_t rank, uint32_t lane)
 {
     static_assert(BLOCK <= 64, "the head of a block is read one position per lane");
-    const uint32_t first = uniform_u32(lds.bin_start[bin]);
-    const uint32_t count = uniform_u32(lds.bin_start[bin + 1]) - first;
     const uint32_t r_in = rank - first;  // 1-based rank inside the bin
 
     // sum of everything before the bin = prefix of its block + the block's positions before `first`
@@ -318,6 +316,15 @@ __device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint
     return p;
 }
 
+// The same for bin `bin`.
+template <int BLOCK, class Lds>
+__device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint32_t rank, uint32_t lane)
+{
+    const uint32_t first = uniform_u32(lds.bin_start[bin]);
+    const uint32_t count = uniform_u32(lds.bin_start[bin + 1]) - first;
+    return pick_in_span<BLOCK>(lds, first, count, rank, lane);
+}
+
 // rank is 1-based, 1 <= rank <= bucket length.  my_start[t] = bin_start[lane * PER + t], kept in registers.
 template <int D, int B, int S>
 __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B, S>& lds, const uint32_t (&my_start)[B / 64],
@@ -339,10 +346,16 @@ __device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t r
 {
     constexpr uint32_t PER = Lds::B / 64;
     static_assert(PER <= 64, "one lane per bin of a segment");
-    const uint32_t segment = (uint32_t)__popcll(__ballot(lds.bin_start[lane * PER] < rank)) - 1u;
-    const bool below = lane < PER && lds.bin_start[segment * PER + (lane < PER ? lane : 0u)] < rank;
-    const uint32_t bin = segment * PER + (uint32_t)__popcll(__ballot(below)) - 1u;
-    return pick_in_bin<Lds::BLOCK>(lds, bin, rank, lane);
+    const uint32_t coarse = lds.bin_start[lane * PER];
+    const uint32_t segment = (uint32_t)__popcll(__ballot(coarse < rank)) - 1u;
+    const uint32_t fine = lds.bin_start[segment * PER + (lane < PER ? lane : 0u)];
+    const uint32_t within = (uint32_t)__popcll(__ballot(lane < PER && fine < rank)) - 1u;  // the bin is segment * PER + within
+    // its first position and that of the next bin are already in the registers of two lanes
+    const uint32_t first = __builtin_amdgcn_readlane(fine, within);
+    const uint32_t next = within + 1u < PER ? __builtin_amdgcn_readlane(fine, (within + 1u) & 63u)
+                          : segment < 63u   ? __builtin_amdgcn_readlane(coarse, (segment + 1u) & 63u)
+                                            : uniform_u32(lds.bin_start[Lds::B]);
+    return pick_in_span<Lds::BLOCK>(lds, first, next - first, rank, lane);
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
