@@ -33,6 +33,18 @@ __device__ __forceinline__ float select_tree(const bool (&bit)[4], const float* 
 }
 
 template <int BITS, int S>
+__device__ __forceinline__ float select_from_bits(const bool (&bit)[4], const float (&lv)[S])
+{
+    if constexpr (S == (1 << BITS)) {
+        return select_tree<BITS>(bit, lv);
+    } else {
+        static_assert(S == (1 << (BITS - 1)) + 1, "level count");
+        const float low = select_tree<BITS - 1>(bit, lv);
+        return bit[BITS - 1] ? lv[S - 1] : low;
+    }
+}
+
+template <int BITS, int S>
 __device__ __forceinline__ float select_level(const uint64_t* __restrict__ w, const float (&lv)[S])
 {
     bool bit[4] = {false, false, false, false};
@@ -82,6 +94,69 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
 #pragma unroll
     for (int j = 0; j < kSpanWords; ++j) acc[j] = 0.0;
 
+    if (WPB > 0 && whole) {
+        // Every element of the span exists and its buckets lie at fixed places: the span's code words and level
+        // tables are fetched with vector loads (lane i takes dword i), for several workers at once so that their
+        // trips to HBM overlap, and reach the scalar registers through v_readlane.  (Scalar loads, which deliver the
+        // lane masks directly, keep too few bytes in flight per wavefront once the streams come from HBM instead of
+        // the last-level cache.)
+        constexpr int kTables = WPB > 0 ? kSpanWords / WPB : 1;
+        constexpr int R = (32 * BITS + 63) / 64;        // registers for the 32 * BITS dwords of code words
+        constexpr int LR = (kTables * S + 63) / 64;     // registers for the kTables * S level values
+        constexpr uint32_t BATCH = R + LR > 2 ? 4 : 8;  // workers in flight
+        const uint32_t first_bucket = WPB == kSpanWords ? word0 / words_per_bucket : word0 / (uint32_t)(WPB > 0 ? WPB : 1);
+        for (uint32_t w0 = 0; w0 < num_workers; w0 += BATCH) {
+            uint32_t code_reg[BATCH][R];
+            float level_reg[BATCH][LR];
+#pragma unroll
+            for (uint32_t b = 0; b < BATCH; ++b) {
+#pragma unroll
+                for (int k = 0; k < R; ++k) code_reg[b][k] = 0u;
+#pragma unroll
+                for (int k = 0; k < LR; ++k) level_reg[b][k] = 0.0f;
+                if (w0 + b < num_workers) {
+                    const uint32_t* c32 = reinterpret_cast<const uint32_t*>(ptrs.codes[w0 + b] + (size_t)word0 * BITS);
+                    const float* tables = ptrs.levels[w0 + b] + (size_t)first_bucket * S;
+#pragma unroll
+                    for (int k = 0; k < R; ++k) {
+                        const uint32_t i = 64u * k + lane;
+                        if (i < 32u * BITS) code_reg[b][k] = c32[i];
+                    }
+#pragma unroll
+                    for (int k = 0; k < LR; ++k) {
+                        const uint32_t i = 64u * k + lane;
+                        if (i < (uint32_t)(kTables * S)) level_reg[b][k] = tables[i];
+                    }
+                }
+            }
+#pragma unroll
+            for (uint32_t b = 0; b < BATCH; ++b) {
+                if (w0 + b < num_workers) {
+#pragma unroll
+                    for (int t = 0; t < kTables; ++t) {
+                        float lv[S];
+#pragma unroll
+                        for (int k = 0; k < S; ++k) {
+                            const int at = t * S + k;
+                            lv[k] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(level_reg[b][at / 64]), at % 64));
+                        }
+#pragma unroll
+                        for (int j = t * (WPB > 0 ? WPB : 1); j < (t + 1) * (WPB > 0 ? WPB : 1); ++j) {
+                            bool bit[4] = {false, false, false, false};
+#pragma unroll
+                            for (int p = 0; p < BITS; ++p) {
+                                const int d0 = 2 * (j * BITS + p), d1 = d0 + 1;
+                                const uint32_t lo = __builtin_amdgcn_readlane(code_reg[b][d0 / 64], d0 % 64);
+                                const uint32_t hi = __builtin_amdgcn_readlane(code_reg[b][d1 / 64], d1 % 64);
+                                bit[p] = __builtin_amdgcn_inverse_ballot_w64(((uint64_t)hi << 32) | lo);
+                            }
+                            acc[j] += (double)select_from_bits<BITS, S>(bit, lv);
+                        }
+                    }
+                }
+            }
+        }
+    } else  // the ragged end of the gradient and bucket sizes without a fixed layout: scalar loads, word by word
     for (uint32_t w = 0; w < num_workers; ++w) {
         const uint64_t* __restrict__ cw = ptrs.codes[w] + (size_t)word0 * BITS;
         const float* __restrict__ table = ptrs.levels[w];
@@ -89,25 +164,15 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
             constexpr int kTables = kSpanWords / WPB;
             const uint32_t first_bucket = WPB == kSpanWords ? word0 / words_per_bucket : word0 / (uint32_t)WPB;
             const float* __restrict__ first_table = table + (size_t)first_bucket * S;
-            if (whole) {
 #pragma unroll
-                for (int t = 0; t < kTables; ++t) {
+            for (int t = 0; t < kTables; ++t)
+                if ((uint32_t)(t * WPB) < n_words) {  // a bucket past the end has no table
                     float lv[S];
                     load_levels<S>(first_table + t * S, lv);
 #pragma unroll
-                    for (int j = t * WPB; j < (t + 1) * WPB; ++j) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
+                    for (int j = t * WPB; j < (t + 1) * WPB; ++j)
+                        if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
                 }
-            } else {
-#pragma unroll
-                for (int t = 0; t < kTables; ++t)
-                    if ((uint32_t)(t * WPB) < n_words) {  // a bucket past the end has no table
-                        float lv[S];
-                        load_levels<S>(first_table + t * S, lv);
-#pragma unroll
-                        for (int j = t * WPB; j < (t + 1) * WPB; ++j)
-                            if ((uint32_t)j < n_words) acc[j] += (double)select_level<BITS, S>(cw + j * BITS, lv);
-                    }
-            }
         } else {
 #pragma unroll
             for (int j = 0; j < kSpanWords; ++j)
