@@ -9,7 +9,8 @@ buffers (>= 1 GB in total) so that the 256 MB last-level cache cannot serve repe
 
 Prints ONE JSON line.  `value` is the fp32-gradient throughput of the whole step (4*n*workers
 bytes per step / time per step); `roofline` prices the dominant kernel's algorithmic bytes per
-launch against the HBM peak using HIP-event timings taken inside the timed region;
+launch against the HBM peak using HIP-event timings taken inside the timed region (the decoder's entry also
+carries `cold_*` figures: the same kernel over packed streams that no cache holds);
 `cpu_baseline` is the plain CPU oracle timed on the host cores, with OpenMP over buckets and on one
 thread (a reported baseline only).
 """
@@ -172,9 +173,10 @@ def main() -> int:
     eq1.record(stream)
     torch.cuda.synchronize()
     # The decoder's inputs are the packed streams, 1/32 .. 1/8 of the gradient's size: the sets the step loop rotates
-    # over would all stay in the 256 MB last-level cache.  Its own timing therefore rotates over as many further
-    # sets of packed streams and level tables as it takes to hold 512 MB (at most 192), filled by untimed quantize
-    # launches; the outputs rotate over the step loop's buffers.
+    # over stay in the 256 MB last-level cache, as they do inside a step, where the decoder reads what the quantizer
+    # has just written.  The decoder is therefore timed twice: over those sets, and over as many further sets of packed
+    # streams and level tables as it takes to hold 512 MB (at most 192; filled by untimed quantize launches), which is
+    # what it sees when the streams arrive from elsewhere.  The outputs rotate over the step loop's buffers.
     codes_per_set = W * n_words * 8
     n_sets = max(n_buf, min(192, -(-(512 << 20) // codes_per_set) + 1))
     d_args = list(a_args)
@@ -195,11 +197,19 @@ def main() -> int:
     torch.cuda.synchronize()
     for i in range(min(n_sets, 8)):
         average(*d_args[i])
-    ea0.record(stream)
+    ec0, ec1 = ev(), ev()
+    ec0.record(stream)
     for i in range(args.steps):
         average(*d_args[i % n_sets])
+    ec1.record(stream)
+    torch.cuda.synchronize()
+    # ... and over the step loop's own sets, i.e. with the packed streams where a step leaves them
+    ea0.record(stream)
+    for i in range(args.steps):
+        average(*a_args[i % n_buf])
     ea1.record(stream)
     torch.cuda.synchronize()
+    a_cold = ec0.elapsed_time(ec1) / args.steps  # ms per decode-average launch on cold packed streams
     q_avg = eq0.elapsed_time(eq1) / (args.steps * W)  # ms per quantize launch
     a_avg = ea0.elapsed_time(ea1) / args.steps        # ms per decode-average launch
     q_bytes, a_bytes = algorithmic_bytes(n, d, bits, W, ogq.ogq_levels_per_bucket(params[0]))
@@ -245,6 +255,8 @@ def main() -> int:
         "algorithmic_bytes_per_launch": q_bytes if dominant_is_quant else a_bytes,
         "avg_launch_us": round((q_avg if dominant_is_quant else a_avg) * 1e3, 2),
     }
+    cold = {"cold_avg_launch_us": round(a_cold * 1e3, 2), "cold_achieved": round(a_bytes / (a_cold * 1e-3) / 1e9, 1),
+            "cold_frac": round(a_bytes / (a_cold * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "cold_input_sets": n_sets}
     other = {
         "kernel": "dequantize_average_kernel" if dominant_is_quant else quant_name,
         "achieved": round(a_gbs if dominant_is_quant else q_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -253,6 +265,8 @@ def main() -> int:
         "algorithmic_bytes_per_launch": a_bytes if dominant_is_quant else q_bytes,
         "avg_launch_us": round((a_avg if dominant_is_quant else q_avg) * 1e3, 2),
     }
+
+    (other if dominant_is_quant else roof).update(cold)  # the decoder's entry also carries its cold-stream figures
 
     # VALU instructions per wavefront of the quantize kernel, from rocprofv3 --pmc SQ_INSTS_VALU / SQ_WAVES
     # (profiles/valu_instructions.txt), priced against 78.6 T lane-operations/s (256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz)
