@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--buffers", type=int, default=0, help="distinct input buffers (0 = enough for 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the K timed steps into one HIP graph and time its replay (same kernels, same order)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -150,11 +152,21 @@ def main() -> int:
 
     # ---- timed region: exactly K steps ------------------------------------------------------------
     e_begin, e_end = ev(), ev()
+    graph = None
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(args.steps):
+                step(args.warmup + i)
+        torch.cuda.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e_begin.record(stream)
-    for i in range(args.steps):
-        step(args.warmup + i)
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(args.steps):
+            step(args.warmup + i)
     e_end.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -289,7 +301,8 @@ def main() -> int:
         "dtype": "f32 data, f64 sums", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.description}", "n": n, "bucket_size": d, "bits": bits,
                    "workers": W, "level_iters": wl.level_iters, "clip_factor": wl.clip_factor,
-                   "input_buffers": n_buf, "decoder_input_sets": n_sets},
+                   "input_buffers": n_buf, "decoder_input_sets": n_sets,
+                   "launch": "one HIP graph of the K steps" if args.graph else "direct"},
         "elements_per_s": round(n * W / (ms_per_step * 1e-3), 1),
         "quantize_gbs_fp32_in": round(4 * n / (q_avg * 1e-3) / 1e9, 1),
         "dequant_avg_gbs_fp32_out": round(4 * n / (a_avg * 1e-3) / 1e9, 1),
