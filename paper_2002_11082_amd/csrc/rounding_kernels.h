@@ -770,6 +770,17 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
             const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + 256 * c + 4 * lane));
             v[c][0] = q.x; v[c][1] = q.y; v[c][2] = q.z; v[c][3] = q.w;
         }
+    } else if (len % 4u == 0u) {
+        // a bucket shorter than the wavefront's capacity whose length is a multiple of 4 (every bucket but a ragged
+        // last one): whole 16-byte loads, the lanes past the end read the bucket's first elements and drop them
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const uint32_t e = 256u * c + 4u * lane;
+            const bool inside = e < len;
+            const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + (inside ? e : 0u)));
+            v[c][0] = inside ? q.x : 0.0f; v[c][1] = inside ? q.y : 0.0f;
+            v[c][2] = inside ? q.z : 0.0f; v[c][3] = inside ? q.w : 0.0f;
+        }
     } else {
 #pragma unroll
         for (int c = 0; c < C; ++c)
@@ -1004,6 +1015,16 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
             const floatx4 q =
                 __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + first + 256 * c + 4 * lane));
             v[c][0] = q.x; v[c][1] = q.y; v[c][2] = q.z; v[c][3] = q.w;
+        }
+    } else if (len % 4u == 0u) {
+        // whole 16-byte loads; the lanes past the end read the bucket's first elements and drop them
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const uint32_t e = 256u * c + 4u * lane;
+            const bool inside = e < my_len;
+            const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + (inside ? first + e : 0u)));
+            v[c][0] = inside ? q.x : 0.0f; v[c][1] = inside ? q.y : 0.0f;
+            v[c][2] = inside ? q.z : 0.0f; v[c][3] = inside ? q.w : 0.0f;
         }
     } else {
 #pragma unroll
