@@ -503,6 +503,26 @@ def test_decode_average_small(bits, scheme, d):
             parity.check_average(out.cpu().numpy(), ref, scale, tag=f"avg-b{bits}-d{d}-n{n}-W{W}")
 
 
+@pytest.mark.parametrize("bits,scheme,d", [(1, ogq.BINGRAD_B, 2048), (2, ogq.ORQ, 1024), (3, ogq.ORQ, 4096), (4, ogq.ORQ_PAPER, 512),
+                                           (3, ogq.ORQ_PAPER, 128), (2, ogq.EVEN, 192)])
+def test_decode_average_many_distinct_workers(bits, scheme, d):
+    """More workers than the decoder fetches at once (4 or 8), every one with its own gradient, levels and codes:
+    worker counts that end inside a batch and on a batch boundary, whole spans and a ragged last one."""
+    rng = np.random.default_rng(17 * bits + d)
+    stride = oracle.levels_per_bucket(scheme, bits)
+    n = 5 * 1024 + 2 * d + 65
+    for W in (5, 9, 16, 33):
+        gs = [_rng_bucket(rng, n, "heavy" if w % 3 else "normal") * np.float32(1 + w) for w in range(W)]
+        q = [oracle.quantize(g, d, bits, scheme, 1, seed=90 + w) for w, g in enumerate(gs)]
+        ref = oracle.dequantize_average([w for _, w in q], [l for l, _ in q], n, d, bits, stride)
+        scale = parity.term_scale([l for l, _ in q], [w for _, w in q], n, d, bits, stride)
+        dl = [torch.from_numpy(np.concatenate([l, np.zeros(4, np.float32)])).to(DEV) for l, _ in q]
+        dc = [torch.from_numpy(np.concatenate([w, np.zeros(2, np.uint64)]).view(np.int64)).to(DEV) for _, w in q]
+        out = ogq.ogq_dequantize_average(dc, dl, n, ogq.make_params(d, bits, scheme))
+        torch.cuda.synchronize()
+        parity.check_average(out.cpu().numpy(), ref, scale, tag=f"avg-distinct-b{bits}-s{scheme}-d{d}-W{W}")
+
+
 def test_decode_average_many_identical_workers():
     rng = np.random.default_rng(5)
     n, d, bits = 5000, 512, 2
