@@ -6,6 +6,8 @@
 #ifndef OGQ_ROUNDING_KERNELS_H
 #define OGQ_ROUNDING_KERNELS_H
 
+#include <type_traits>
+
 #include "device_common.h"
 
 namespace ogq {
@@ -360,6 +362,19 @@ __device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t r
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Runs f(c, all) for the chunks c (256 elements each) that hold at least one of the `len` valid elements.  `all` is a
+// std::true_type when every element of the chunk is valid, so that f can drop its per-element bounds tests: at most one
+// chunk of a bucket is cut by its end, and the chunks past it are skipped altogether (wave-uniform branches).
+template <int C, bool FULL, class F>
+__device__ __forceinline__ void for_each_chunk(uint32_t len, F f)
+{
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        if (FULL || 256u * (uint32_t)(c + 1) <= len) f(c, std::true_type{});
+        else if (256u * (uint32_t)c < len) f(c, std::false_type{});
+    }
+}
+
 // Returns x unchanged but hides it from common-subexpression elimination, so that values derived
 // from the register-resident bucket are recomputed in each phase instead of being kept alive.
 __device__ __forceinline__ float recompute_from(float x)
@@ -390,6 +405,10 @@ __device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (
     const size_t word0 = begin / 64;
 #pragma unroll
     for (int c = 0; c < C; ++c) {
+        constexpr bool ALL = FULL;
+        if constexpr (!FULL) {
+            if (256u * (uint32_t)c >= len) continue;  // nothing of the bucket in this chunk: no words to write
+        }
         const uint64_t block = (index_offset + begin + 256u * c + 4u * lane) >> 2;
         uint32_t r[4];
         philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), k0, k1, r);
@@ -413,7 +432,7 @@ __device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (
             const float u = (float)(r[k] >> 8) * 0x1p-24f;
             const float scaled = u * w;
             uint64_t carry = __ballot(scaled < delta);  // rounded up
-            if constexpr (!FULL) carry &= __ballot(256u * c + 4u * lane + k < len);
+            if constexpr (!ALL) carry &= __ballot(256u * c + 4u * lane + k < len);
 #pragma unroll
             for (int p = 0; p < BITS; ++p) {
                 // bit p of the number of levels 1..S-2 not above x
@@ -423,7 +442,7 @@ __device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (
                     const int lo_t = j << p, hi_t = (j + 1) << p;
                     index_bit |= hi_t <= S - 2 ? (not_below[lo_t] & ~not_below[hi_t]) : not_below[lo_t];
                 }
-                if constexpr (!FULL) index_bit &= __ballot(256u * c + 4u * lane + k < len);
+                if constexpr (!ALL) index_bit &= __ballot(256u * c + 4u * lane + k < len);
                 const uint64_t code_bit = index_bit ^ carry;
                 carry &= index_bit;
                 plane[p] |= __builtin_amdgcn_inverse_ballot_w64(code_bit) ? bit_of[k] : 0u;
@@ -799,15 +818,15 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
     // ---- extremes ------------------------------------------------------------------------------
     float lane_min = __uint_as_float(0x7F800000u), lane_max = __uint_as_float(0xFF800000u);
     uint32_t lane_zeros = 0;
-#pragma unroll
-    for (int c = 0; c < C; ++c)
+    for_each_chunk<C, FULL>(len, [&](int c, auto all) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const bool valid = full || (256u * c + 4u * lane + k < len);
+            const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < len);
             lane_min = fminf(lane_min, valid ? v[c][k] : __uint_as_float(0x7F800000u));
             lane_max = fmaxf(lane_max, valid ? v[c][k] : __uint_as_float(0xFF800000u));
             if constexpr (PB) lane_zeros += (valid && v[c][k] == 0.0f) ? 1u : 0u;
         }
+    });
     const float bucket_min = wave_min(lane_min) + 0.0f;  // -0 -> +0
     const float bucket_max = wave_max(lane_max) + 0.0f;
     const uint32_t key_min = float_to_key(bucket_min), key_max = float_to_key(bucket_max);
@@ -823,15 +842,15 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         uint32_t slot[C][4];  // bin | position inside the bin << 16
-#pragma unroll
-        for (int c = 0; c < C; ++c)
+        for_each_chunk<C, FULL>(len, [&](int c, auto all) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const bool valid = full || (256u * c + 4u * lane + k < len);
+                const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < len);
                 const uint32_t bin = value_bin<HALF, SHIFT>(recompute_from(v[c][k]) + 0.0f, t_low);
                 slot[c][k] = 0u;
                 if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
             }
+        });
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
@@ -861,22 +880,26 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         // ---- scatter the values into their bins: the bin starts of a group of elements are all read before the
         //      group's values are written (a read behind a write to the same LDS object would wait for it) ------
         constexpr int GROUP = C < 4 ? C : 4;
-#pragma unroll
-        for (int c0 = 0; c0 < C; c0 += GROUP) {
+        auto scatter_group = [&](int c0, auto all) {
 #pragma unroll
             for (int c = c0; c < c0 + GROUP; ++c)
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const bool valid = full || (256u * c + 4u * lane + k < len);
+                    const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < len);
                     if (valid) slot[c][k] = lds.bin_start[slot[c][k] & 0xFFFFu] + (slot[c][k] >> 16);
                 }
 #pragma unroll
             for (int c = c0; c < c0 + GROUP; ++c)
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const bool valid = full || (256u * c + 4u * lane + k < len);
+                    const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < len);
                     if (valid) lds.grouped[skewed(slot[c][k])] = __float_as_uint(v[c][k]);
                 }
+        };
+#pragma unroll
+        for (int c0 = 0; c0 < C; c0 += GROUP) {
+            if (full || 256u * (uint32_t)(c0 + GROUP) <= len) scatter_group(c0, std::true_type{});
+            else if (256u * (uint32_t)c0 < len) scatter_group(c0, std::false_type{});
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -1046,15 +1069,15 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
     // ---- extremes of the whole bucket ----------------------------------------------------------------
     float lane_min = __uint_as_float(0x7F800000u), lane_max = __uint_as_float(0xFF800000u);
     uint32_t lane_zeros = 0;
-#pragma unroll
-    for (int c = 0; c < C; ++c)
+    for_each_chunk<C, FULL>(my_len, [&](int c, auto all) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+            const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < my_len);
             lane_min = fminf(lane_min, valid ? v[c][k] : __uint_as_float(0x7F800000u));
             lane_max = fmaxf(lane_max, valid ? v[c][k] : __uint_as_float(0xFF800000u));
             if constexpr (PB) lane_zeros += (valid && v[c][k] == 0.0f) ? 1u : 0u;
         }
+    });
     float bucket_min = wave_min(lane_min), bucket_max = wave_max(lane_max);
     uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
     {
@@ -1080,15 +1103,15 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
         for (uint32_t i = tid; i < (uint32_t)B; i += THREADS) lds.bin_start[i] = 0u;
         __syncthreads();
         uint32_t slot[C][4];  // bin | position inside the bin << 16
-#pragma unroll
-        for (int c = 0; c < C; ++c)
+        for_each_chunk<C, FULL>(my_len, [&](int c, auto all) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < my_len);
                 const uint32_t bin = value_bin<HALF, SHIFT>(recompute_from(v[c][k]) + 0.0f, t_low);
                 slot[c][k] = 0u;
                 if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
             }
+        });
         __syncthreads();
 
         // ---- exclusive prefix over the bin counts (wavefront 0; lane l owns bins l*PER .. l*PER+PER-1) ------
@@ -1108,22 +1131,26 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
 
         // ---- scatter the values into their bins (bin starts of a group of elements read before its writes) ------
         constexpr int GROUP = C < 4 ? C : 4;
-#pragma unroll
-        for (int c0 = 0; c0 < C; c0 += GROUP) {
+        auto scatter_group = [&](int c0, auto all) {
 #pragma unroll
             for (int c = c0; c < c0 + GROUP; ++c)
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                    const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < my_len);
                     if (valid) slot[c][k] = lds.bin_start[slot[c][k] & 0xFFFFu] + (slot[c][k] >> 16);
                 }
 #pragma unroll
             for (int c = c0; c < c0 + GROUP; ++c)
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const bool valid = FULL || (256u * c + 4u * lane + k < my_len);
+                    const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < my_len);
                     if (valid) lds.grouped[skewed(slot[c][k])] = __float_as_uint(v[c][k]);
                 }
+        };
+#pragma unroll
+        for (int c0 = 0; c0 < C; c0 += GROUP) {
+            if (FULL || 256u * (uint32_t)(c0 + GROUP) <= my_len) scatter_group(c0, std::true_type{});
+            else if (256u * (uint32_t)c0 < my_len) scatter_group(c0, std::false_type{});
         }
         __syncthreads();
 
