@@ -303,6 +303,22 @@ def test_bucket_size_sweep_of_the_paper_at_resnet50_size():
     assert err[ogq.ORQ_PAPER][-1] > err[ogq.ORQ_PAPER][0] and err[ogq.EVEN][-1] > err[ogq.EVEN][0]
 
 
+@pytest.mark.parametrize("scheme,bits", [(ogq.ORQ, 2), (ogq.ORQ, 3), (ogq.ORQ_PAPER, 2), (ogq.ORQ_PAPER, 4), (ogq.LINEAR, 3),
+                                         (ogq.BINGRAD_PB, 1)])
+@pytest.mark.parametrize("d", [512, 2048, 4096, 16384])
+def test_crowded_bins_of_distinct_values(scheme, bits, d):
+    """Buckets whose values crowd a few bins of the in-bucket grouping without being equal: a shifted normal puts
+    65 .. 256 distinct values (selection on register-held keys) or many hundreds (selection over LDS) into one bin,
+    for the rank picks of every rule."""
+    rng = np.random.default_rng(d + 7 * bits + scheme)
+    n = 6 * d + 200
+    for mean, sigma in ((5.0, 0.5), (-3.0, 0.2), (5.0, 0.02), (0.75, 0.1)):
+        g = rng.normal(mean, sigma, n).astype(np.float32)
+        g[::97] *= np.float32(-1.0)   # a few values on the other side of zero
+        for iters in (0, 2):
+            parity.check_quantize(g, d, bits, scheme, iters, seed=d + 3, tag=f"crowded-s{scheme}b{bits}-d{d}-m{mean}-sd{sigma}-it{iters}")
+
+
 def test_orq_sweeps_and_offsets():
     rng = np.random.default_rng(77)
     g = _rng_bucket(rng, 8 * 1024 + 100, "heavy")
