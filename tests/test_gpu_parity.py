@@ -368,6 +368,44 @@ def test_random_shapes_and_parameters():
                               clip_factor=clip, tag=f"random-{trial}")
 
 
+def test_random_value_distributions():
+    """Distributions the other tests do not draw: log-normal with a dynamic range of 2^30, Cauchy, subnormal values,
+    70 % zeros, sorted input, a handful of distinct values, scaled integers; random bucket sizes up to 32768, schemes,
+    sweeps, clipping and index offsets (under the acceptance rules; an earlier run of 15,000 such cases had levels one
+    fp32 ulp apart in one clipped log-normal bucket and equal everywhere else)."""
+    rng = np.random.default_rng(77)
+
+    def draw(n):
+        k = int(rng.integers(0, 8))
+        if k == 0:
+            return (rng.lognormal(0, 3, n) * rng.choice([-1, 1], n)).astype(np.float32)
+        if k == 1:
+            return rng.choice(rng.normal(0, 1, 17).astype(np.float32), n)
+        if k == 2:
+            return (rng.standard_cauchy(n) * 1e-3).astype(np.float32)
+        if k == 3:
+            return rng.normal(0, 1e-40, n).astype(np.float32)
+        if k == 4:
+            g = rng.normal(0, 1e-3, n).astype(np.float32)
+            g[rng.random(n) < 0.7] = 0
+            return g
+        if k == 5:
+            return rng.normal(rng.uniform(-10, 10), 10.0 ** rng.uniform(-4, 0), n).astype(np.float32)
+        if k == 6:
+            return np.sort(rng.normal(0, 1, n).astype(np.float32))
+        return (rng.integers(-1000, 1000, n) * np.float32(2.0 ** rng.integers(-20, 20))).astype(np.float32)
+
+    schemes = [(ogq.BINGRAD_B, 1), (ogq.ORQ, 1), (ogq.ORQ, 2), (ogq.ORQ, 3), (ogq.BINGRAD_PB, 1), (ogq.ORQ_PAPER, 2),
+               (ogq.ORQ_PAPER, 3), (ogq.ORQ_PAPER, 4), (ogq.SCALED_SIGN, 1), (ogq.EVEN, 3), (ogq.LINEAR, 2), (ogq.LINEAR, 4)]
+    for trial in range(360):
+        scheme, bits = schemes[trial % len(schemes)]
+        d = 64 * int(rng.choice([1, 2, 3, 4, 8, 12, 16, 32, 33, 48, 64, 96, 128, 200, 256, 512]))
+        n = int(rng.integers(1, 4 * d + 100))
+        parity.check_quantize(draw(n), d, bits, scheme, int(rng.integers(0, 4)), seed=int(rng.integers(1 << 62)),
+                              index_offset=64 * int(rng.integers(0, 1 << 30)), clip_factor=float(rng.choice([0.0, 0.0, 2.5, 1.7])),
+                              tag=f"dist-{trial}")
+
+
 def test_non_finite_values_stay_inside_their_bucket():
     """NaN and infinities give unspecified levels and codes for their own bucket only: every call returns, and the
     buckets without them still match the oracle (every kernel family and bucket-size class)."""
