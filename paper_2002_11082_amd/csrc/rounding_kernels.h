@@ -538,10 +538,16 @@ __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k,
 // up to the root and those of the right half only levels from the root on, so wavefront 0 takes the left and
 // wavefront 1 the right half, step by step.  Sweeps, two at a time: wavefront 0 runs sweep s, wavefront 1 sweep
 // s + 1 two levels behind it (level k of a sweep needs level k - 1 of the same sweep and level k + 1 of the sweep
-// before).  Every wavefront of the workgroup must call this; a workgroup barrier ends every step.
+// before).  Where wavefront 0 runs out of greedy solves before wavefront 1 (8 levels), it starts the first sweep in
+// those steps.  Every wavefront of the workgroup must call this; a workgroup barrier ends every step.
 struct TeamGreedy {
     uint16_t entry[2][8];  // k | l << 4 | r << 8 per wavefront and step; 0 = idle
     int steps;
+    // Greedy steps in which wavefront 0 has nothing left to do and can already run the first solves of the first
+    // sweep (levels 1, 2): head_step[h] = the step that takes level h + 1, or -1.  Possible when the greedy value of
+    // level h + 2 is final by then and the solve of wavefront 1 in that step touches none of the levels h .. h + 2.
+    int head_step[2];
+    int head;
 };
 
 template <int S>
@@ -563,6 +569,27 @@ constexpr TeamGreedy team_greedy()
         }
     }
     g.steps = o.count == 0 ? 0 : (next[0] > next[1] ? next[0] : next[1]);
+    g.head_step[0] = g.head_step[1] = -1;
+    g.head = 0;
+    for (int step = 1; step < g.steps && g.head < 2; ++step) {
+        if (g.entry[0][step] != 0) continue;
+        bool later_work = false;  // only trailing idle steps of wavefront 0
+        for (int q = step; q < g.steps; ++q) later_work = later_work || g.entry[0][q] != 0;
+        if (later_work) continue;
+        const int h = g.head, level = h + 1;
+        if (level > S - 2) break;
+        // greedy value of level + 1 final before this step (or it is the top level)
+        bool right_final = level + 1 == S - 1;
+        for (int w = 0; w < 2; ++w)
+            for (int q = 0; q < step; ++q)
+                if (g.entry[w][q] != 0 && (int)(g.entry[w][q] & 15u) == level + 1) right_final = true;
+        const uint32_t other = g.entry[1][step];
+        const int ok = (int)(other & 15u), ol = (int)((other >> 4) & 15u), orr = (int)((other >> 8) & 15u);
+        const bool apart = other == 0 || ((ok < level - 1 || ok > level + 1) && ol != level && orr != level);
+        if (!right_final || !apart) break;
+        g.head_step[h] = step;
+        ++g.head;
+    }
     return g;
 }
 
@@ -579,13 +606,17 @@ __device__ __forceinline__ void orq_team_solve(Lds& lds, PickFn pick, uint32_t w
         if (wave < 2u) {
             const uint32_t e = wave == 0u ? greedy.entry[0][step] : greedy.entry[1][step];
             if (e != 0u) orq_solve_one(lds, pick, e & 15u, (e >> 4) & 15u, (e >> 8) & 15u, len, lane);
+            if (wave == 0u && sweeps > 0u) {  // head start of the first sweep
+                if (greedy.head_step[0] == step) orq_solve_one(lds, pick, 1u, 0u, 2u, len, lane);
+                if (greedy.head_step[1] == step) orq_solve_one(lds, pick, 2u, 1u, 3u, len, lane);
+            }
         }
         __syncthreads();
     }
     for (uint32_t s = 0; s < sweeps; s += 2u) {
         const bool pair = s + 1u < sweeps;
         const uint32_t steps = INTERIOR + (pair ? 2u : 0u);
-        for (uint32_t t = 0; t < steps; ++t) {
+        for (uint32_t t = (s == 0u ? (uint32_t)greedy.head : 0u); t < steps; ++t) {
             if (wave == 0u && t < INTERIOR) orq_solve_one(lds, pick, t + 1u, t, t + 2u, len, lane);
             if (wave == 1u && pair && t >= 2u) orq_solve_one(lds, pick, t - 1u, t - 2u, t, len, lane);
             __syncthreads();
