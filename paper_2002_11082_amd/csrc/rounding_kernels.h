@@ -554,7 +554,7 @@ template <int S>
 constexpr TeamGreedy team_greedy()
 {
     const GreedyOrder o = greedy_order<S>();
-    TeamGreedy g{{{0, 0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0, 0}}, 0};
+    TeamGreedy g{{{0, 0, 0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0, 0, 0}}, 0, {-1, -1}, 0};
     int next[2] = {1, 1};
     int root = 0;
     for (int i = 0; i < o.count; ++i) {
