@@ -1019,6 +1019,68 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(C == 8 ? 
 }
 
 // ----------------------------------------------------------------------------------------------
+// Evenly spaced levels (QSGD-s, TernGrad) for buckets of 64 or 128 elements: one wavefront takes 256 consecutive
+// elements, i.e. NB = 4 or 2 whole buckets (lane l holds elements 4l .. 4l+3, bucket l / G of the wavefront with
+// G = 64 / NB lanes per bucket), instead of leaving three quarters or half of its lanes idle.  The only statistic of
+// the rule, the largest magnitude, is reduced inside each group of G lanes; every lane then holds the levels of its
+// own bucket, which is all the encoder needs.  No clipping here.
+// ----------------------------------------------------------------------------------------------
+template <int S, int BITS, int NB, bool FULL>
+__device__ __forceinline__ void even_small_span(const float* __restrict__ g, uint32_t len, size_t begin, uint32_t first_bucket,
+                                                uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
+                                                uint32_t* __restrict__ codes32)
+{
+    constexpr uint32_t G = 64u / NB;           // lanes per bucket
+    constexpr uint32_t D = 256u / NB;          // elements per bucket
+    const uint32_t lane = threadIdx.x & 63u;
+    float v[1][4];
+    if (FULL || len % 4u == 0u) {
+        const bool inside = FULL || 4u * lane < len;
+        const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + (inside ? 4u * lane : 0u)));
+        v[0][0] = inside ? q.x : 0.0f; v[0][1] = inside ? q.y : 0.0f;
+        v[0][2] = inside ? q.z : 0.0f; v[0][3] = inside ? q.w : 0.0f;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[0][k] = 4u * lane + k < len ? g[4u * lane + k] : 0.0f;
+    }
+    // largest magnitude of the lane's bucket (padding holds 0)
+    uint32_t mag = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) mag = umax32(mag, __float_as_uint(v[0][k]) & 0x7FFFFFFFu);
+    mag = umax32(mag, dpp_u32<kDppXor1>(mag));
+    mag = umax32(mag, dpp_u32<kDppXor2>(mag));
+    mag = umax32(mag, dpp_u32<kDppHalfMirror>(mag));
+    mag = umax32(mag, dpp_u32<kDppMirror>(mag));  // the 16 lanes of a row
+    if constexpr (G == 32u) mag = umax32(mag, lane_xor<16>(mag, lane));
+    float lv[S];
+    const double largest = (double)__uint_as_float(mag);
+#pragma unroll
+    for (int k = 0; k < S; ++k) lv[k] = (float)(largest * (double)(2 * k - (S - 1)) / (double)(S - 1));
+    const uint32_t q = lane / G;  // bucket of this lane inside the wavefront
+    if (lane % G == 0u && (FULL || q * D < len)) {
+#pragma unroll
+        for (int k = 0; k < S; ++k) levels[(size_t)(first_bucket + q) * S + k] = lv[k];
+    }
+    orq_encode<1, S, BITS, FULL>(v, lv, len, begin, seed, index_offset, codes32);
+}
+
+template <int S, int BITS, int NB>
+__global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __restrict__ grad, size_t n, uint64_t seed,
+                                                               uint64_t index_offset, float* __restrict__ levels,
+                                                               uint32_t* __restrict__ codes32)
+{
+    const size_t span = (size_t)blockIdx.x * 4u + (threadIdx.x >> 6);  // 256 elements each
+    const size_t begin = span * 256u;
+    if (begin >= n) return;
+    const size_t rest = n - begin;
+    const uint32_t first_bucket = (uint32_t)(span * NB);
+    if (rest >= 256u)
+        even_small_span<S, BITS, NB, true>(grad + begin, 256u, begin, first_bucket, seed, index_offset, levels, codes32);
+    else
+        even_small_span<S, BITS, NB, false>(grad + begin, (uint32_t)rest, begin, first_bucket, seed, index_offset, levels, codes32);
+}
+
+// ----------------------------------------------------------------------------------------------
 // ORQ and the other random-rounding rules with W = 2, 4 or 8 wavefronts of a workgroup owning one bucket (up
 // to 32768 elements), wavefront w holding bucket elements [256 C w, 256 C (w + 1)) in the register layout of
 // orq_bucket.  All of them build the grouping of the whole bucket in LDS (histogram, bin
@@ -1296,10 +1358,34 @@ void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, fl
                            static_cast<uint32_t*>(codes));
 }
 
+template <int S, int BITS>
+void launch_even_small(const float* g, size_t n, const ogq_params_t* p, float* lv, void* codes, hipStream_t st)
+{
+    const size_t spans = (n + 255u) / 256u;
+    const dim3 grid((uint32_t)((spans + 3u) / 4u)), block(4 * kWave);
+    if (p->bucket_size == 64u)
+        hipLaunchKernelGGL((even_small_kernel<S, BITS, 4>), grid, block, 0, st, g, n, p->seed, p->index_offset, lv,
+                           static_cast<uint32_t*>(codes));
+    else
+        hipLaunchKernelGGL((even_small_kernel<S, BITS, 2>), grid, block, 0, st, g, n, p->seed, p->index_offset, lv,
+                           static_cast<uint32_t*>(codes));
+}
+
 template <int C, int RULE>
 void launch_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                          hipStream_t st)
 {
+    if constexpr (C == 1 && RULE == kEven) {
+        // buckets of 64 and 128 elements without clipping: several buckets per wavefront
+        if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+            switch (p->bits) {
+                case 2: launch_even_small<3, 2>(g, n, p, lv, codes, st); break;
+                case 3: launch_even_small<5, 3>(g, n, p, lv, codes, st); break;
+                default: launch_even_small<9, 4>(g, n, p, lv, codes, st); break;
+            }
+            return;
+        }
+    }
     switch (p->bits) {  // 2^(bits-1) + 1 levels
         case 2: launch_orq<C, 3, 2, RULE>(g, n, p, nb, lv, codes, st); break;
         case 3: launch_orq<C, 5, 3, RULE>(g, n, p, nb, lv, codes, st); break;

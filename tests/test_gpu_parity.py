@@ -182,13 +182,15 @@ def test_scaled_sign_several_buckets_per_wavefront_above_four_million_elements(d
 
 @pytest.mark.parametrize("scheme", [ogq.EVEN, ogq.LINEAR])
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("d", [64, 320, 512, 2048, 4096])
+@pytest.mark.parametrize("d", [64, 128, 320, 512, 2048, 4096])
 def test_even_and_linear_levels_small(scheme, bits, d):
     rng = np.random.default_rng(17 * bits + d + scheme)
     for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
-        for n in (1, 2, 3, 65, d - 1, d, 3 * d + 129):
+        # (with 64 and 128 elements per bucket a wavefront holds several buckets: whole and cut-off groups of them)
+        for n in (1, 2, 3, 65, d - 1, d, 3 * d + 129, 1024 + 5 * d, 2048 + 3 * d + 4, 4096 + d + 62):
             g = _rng_bucket(rng, n, kind)
-            parity.check_quantize(g, d, bits, scheme, 0, seed=7 + n, tag=f"rule{scheme}-b{bits}-{kind}-d{d}-n{n}")
+            parity.check_quantize(g, d, bits, scheme, 0, seed=7 + n, index_offset=64 * (n % 7),
+                                  tag=f"rule{scheme}-b{bits}-{kind}-d{d}-n{n}")
         g = _rng_bucket(rng, 4 * d + 3, kind)
         parity.check_quantize(g, d, bits, scheme, 0, seed=3, clip_factor=2.5, index_offset=64 * 12345,
                               tag=f"rule{scheme}-b{bits}-clip-{kind}-d{d}")
