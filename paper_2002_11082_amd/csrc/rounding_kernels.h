@@ -222,7 +222,9 @@ struct Picked {
 
 // The element of 1-based rank `rank`, which lies in the bin that holds positions [first, first + count).  BLOCK =
 // positions per entry of the fp64 block prefix (at most 64).
-template <int BLOCK, class Lds>
+// SUMS = false: only the element is wanted (rules whose solves never read the counts and sums of a picked level: a
+// single interior level, Linear-s); the block prefix is then neither needed nor read.
+template <int BLOCK, bool SUMS = true, class Lds>
 __device__ __forceinline__ Picked pick_in_span(const Lds& lds, uint32_t first, uint32_t count, uint32_t rank, uint32_t lane)
 {
     static_assert(BLOCK <= 64, "the head of a block is read one position per lane");
@@ -231,8 +233,12 @@ __device__ __forceinline__ Picked pick_in_span(const Lds& lds, uint32_t first, u
     // sum of everything before the bin = prefix of its block + the block's positions before `first`
     const uint32_t block = first / BLOCK;
     const uint32_t block_first = block * BLOCK;
-    const double before_block = uniform_f64(lds.block_prefix[block]);
-    const float head = lane < first - block_first ? __uint_as_float(lds.grouped[skewed(block_first + lane)]) : 0.0f;
+    double before_block = 0.0;
+    float head = 0.0f;
+    if constexpr (SUMS) {
+        before_block = uniform_f64(lds.block_prefix[block]);
+        head = lane < first - block_first ? __uint_as_float(lds.grouped[skewed(block_first + lane)]) : 0.0f;
+    }
 
     uint32_t key, c_lt, c_le;
     double s_lt;
@@ -241,11 +247,16 @@ __device__ __forceinline__ Picked pick_in_span(const Lds& lds, uint32_t first, u
             lane < count ? stored_key(lds.grouped[skewed(first + lane)]) : 0xFFFFFFFFu;
         const uint32_t sorted = wave_sort_u32(mine, lane, count);
         key = __builtin_amdgcn_readlane(sorted, r_in - 1u);
-        const bool lt = sorted < key;
-        const bool le = (sorted <= key) && (lane < count);
-        c_lt = (uint32_t)__popcll(__ballot(lt));
-        c_le = (uint32_t)__popcll(__ballot(le));
-        s_lt = wave_sum((double)head + (lt ? (double)key_to_float(sorted) : 0.0));
+        if constexpr (SUMS) {
+            const bool lt = sorted < key;
+            const bool le = (sorted <= key) && (lane < count);
+            c_lt = (uint32_t)__popcll(__ballot(lt));
+            c_le = (uint32_t)__popcll(__ballot(le));
+            s_lt = wave_sum((double)head + (lt ? (double)key_to_float(sorted) : 0.0));
+        } else {
+            c_lt = c_le = 0u;
+            s_lt = 0.0;
+        }
     } else {
         // A crowded bin (many equal or nearly equal values): bisection on the key, over the bits in which the bin's
         // smallest and largest key differ (none when all its values are equal).  Up to 256 keys stay in registers.
@@ -299,6 +310,7 @@ __device__ __forceinline__ Picked pick_in_span(const Lds& lds, uint32_t first, u
         c_lt = 0;
         c_le = 0;
         double part = (double)head;
+        if constexpr (SUMS)
         for (uint32_t base = 0; base < count; base += 64u) {
             const uint32_t i = base + lane;
             const float x = i < count ? __uint_as_float(lds.grouped[skewed(first + i)]) + 0.0f : 0.0f;
@@ -308,7 +320,7 @@ __device__ __forceinline__ Picked pick_in_span(const Lds& lds, uint32_t first, u
             c_le += (uint32_t)__popcll(__ballot(k <= key && i < count));
             part += lt ? (double)x : 0.0;
         }
-        s_lt = wave_sum(part);
+        s_lt = SUMS ? wave_sum(part) : 0.0;
     }
     Picked p;
     p.key = key;
@@ -320,16 +332,16 @@ __device__ __forceinline__ Picked pick_in_span(const Lds& lds, uint32_t first, u
 }
 
 // The same for bin `bin`.
-template <int BLOCK, class Lds>
+template <int BLOCK, bool SUMS = true, class Lds>
 __device__ __forceinline__ Picked pick_in_bin(const Lds& lds, uint32_t bin, uint32_t rank, uint32_t lane)
 {
     const uint32_t first = uniform_u32(lds.bin_start[bin]);
     const uint32_t count = uniform_u32(lds.bin_start[bin + 1]) - first;
-    return pick_in_span<BLOCK>(lds, first, count, rank, lane);
+    return pick_in_span<BLOCK, SUMS>(lds, first, count, rank, lane);
 }
 
 // rank is 1-based, 1 <= rank <= bucket length.  my_start[t] = bin_start[lane * PER + t], kept in registers.
-template <int D, int B, int S>
+template <int D, int B, int S, bool SUMS = true>
 __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B, S>& lds, const uint32_t (&my_start)[B / 64],
                                             uint32_t rank, uint32_t lane)
 {
@@ -339,12 +351,12 @@ __device__ __forceinline__ Picked pick_rank(const OrqLds<D, B, S>& lds, const ui
 #pragma unroll
     for (int t = 0; t < PER; ++t) starts_below += (uint32_t)__popcll(__ballot(my_start[t] < rank));
     const uint32_t bin = starts_below - 1u;  // bin_start[0] = 0 < rank: at least one
-    return pick_in_bin<D / 64>(lds, bin, rank, lane);
+    return pick_in_bin<D / 64, SUMS>(lds, bin, rank, lane);
 }
 
 // The same with the bin found by two looks into LDS (every (B/64)-th bin start, then the B/64 bins in between):
 // no registers are tied up by the bin starts.
-template <class Lds>
+template <bool SUMS = true, class Lds>
 __device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t rank, uint32_t lane)
 {
     constexpr uint32_t PER = Lds::B / 64;
@@ -358,7 +370,7 @@ __device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t r
     const uint32_t next = within + 1u < PER ? __builtin_amdgcn_readlane(fine, (within + 1u) & 63u)
                           : segment < 63u   ? __builtin_amdgcn_readlane(coarse, (segment + 1u) & 63u)
                                             : uniform_u32(lds.bin_start[Lds::B]);
-    return pick_in_span<Lds::BLOCK>(lds, first, next - first, rank, lane);
+    return pick_in_span<Lds::BLOCK, SUMS>(lds, first, next - first, rank, lane);
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -937,17 +949,33 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         __builtin_amdgcn_wave_barrier();
 
         // ---- fp64 prefix of the grouped values at block granularity (lane l sums block l) ------------
+        // Only the rules whose solves read the counts and sums of picked levels need it: with a single interior
+        // level the one solve reads the bucket's total alone, and Linear-s reads nothing.
+        constexpr bool SUMS = (RULE == kOptimal && S > 3) || PB;
         {
-            constexpr uint32_t BLOCK = D / 64;
-            double part = 0.0;
+            double incl = 0.0;
+            if constexpr (SUMS) {
+                constexpr uint32_t BLOCK = D / 64;
+                double part = 0.0;
 #pragma unroll
-            for (uint32_t i = 0; i < BLOCK; ++i) {
-                const uint32_t position = lane * BLOCK + i;
-                const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
-                part += (double)x;
+                for (uint32_t i = 0; i < BLOCK; ++i) {
+                    const uint32_t position = lane * BLOCK + i;
+                    const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
+                    part += (double)x;
+                }
+                incl = wave_inclusive_scan_f64(part);
+                lds.block_prefix[lane] = incl - part;
+            } else if constexpr (RULE == kOptimal) {
+                double part = 0.0;
+                for_each_chunk<C, FULL>(len, [&](int c, auto all) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < len);
+                        part += valid ? (double)v[c][k] : 0.0;
+                    }
+                });
+                incl = wave_sum(part);  // the same in every lane
             }
-            const double incl = wave_inclusive_scan_f64(part);
-            lds.block_prefix[lane] = incl - part;
             if (lane == 63u) {
                 // the top level is only ever the right end of a solve
                 lds.lvl_count_le[S - 1] = len;
@@ -972,7 +1000,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
 
         const uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
         pb_level = orq_solve_levels<S, RULE>(
-            lds, [&](uint32_t rank) { return pick_rank<D, B, S>(lds, my_start, rank, lane); },
+            lds, [&](uint32_t rank) { return pick_rank<D, B, S, SUMS>(lds, my_start, rank, lane); },
             [&](uint32_t bin) { return __uint_as_float((t_low + (bin - (uint32_t)HALF)) << SHIFT); }, len, zeros, sweeps, lane);
     }
 
@@ -1249,23 +1277,40 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
         __syncthreads();
 
         // ---- fp64 prefix of the grouped values per block of 4C positions (thread t sums block t) ----------
+        // Skipped, but for the bucket's total, by the rules whose solves read no picked level's counts or sums.
+        constexpr bool SUMS = (RULE == kOptimal && S > 3) || PB;
         {
-            constexpr uint32_t BLOCK = OrqTeamLds<W, C>::BLOCK;
-            double part = 0.0;
-            for (uint32_t i = 0; i < BLOCK; ++i) {
-                const uint32_t position = tid * BLOCK + i;
-                const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
-                part += (double)x;
-            }
-            const double incl = wave_inclusive_scan_f64(part);
-            const TeamSlot* s = team.exchange(readlane_f64(incl, 63), 0u, 0u);
-            double before = 0.0, total = 0.0;
+            double total = 0.0;
+            if constexpr (SUMS) {
+                constexpr uint32_t BLOCK = OrqTeamLds<W, C>::BLOCK;
+                double part = 0.0;
+                for (uint32_t i = 0; i < BLOCK; ++i) {
+                    const uint32_t position = tid * BLOCK + i;
+                    const float x = position < len ? __uint_as_float(lds.grouped[skewed(position)]) : 0.0f;
+                    part += (double)x;
+                }
+                const double incl = wave_inclusive_scan_f64(part);
+                const TeamSlot* s = team.exchange(readlane_f64(incl, 63), 0u, 0u);
+                double before = 0.0;
 #pragma unroll
-            for (int w = 0; w < W; ++w) {
-                if ((uint32_t)w < wave) before += s[w].sum;
-                total += s[w].sum;
+                for (int w = 0; w < W; ++w) {
+                    if ((uint32_t)w < wave) before += s[w].sum;
+                    total += s[w].sum;
+                }
+                lds.block_prefix[tid] = before + (incl - part);
+            } else if constexpr (RULE == kOptimal) {
+                double part = 0.0;
+                for_each_chunk<C, FULL>(my_len, [&](int c, auto all) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < my_len);
+                        part += valid ? (double)v[c][k] : 0.0;
+                    }
+                });
+                const TeamSlot* s = team.exchange(wave_sum(part), 0u, 0u);
+#pragma unroll
+                for (int w = 0; w < W; ++w) total += s[w].sum;
             }
-            lds.block_prefix[tid] = before + (incl - part);
             if (tid == 0u) {
                 // the bottom level is only ever the left end of a solve, the top level the right end
                 lds.lvl_count_lt[0] = 0u;
@@ -1286,13 +1331,13 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
 
         if constexpr (RULE == kOptimal && S > 2) {
             // ---- the level solves, spread over the first two wavefronts ------------------------------------------
-            orq_team_solve<S>(lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); }, wave, len, sweeps,
+            orq_team_solve<S>(lds, [&](uint32_t rank) { return pick_rank_by_lookup<SUMS>(lds, rank, lane); }, wave, len, sweeps,
                               lane);
         } else {
             // ---- the other rules' solves are serial: wavefront 0 ---------------------------------------------------
             if (wave == 0u) {
                 const float pb_level = orq_solve_levels<S, RULE>(
-                    lds, [&](uint32_t rank) { return pick_rank_by_lookup(lds, rank, lane); },
+                    lds, [&](uint32_t rank) { return pick_rank_by_lookup<SUMS>(lds, rank, lane); },
                     [&](uint32_t bin) { return __uint_as_float((t_low + (bin - (uint32_t)HALF)) << SHIFT); }, len, zeros, sweeps,
                     lane);
                 if (PB && lane == 0u) {
