@@ -1109,6 +1109,195 @@ __global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __re
 }
 
 // ----------------------------------------------------------------------------------------------
+// ORQ with three levels and Linear-s for buckets of 64 or 128 elements, NB = 4 or 2 whole buckets per wavefront in
+// the layout of even_small_span.  A bucket this small is not grouped into bins: its 4 G keys (G = 64 / NB lanes,
+// 4 registers each) are sorted in registers by a bitonic network whose every compare-exchange is ascending -- the
+// first step of a merge pairs element e with e ^ (run length - 1), i.e. reverses the second run -- so that no step
+// needs a direction.  Element e = 4 * (lane inside the bucket) + register.  The levels are then order statistics
+// fetched from the sorted registers: the extremes, and either the element of the rank that the optimal condition
+// asks for (with three levels there is one solve, between the extremes, and it reads the bucket's total alone;
+// sweeps repeat it unchanged) or Linear-s's ranks.  No clipping here.
+// ----------------------------------------------------------------------------------------------
+constexpr int kDppQuadReverse = 0x1B;  // quad_perm [3,2,1,0]: partner lane ^ 3
+
+// Value held by lane (lane ^ (2 M - 1)): every group of 2 M lanes in reverse order.
+template <int M>
+__device__ __forceinline__ uint32_t lane_reverse(uint32_t x, uint32_t lane)
+{
+    if constexpr (M == 1) {
+        return dpp_u32<kDppXor1>(x);
+    } else if constexpr (M == 2) {
+        return dpp_u32<kDppQuadReverse>(x);
+    } else if constexpr (M == 4) {
+        return dpp_u32<kDppHalfMirror>(x);
+    } else if constexpr (M == 8) {
+        return dpp_u32<kDppMirror>(x);
+    } else {
+        static_assert(M == 16, "groups of at most 32 lanes");
+        return lane_xor<16>(dpp_u32<kDppMirror>(x), lane);
+    }
+}
+
+__device__ __forceinline__ void sort_pair(uint32_t& a, uint32_t& b)
+{
+    const uint32_t mn = umin32(a, b), mx = umax32(a, b);
+    a = mn;
+    b = mx;
+}
+
+// The steps of a merge that pair lanes J apart (J = M / 2 ... 1), register by register.
+template <int J>
+__device__ __forceinline__ void row_sort_across(uint32_t (&x)[4], uint32_t lane)
+{
+    if constexpr (J >= 1) {
+        const bool lower = (lane & (uint32_t)J) == 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t y = lane_xor<J>(x[r], lane);
+            x[r] = lower ? umin32(x[r], y) : umax32(x[r], y);
+        }
+        row_sort_across<J / 2>(x, lane);
+    }
+}
+
+// Merges the sorted runs of 4 M elements (M lanes) pairwise into sorted runs of 8 M, and so on up to 4 G.
+template <int M, int G>
+__device__ __forceinline__ void row_sort_merge(uint32_t (&x)[4], uint32_t lane)
+{
+    if constexpr (2 * M <= G) {
+        const bool lower = (lane & (uint32_t)M) == 0;
+        uint32_t y[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) y[r] = lane_reverse<M>(x[3 - r], lane);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = lower ? umin32(x[r], y[r]) : umax32(x[r], y[r]);
+        row_sort_across<M / 2>(x, lane);
+        sort_pair(x[0], x[2]);
+        sort_pair(x[1], x[3]);
+        sort_pair(x[0], x[1]);
+        sort_pair(x[2], x[3]);
+        row_sort_merge<2 * M, G>(x, lane);
+    }
+}
+
+// Ascending sort of the 4 G keys of every group of G lanes (G = 16 or 32).
+template <int G>
+__device__ __forceinline__ void row_sort(uint32_t (&x)[4], uint32_t lane)
+{
+    sort_pair(x[0], x[1]);  // runs of 2
+    sort_pair(x[2], x[3]);
+    sort_pair(x[0], x[3]);  // runs of 4
+    sort_pair(x[1], x[2]);
+    sort_pair(x[0], x[1]);
+    sort_pair(x[2], x[3]);
+    row_sort_merge<1, G>(x, lane);
+}
+
+// Element `index` (0-based, the same in all lanes of the group) of the sorted group whose first lane is `first_lane`.
+__device__ __forceinline__ uint32_t row_fetch(const uint32_t (&x)[4], uint32_t index, uint32_t first_lane)
+{
+    const uint32_t lo = (index & 1u) ? x[1] : x[0];
+    const uint32_t hi = (index & 1u) ? x[3] : x[2];
+    const uint32_t mine = (index & 2u) ? hi : lo;
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)((first_lane + (index >> 2)) << 2), (int)mine);
+}
+
+// Sum over the group of G lanes, in every lane of the group.
+template <int G>
+__device__ __forceinline__ double row_sum_f64(double x, uint32_t lane)
+{
+    x += dpp_f64<kDppXor1>(x);
+    x += dpp_f64<kDppXor2>(x);
+    x += dpp_f64<kDppHalfMirror>(x);
+    x += dpp_f64<kDppMirror>(x);
+    if constexpr (G == 32) {
+        const uint64_t u = (uint64_t)__double_as_longlong(x);
+        const uint32_t lo = lane_xor<16>((uint32_t)u, lane), hi = lane_xor<16>((uint32_t)(u >> 32), lane);
+        x += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+    }
+    return x;
+}
+
+template <int S, int BITS, int NB, bool FULL, int RULE>
+__device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, uint32_t len, size_t begin, uint32_t first_bucket,
+                                                  uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
+                                                  uint32_t* __restrict__ codes32)
+{
+    static_assert(RULE == kLinear || (RULE == kOptimal && S == 3), "one solve between the extremes, or none");
+    constexpr uint32_t G = 64u / NB;  // lanes per bucket
+    constexpr uint32_t D = 256u / NB;  // elements per bucket
+    const uint32_t lane = threadIdx.x & 63u;
+    float v[1][4];
+    if (FULL || len % 4u == 0u) {
+        const bool inside = FULL || 4u * lane < len;
+        const floatx4 q = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + (inside ? 4u * lane : 0u)));
+        v[0][0] = inside ? q.x : 0.0f; v[0][1] = inside ? q.y : 0.0f;
+        v[0][2] = inside ? q.z : 0.0f; v[0][3] = inside ? q.w : 0.0f;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[0][k] = 4u * lane + k < len ? g[4u * lane + k] : 0.0f;
+    }
+    const uint32_t q = lane / G;  // bucket of this lane inside the wavefront
+    uint32_t count = D;           // elements of that bucket (the gradient may end inside or before it)
+    if constexpr (!FULL) count = q * D < len ? (len - q * D < D ? len - q * D : D) : 0u;
+
+    uint32_t x[4];
+    double part = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const bool valid = FULL || 4u * lane + k < len;
+        const float value = v[0][k] + 0.0f;  // -0 -> +0
+        x[k] = valid ? float_to_key(value) : 0xFFFFFFFFu;  // padding sorts behind every value
+        if constexpr (RULE == kOptimal) part += valid ? (double)value : 0.0;
+    }
+    row_sort<(int)G>(x, lane);
+
+    const uint32_t first_lane = lane & ~(G - 1u);
+    const uint32_t last = count > 0u ? count - 1u : 0u;
+    float lv[S];
+    lv[0] = key_to_float(row_fetch(x, 0u, first_lane));
+    lv[S - 1] = key_to_float(row_fetch(x, last, first_lane));
+    if constexpr (RULE == kLinear) {
+#pragma unroll
+        for (int k = 1; k + 1 < S; ++k) lv[k] = key_to_float(row_fetch(x, ((uint32_t)k * last) / (uint32_t)(S - 1), first_lane));
+    } else {
+        // S = sum (v - L) over the bucket, T = S / (R - L), level = element of rank #{v <= R} - floor(T)
+        const double total = row_sum_f64<(int)G>(part, lane);
+        const float L = lv[0], R = lv[2];
+        const double T = (total - (double)L * (double)count) / ((double)R - (double)L);  // not used when L == R
+        double m = floor(T);
+        if (!(m >= 0.0)) m = 0.0;
+        if (m > (double)count) m = (double)count;
+        uint32_t rank = m >= (double)count ? 1u : count - (uint32_t)m;
+        rank = rank < 1u ? 1u : rank;
+        const float picked = key_to_float(row_fetch(x, rank - 1u, first_lane));
+        lv[1] = (L < R && !(picked < L)) ? picked : L;
+    }
+    if (lane % G == 0u && (FULL || q * D < len)) {
+#pragma unroll
+        for (int k = 0; k < S; ++k) levels[(size_t)(first_bucket + q) * S + k] = lv[k];
+    }
+    orq_encode<1, S, BITS, FULL>(v, lv, len, begin, seed, index_offset, codes32);
+}
+
+template <int S, int BITS, int NB, int RULE>
+__global__ __launch_bounds__(4 * kWave) void sorted_small_kernel(const float* __restrict__ grad, size_t n, uint64_t seed,
+                                                                 uint64_t index_offset, float* __restrict__ levels,
+                                                                 uint32_t* __restrict__ codes32)
+{
+    const size_t span = (size_t)blockIdx.x * 4u + (threadIdx.x >> 6);  // 256 elements each
+    const size_t begin = span * 256u;
+    if (begin >= n) return;
+    const size_t rest = n - begin;
+    const uint32_t first_bucket = (uint32_t)(span * NB);
+    if (rest >= 256u)
+        sorted_small_span<S, BITS, NB, true, RULE>(grad + begin, 256u, begin, first_bucket, seed, index_offset, levels, codes32);
+    else
+        sorted_small_span<S, BITS, NB, false, RULE>(grad + begin, (uint32_t)rest, begin, first_bucket, seed, index_offset, levels,
+                                                    codes32);
+}
+
+// ----------------------------------------------------------------------------------------------
 // ORQ and the other random-rounding rules with W = 2, 4 or 8 wavefronts of a workgroup owning one bucket (up
 // to 32768 elements), wavefront w holding bucket elements [256 C w, 256 C (w + 1)) in the register layout of
 // orq_bucket.  All of them build the grouping of the whole bucket in LDS (histogram, bin
@@ -1416,10 +1605,37 @@ void launch_even_small(const float* g, size_t n, const ogq_params_t* p, float* l
                            static_cast<uint32_t*>(codes));
 }
 
+template <int S, int BITS, int RULE>
+void launch_sorted_small(const float* g, size_t n, const ogq_params_t* p, float* lv, void* codes, hipStream_t st)
+{
+    const size_t spans = (n + 255u) / 256u;
+    const dim3 grid((uint32_t)((spans + 3u) / 4u)), block(4 * kWave);
+    if (p->bucket_size == 64u)
+        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 4, RULE>), grid, block, 0, st, g, n, p->seed, p->index_offset, lv,
+                           static_cast<uint32_t*>(codes));
+    else
+        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 2, RULE>), grid, block, 0, st, g, n, p->seed, p->index_offset, lv,
+                           static_cast<uint32_t*>(codes));
+}
+
 template <int C, int RULE>
 void launch_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes,
                          hipStream_t st)
 {
+    if constexpr (C == 1 && (RULE == kOptimal || RULE == kLinear)) {
+        // buckets of 64 and 128 elements without clipping, sorted in registers, several per wavefront
+        if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+            if (p->bits == 2) {
+                launch_sorted_small<3, 2, RULE>(g, n, p, lv, codes, st);
+                return;
+            }
+            if constexpr (RULE == kLinear) {
+                if (p->bits == 3) launch_sorted_small<5, 3, RULE>(g, n, p, lv, codes, st);
+                else launch_sorted_small<9, 4, RULE>(g, n, p, lv, codes, st);
+                return;
+            }
+        }
+    }
     if constexpr (C == 1 && RULE == kEven) {
         // buckets of 64 and 128 elements without clipping: several buckets per wavefront
         if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {

@@ -126,15 +126,17 @@ def test_bingrad_pb_resnet50_size_sampled():
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("d", [64, 512, 2048, 4096])
+@pytest.mark.parametrize("d", [64, 128, 512, 2048, 4096])
 def test_orq_paper_level_counts_small(bits, d):
     # s = 3, 5, 9 levels; zero sweeps is Algorithm 1 as printed
     rng = np.random.default_rng(7 * bits + d)
     for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
-        for n in (1, 2, 65, d - 1, d, 3 * d + 129):
+        # (with three levels and 64 or 128 elements per bucket a wavefront sorts several buckets in its registers:
+        # whole and cut-off groups of them)
+        for n in (1, 2, 3, 65, d - 1, d, d + 1, 3 * d + 129, 1024 + 5 * d, 2048 + 3 * d + 4, 4096 + d + 62):
             g = _rng_bucket(rng, n, kind)
             for sweeps in (0, 1):
-                parity.check_quantize(g, d, bits, ogq.ORQ_PAPER, sweeps, seed=99 + n,
+                parity.check_quantize(g, d, bits, ogq.ORQ_PAPER, sweeps, seed=99 + n, index_offset=64 * (n % 5),
                                       tag=f"orqpaper{bits}-{kind}-d{d}-n{n}-sw{sweeps}")
 
 
