@@ -1218,12 +1218,69 @@ __device__ __forceinline__ double row_sum_f64(double x, uint32_t lane)
     return x;
 }
 
+// Inclusive scan over the lanes of every group of G lanes (G = 16 or 32).
+template <int G>
+__device__ __forceinline__ double row_inclusive_scan_f64(double x)
+{
+    x += dpp_or_zero_f64<kDppRowShr1, 0xF>(x);
+    x += dpp_or_zero_f64<kDppRowShr2, 0xF>(x);
+    x += dpp_or_zero_f64<kDppRowShr4, 0xF>(x);
+    x += dpp_or_zero_f64<kDppRowShr8, 0xF>(x);
+    if constexpr (G == 32) x += dpp_or_zero_f64<kDppRowBcast15, 0xA>(x);
+    return x;
+}
+
+__device__ __forceinline__ double lane_fetch_f64(double x, uint32_t from_lane)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(from_lane << 2), (int)(uint32_t)u);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(from_lane << 2), (int)(uint32_t)(u >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// row_fetch for the fp64 sums that sit beside the sorted keys.
+__device__ __forceinline__ double row_fetch_f64(const double (&x)[4], uint32_t index, uint32_t first_lane)
+{
+    const double lo = (index & 1u) ? x[1] : x[0];
+    const double hi = (index & 1u) ? x[3] : x[2];
+    return lane_fetch_f64((index & 2u) ? hi : lo, first_lane + (index >> 2));
+}
+
+// Per level, in the registers of every lane of the bucket's group: what OrqLds keeps per level.
+template <int S>
+struct RowLevels {
+    float value[S];
+    uint32_t count_lt[S], count_le[S], rank[S];
+    double sum_lt[S], sum_le[S];
+};
+
+template <int S, int STEP, class Solve>
+__device__ __forceinline__ void for_greedy_steps(Solve&& solve)
+{
+    constexpr GreedyOrder order = greedy_order<S>();
+    if constexpr (STEP < order.count) {
+        constexpr uint32_t e = STEP < 5 ? (uint32_t)(order.packed[0] >> (12 * STEP)) : (uint32_t)(order.packed[1] >> (12 * (STEP - 5)));
+        solve(std::integral_constant<int, (int)(e & 15u)>{}, std::integral_constant<int, (int)((e >> 4) & 15u)>{},
+              std::integral_constant<int, (int)((e >> 8) & 15u)>{});
+        for_greedy_steps<S, STEP + 1>(solve);
+    }
+}
+
+template <int S, int K, class Solve>
+__device__ __forceinline__ void for_sweep_levels(Solve&& solve)
+{
+    if constexpr (K + 1 < S) {
+        solve(std::integral_constant<int, K>{}, std::integral_constant<int, K - 1>{}, std::integral_constant<int, K + 1>{});
+        for_sweep_levels<S, K + 1>(solve);
+    }
+}
+
 template <int S, int BITS, int NB, bool FULL, int RULE>
 __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, uint32_t len, size_t begin, uint32_t first_bucket,
-                                                  uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
-                                                  uint32_t* __restrict__ codes32)
+                                                  uint32_t sweeps, uint64_t seed, uint64_t index_offset,
+                                                  float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
-    static_assert(RULE == kLinear || (RULE == kOptimal && S == 3), "one solve between the extremes, or none");
+    static_assert(RULE == kLinear || (RULE == kOptimal && S >= 3), "rules that read order statistics");
     constexpr uint32_t G = 64u / NB;  // lanes per bucket
     constexpr uint32_t D = 256u / NB;  // elements per bucket
     const uint32_t lane = threadIdx.x & 63u;
@@ -1248,7 +1305,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
         const bool valid = FULL || 4u * lane + k < len;
         const float value = v[0][k] + 0.0f;  // -0 -> +0
         x[k] = valid ? float_to_key(value) : 0xFFFFFFFFu;  // padding sorts behind every value
-        if constexpr (RULE == kOptimal) part += valid ? (double)value : 0.0;
+        if constexpr (RULE == kOptimal && S == 3) part += valid ? (double)value : 0.0;
     }
     row_sort<(int)G>(x, lane);
 
@@ -1260,6 +1317,88 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
     if constexpr (RULE == kLinear) {
 #pragma unroll
         for (int k = 1; k + 1 < S; ++k) lv[k] = key_to_float(row_fetch(x, ((uint32_t)k * last) / (uint32_t)(S - 1), first_lane));
+    } else if constexpr (S > 3) {
+        // The solves of orq_solve_levels, every lane keeping the records of its own bucket.  What a solve needs
+        // around a picked element comes from the sorted registers: the counts of smaller and of not larger keys
+        // (summed over the group), and the sum of the smaller ones, an entry of the exclusive fp64 prefix.
+        const uint32_t l4 = 4u * (lane & (G - 1u));
+        double before[4];  // sum of the sorted elements in front of element 4 l + r
+        double total;
+        {
+            double run = 0.0, mine[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                mine[r] = run;
+                run += l4 + r < count ? (double)key_to_float(x[r]) : 0.0;
+            }
+            const double incl = row_inclusive_scan_f64<(int)G>(run);
+            const double lanes_before = incl - run;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) before[r] = lanes_before + mine[r];
+            total = lane_fetch_f64(incl, first_lane + G - 1u);
+        }
+        RowLevels<S> st;
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+            st.value[k] = k == S - 1 ? lv[S - 1] : lv[0];
+            st.count_lt[k] = k == S - 1 ? count : 0u;
+            st.count_le[k] = k == S - 1 ? count : 0u;
+            st.sum_lt[k] = k == S - 1 ? total : 0.0;
+            st.sum_le[k] = k == S - 1 ? total : 0.0;
+            st.rank[k] = 0u;
+        }
+        const uint32_t count_or_one = count > 0u ? count : 1u;
+        auto solve = [&](auto kc, auto lc, auto rc) {
+            constexpr int k = decltype(kc)::value, l = decltype(lc)::value, r = decltype(rc)::value;
+            const float L = st.value[l], R = st.value[r];
+            const uint32_t cnt_lt_L = st.count_lt[l], cnt_le_R = st.count_le[r];
+            const double sum_lt_L = st.sum_lt[l], sum_le_R = st.sum_le[r];
+            const bool ordered = L < R;
+            // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
+            const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
+            const double T = Ssum / ((double)R - (double)L);  // not used when L == R
+            double m = floor(T);
+            if (!(m >= 0.0)) m = 0.0;
+            const bool whole = m >= (double)cnt_le_R;
+            uint32_t rank = whole ? 1u : cnt_le_R - (uint32_t)(whole ? 0.0 : m);
+            rank = rank < 1u ? 1u : (rank > count_or_one ? count_or_one : rank);
+            const bool same = ordered && rank == st.rank[k];  // same element as last time
+            if (__ballot(!same) == 0) return;
+            const uint32_t key = row_fetch(x, rank - 1u, first_lane);
+            const float picked = key_to_float(key);
+            uint32_t below = 0, not_above = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                below += x[i] < key ? 1u : 0u;
+                not_above += x[i] <= key ? 1u : 0u;
+            }
+            uint32_t both = below | (not_above << 16);
+            both += dpp_u32<kDppXor1>(both);
+            both += dpp_u32<kDppXor2>(both);
+            both += dpp_u32<kDppHalfMirror>(both);
+            both += dpp_u32<kDppMirror>(both);
+            if constexpr (G == 32u) both += lane_xor<16>(both, lane);
+            const uint32_t c_lt = both & 0xFFFFu, c_le = both >> 16;
+            const double s_lt = row_fetch_f64(before, c_lt, first_lane);
+            const double s_le = s_lt + (double)(c_le - c_lt) * (double)picked;
+            const bool copy_left = !ordered || picked < L;  // the level coincides with the left end
+            const float new_value = copy_left ? L : picked;
+            const uint32_t new_count_lt = copy_left ? cnt_lt_L : c_lt;
+            const double new_sum_lt = copy_left ? sum_lt_L : s_lt;
+            const uint32_t new_count_le = copy_left ? (ordered ? st.count_le[l] : cnt_le_R) : c_le;
+            const double new_sum_le = copy_left ? (ordered ? st.sum_le[l] : sum_le_R) : s_le;
+            const uint32_t new_rank = copy_left ? 0u : rank;
+            st.value[k] = same ? st.value[k] : new_value;
+            st.count_lt[k] = same ? st.count_lt[k] : new_count_lt;
+            st.sum_lt[k] = same ? st.sum_lt[k] : new_sum_lt;
+            st.count_le[k] = same ? st.count_le[k] : new_count_le;
+            st.sum_le[k] = same ? st.sum_le[k] : new_sum_le;
+            st.rank[k] = same ? st.rank[k] : new_rank;
+        };
+        for_greedy_steps<S, 0>(solve);
+        for (uint32_t sweep = 0; sweep < sweeps; ++sweep) for_sweep_levels<S, 1>(solve);
+#pragma unroll
+        for (int k = 1; k + 1 < S; ++k) lv[k] = st.value[k];
     } else {
         // S = sum (v - L) over the bucket, T = S / (R - L), level = element of rank #{v <= R} - floor(T)
         const double total = row_sum_f64<(int)G>(part, lane);
@@ -1281,9 +1420,9 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
 }
 
 template <int S, int BITS, int NB, int RULE>
-__global__ __launch_bounds__(4 * kWave) void sorted_small_kernel(const float* __restrict__ grad, size_t n, uint64_t seed,
-                                                                 uint64_t index_offset, float* __restrict__ levels,
-                                                                 uint32_t* __restrict__ codes32)
+__global__ __launch_bounds__(4 * kWave) void sorted_small_kernel(const float* __restrict__ grad, size_t n, uint32_t sweeps,
+                                                                 uint64_t seed, uint64_t index_offset,
+                                                                 float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
     const size_t span = (size_t)blockIdx.x * 4u + (threadIdx.x >> 6);  // 256 elements each
     const size_t begin = span * 256u;
@@ -1291,10 +1430,11 @@ __global__ __launch_bounds__(4 * kWave) void sorted_small_kernel(const float* __
     const size_t rest = n - begin;
     const uint32_t first_bucket = (uint32_t)(span * NB);
     if (rest >= 256u)
-        sorted_small_span<S, BITS, NB, true, RULE>(grad + begin, 256u, begin, first_bucket, seed, index_offset, levels, codes32);
+        sorted_small_span<S, BITS, NB, true, RULE>(grad + begin, 256u, begin, first_bucket, sweeps, seed, index_offset, levels,
+                                                   codes32);
     else
-        sorted_small_span<S, BITS, NB, false, RULE>(grad + begin, (uint32_t)rest, begin, first_bucket, seed, index_offset, levels,
-                                                    codes32);
+        sorted_small_span<S, BITS, NB, false, RULE>(grad + begin, (uint32_t)rest, begin, first_bucket, sweeps, seed, index_offset,
+                                                    levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1611,11 +1751,11 @@ void launch_sorted_small(const float* g, size_t n, const ogq_params_t* p, float*
     const size_t spans = (n + 255u) / 256u;
     const dim3 grid((uint32_t)((spans + 3u) / 4u)), block(4 * kWave);
     if (p->bucket_size == 64u)
-        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 4, RULE>), grid, block, 0, st, g, n, p->seed, p->index_offset, lv,
-                           static_cast<uint32_t*>(codes));
+        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 4, RULE>), grid, block, 0, st, g, n, p->level_iters, p->seed,
+                           p->index_offset, lv, static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 2, RULE>), grid, block, 0, st, g, n, p->seed, p->index_offset, lv,
-                           static_cast<uint32_t*>(codes));
+        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 2, RULE>), grid, block, 0, st, g, n, p->level_iters, p->seed,
+                           p->index_offset, lv, static_cast<uint32_t*>(codes));
 }
 
 template <int C, int RULE>
@@ -1625,15 +1765,12 @@ void launch_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32
     if constexpr (C == 1 && (RULE == kOptimal || RULE == kLinear)) {
         // buckets of 64 and 128 elements without clipping, sorted in registers, several per wavefront
         if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
-            if (p->bits == 2) {
-                launch_sorted_small<3, 2, RULE>(g, n, p, lv, codes, st);
-                return;
+            switch (p->bits) {
+                case 2: launch_sorted_small<3, 2, RULE>(g, n, p, lv, codes, st); break;
+                case 3: launch_sorted_small<5, 3, RULE>(g, n, p, lv, codes, st); break;
+                default: launch_sorted_small<9, 4, RULE>(g, n, p, lv, codes, st); break;
             }
-            if constexpr (RULE == kLinear) {
-                if (p->bits == 3) launch_sorted_small<5, 3, RULE>(g, n, p, lv, codes, st);
-                else launch_sorted_small<9, 4, RULE>(g, n, p, lv, codes, st);
-                return;
-            }
+            return;
         }
     }
     if constexpr (C == 1 && RULE == kEven) {
@@ -1661,6 +1798,14 @@ void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t
     switch (p->scheme) {
         case OGQ_BINGRAD_PB: launch_orq<C, 2, 1, kPb>(g, n, p, nb, lv, codes, st); break;
         case OGQ_ORQ:
+            if constexpr (C == 1) {
+                // buckets of 64 and 128 elements without clipping, sorted in registers, several per wavefront
+                if (p->bits >= 2 && p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+                    if (p->bits == 2) launch_sorted_small<4, 2, kOptimal>(g, n, p, lv, codes, st);
+                    else launch_sorted_small<8, 3, kOptimal>(g, n, p, lv, codes, st);
+                    break;
+                }
+            }
             switch (p->bits) {
                 case 1: launch_orq<C, 2, 1>(g, n, p, nb, lv, codes, st); break;
                 case 2: launch_orq<C, 4, 2>(g, n, p, nb, lv, codes, st); break;

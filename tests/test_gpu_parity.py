@@ -85,16 +85,18 @@ def test_bingrad_several_buckets_per_wavefront_above_four_million_elements(d):
 
 
 @pytest.mark.parametrize("bits", [1, 2, 3])
-@pytest.mark.parametrize("d", [64, 256, 320, 2048, 4096])
+@pytest.mark.parametrize("d", [64, 128, 256, 320, 2048, 4096])
 def test_orq_small(bits, d):
     rng = np.random.default_rng(100 * bits + d)
     for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
-        for n in (1, 2, 3, 65, d - 1, d, 3 * d + 129):
+        # (the longer ones: whole and cut-off groups of the 64- and 128-element buckets that share a wavefront)
+        for n in (1, 2, 3, 65, d - 1, d, d + 1, 3 * d + 129, 1024 + 5 * d, 2048 + 3 * d + 4):
             if n < 1:
                 continue
             g = _rng_bucket(rng, n, kind)
             for sweeps in (0, 2):
-                parity.check_quantize(g, d, bits, ogq.ORQ, sweeps, seed=1234 + n, tag=f"orq{bits}-{kind}-d{d}-n{n}")
+                parity.check_quantize(g, d, bits, ogq.ORQ, sweeps, seed=1234 + n, index_offset=64 * (n % 3),
+                                      tag=f"orq{bits}-{kind}-d{d}-n{n}")
 
 
 @pytest.mark.parametrize("d", [64, 256, 320, 512, 2048, 4096])
