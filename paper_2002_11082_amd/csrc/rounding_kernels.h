@@ -1109,14 +1109,15 @@ __global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __re
 }
 
 // ----------------------------------------------------------------------------------------------
-// ORQ with three levels and Linear-s for buckets of 64 or 128 elements, NB = 4 or 2 whole buckets per wavefront in
-// the layout of even_small_span.  A bucket this small is not grouped into bins: its 4 G keys (G = 64 / NB lanes,
-// 4 registers each) are sorted in registers by a bitonic network whose every compare-exchange is ascending -- the
-// first step of a merge pairs element e with e ^ (run length - 1), i.e. reverses the second run -- so that no step
-// needs a direction.  Element e = 4 * (lane inside the bucket) + register.  The levels are then order statistics
-// fetched from the sorted registers: the extremes, and either the element of the rank that the optimal condition
-// asks for (with three levels there is one solve, between the extremes, and it reads the bucket's total alone;
-// sweeps repeat it unchanged) or Linear-s's ranks.  No clipping here.
+// ORQ and Linear-s for buckets of 64 or 128 elements, NB = 4 or 2 whole buckets per wavefront in the layout of
+// even_small_span.  A bucket this small is not grouped into bins: its 4 G keys (G = 64 / NB lanes, 4 registers
+// each) are sorted in registers by a bitonic network whose every compare-exchange is ascending -- the first step of
+// a merge pairs element e with e ^ (run length - 1), i.e. reverses the second run -- so that no step needs a
+// direction.  Element e = 4 * (lane inside the bucket) + register.  The levels are then order statistics fetched
+// from the sorted registers: the extremes, and either Linear-s's ranks or the elements of the ranks that the optimal
+// condition asks for.  With three levels there is one solve, between the extremes, and it reads the bucket's total
+// alone (sweeps repeat it unchanged); with more, every lane keeps the level records of its bucket and the solves of
+// all buckets of the wavefront run side by side.  Two levels are the extremes and need no sort.  No clipping here.
 // ----------------------------------------------------------------------------------------------
 constexpr int kDppQuadReverse = 0x1B;  // quad_perm [3,2,1,0]: partner lane ^ 3
 
@@ -1280,7 +1281,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
                                                   uint32_t sweeps, uint64_t seed, uint64_t index_offset,
                                                   float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
-    static_assert(RULE == kLinear || (RULE == kOptimal && S >= 3), "rules that read order statistics");
+    static_assert(RULE == kLinear || RULE == kOptimal, "rules that read order statistics");
     constexpr uint32_t G = 64u / NB;  // lanes per bucket
     constexpr uint32_t D = 256u / NB;  // elements per bucket
     const uint32_t lane = threadIdx.x & 63u;
@@ -1307,110 +1308,127 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
         x[k] = valid ? float_to_key(value) : 0xFFFFFFFFu;  // padding sorts behind every value
         if constexpr (RULE == kOptimal && S == 3) part += valid ? (double)value : 0.0;
     }
-    row_sort<(int)G>(x, lane);
-
-    const uint32_t first_lane = lane & ~(G - 1u);
-    const uint32_t last = count > 0u ? count - 1u : 0u;
     float lv[S];
-    lv[0] = key_to_float(row_fetch(x, 0u, first_lane));
-    lv[S - 1] = key_to_float(row_fetch(x, last, first_lane));
-    if constexpr (RULE == kLinear) {
+    if constexpr (S == 2) {
+        // two levels are the extremes: no sort, two reductions over the group
+        uint32_t low = umin32(umin32(x[0], x[1]), umin32(x[2], x[3])), high = 0u;
 #pragma unroll
-        for (int k = 1; k + 1 < S; ++k) lv[k] = key_to_float(row_fetch(x, ((uint32_t)k * last) / (uint32_t)(S - 1), first_lane));
-    } else if constexpr (S > 3) {
-        // The solves of orq_solve_levels, every lane keeping the records of its own bucket.  What a solve needs
-        // around a picked element comes from the sorted registers: the counts of smaller and of not larger keys
-        // (summed over the group), and the sum of the smaller ones, an entry of the exclusive fp64 prefix.
-        const uint32_t l4 = 4u * (lane & (G - 1u));
-        double before[4];  // sum of the sorted elements in front of element 4 l + r
-        double total;
-        {
-            double run = 0.0, mine[4];
+        for (int k = 0; k < 4; ++k) high = umax32(high, x[k] == 0xFFFFFFFFu ? 0u : x[k]);
+        low = umin32(low, dpp_u32<kDppXor1>(low)); high = umax32(high, dpp_u32<kDppXor1>(high));
+        low = umin32(low, dpp_u32<kDppXor2>(low)); high = umax32(high, dpp_u32<kDppXor2>(high));
+        low = umin32(low, dpp_u32<kDppHalfMirror>(low)); high = umax32(high, dpp_u32<kDppHalfMirror>(high));
+        low = umin32(low, dpp_u32<kDppMirror>(low)); high = umax32(high, dpp_u32<kDppMirror>(high));
+        if constexpr (G == 32u) {
+            low = umin32(low, lane_xor<16>(low, lane));
+            high = umax32(high, lane_xor<16>(high, lane));
+        }
+        lv[0] = key_to_float(low);
+        lv[1] = key_to_float(high);
+    } else {
+        row_sort<(int)G>(x, lane);
+
+        const uint32_t first_lane = lane & ~(G - 1u);
+        const uint32_t last = count > 0u ? count - 1u : 0u;
+        lv[0] = key_to_float(row_fetch(x, 0u, first_lane));
+        lv[S - 1] = key_to_float(row_fetch(x, last, first_lane));
+        if constexpr (RULE == kLinear) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                mine[r] = run;
-                run += l4 + r < count ? (double)key_to_float(x[r]) : 0.0;
+            for (int k = 1; k + 1 < S; ++k) lv[k] = key_to_float(row_fetch(x, ((uint32_t)k * last) / (uint32_t)(S - 1), first_lane));
+        } else if constexpr (S > 3) {
+            // The solves of orq_solve_levels, every lane keeping the records of its own bucket.  What a solve needs
+            // around a picked element comes from the sorted registers: the counts of smaller and of not larger keys
+            // (summed over the group), and the sum of the smaller ones, an entry of the exclusive fp64 prefix.
+            const uint32_t l4 = 4u * (lane & (G - 1u));
+            double before[4];  // sum of the sorted elements in front of element 4 l + r
+            double total;
+            {
+                double run = 0.0, mine[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    mine[r] = run;
+                    run += l4 + r < count ? (double)key_to_float(x[r]) : 0.0;
+                }
+                const double incl = row_inclusive_scan_f64<(int)G>(run);
+                const double lanes_before = incl - run;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) before[r] = lanes_before + mine[r];
+                total = lane_fetch_f64(incl, first_lane + G - 1u);
             }
-            const double incl = row_inclusive_scan_f64<(int)G>(run);
-            const double lanes_before = incl - run;
+            RowLevels<S> st;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) before[r] = lanes_before + mine[r];
-            total = lane_fetch_f64(incl, first_lane + G - 1u);
-        }
-        RowLevels<S> st;
+            for (int k = 0; k < S; ++k) {
+                st.value[k] = k == S - 1 ? lv[S - 1] : lv[0];
+                st.count_lt[k] = k == S - 1 ? count : 0u;
+                st.count_le[k] = k == S - 1 ? count : 0u;
+                st.sum_lt[k] = k == S - 1 ? total : 0.0;
+                st.sum_le[k] = k == S - 1 ? total : 0.0;
+                st.rank[k] = 0u;
+            }
+            const uint32_t count_or_one = count > 0u ? count : 1u;
+            auto solve = [&](auto kc, auto lc, auto rc) {
+                constexpr int k = decltype(kc)::value, l = decltype(lc)::value, r = decltype(rc)::value;
+                const float L = st.value[l], R = st.value[r];
+                const uint32_t cnt_lt_L = st.count_lt[l], cnt_le_R = st.count_le[r];
+                const double sum_lt_L = st.sum_lt[l], sum_le_R = st.sum_le[r];
+                const bool ordered = L < R;
+                // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
+                const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
+                const double T = Ssum / ((double)R - (double)L);  // not used when L == R
+                double m = floor(T);
+                if (!(m >= 0.0)) m = 0.0;
+                const bool whole = m >= (double)cnt_le_R;
+                uint32_t rank = whole ? 1u : cnt_le_R - (uint32_t)(whole ? 0.0 : m);
+                rank = rank < 1u ? 1u : (rank > count_or_one ? count_or_one : rank);
+                const bool same = ordered && rank == st.rank[k];  // same element as last time
+                if (__ballot(!same) == 0) return;
+                const uint32_t key = row_fetch(x, rank - 1u, first_lane);
+                const float picked = key_to_float(key);
+                uint32_t below = 0, not_above = 0;
 #pragma unroll
-        for (int k = 0; k < S; ++k) {
-            st.value[k] = k == S - 1 ? lv[S - 1] : lv[0];
-            st.count_lt[k] = k == S - 1 ? count : 0u;
-            st.count_le[k] = k == S - 1 ? count : 0u;
-            st.sum_lt[k] = k == S - 1 ? total : 0.0;
-            st.sum_le[k] = k == S - 1 ? total : 0.0;
-            st.rank[k] = 0u;
-        }
-        const uint32_t count_or_one = count > 0u ? count : 1u;
-        auto solve = [&](auto kc, auto lc, auto rc) {
-            constexpr int k = decltype(kc)::value, l = decltype(lc)::value, r = decltype(rc)::value;
-            const float L = st.value[l], R = st.value[r];
-            const uint32_t cnt_lt_L = st.count_lt[l], cnt_le_R = st.count_le[r];
-            const double sum_lt_L = st.sum_lt[l], sum_le_R = st.sum_le[r];
-            const bool ordered = L < R;
-            // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
-            const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
-            const double T = Ssum / ((double)R - (double)L);  // not used when L == R
+                for (int i = 0; i < 4; ++i) {
+                    below += x[i] < key ? 1u : 0u;
+                    not_above += x[i] <= key ? 1u : 0u;
+                }
+                uint32_t both = below | (not_above << 16);
+                both += dpp_u32<kDppXor1>(both);
+                both += dpp_u32<kDppXor2>(both);
+                both += dpp_u32<kDppHalfMirror>(both);
+                both += dpp_u32<kDppMirror>(both);
+                if constexpr (G == 32u) both += lane_xor<16>(both, lane);
+                const uint32_t c_lt = both & 0xFFFFu, c_le = both >> 16;
+                const double s_lt = row_fetch_f64(before, c_lt, first_lane);
+                const double s_le = s_lt + (double)(c_le - c_lt) * (double)picked;
+                const bool copy_left = !ordered || picked < L;  // the level coincides with the left end
+                const float new_value = copy_left ? L : picked;
+                const uint32_t new_count_lt = copy_left ? cnt_lt_L : c_lt;
+                const double new_sum_lt = copy_left ? sum_lt_L : s_lt;
+                const uint32_t new_count_le = copy_left ? (ordered ? st.count_le[l] : cnt_le_R) : c_le;
+                const double new_sum_le = copy_left ? (ordered ? st.sum_le[l] : sum_le_R) : s_le;
+                const uint32_t new_rank = copy_left ? 0u : rank;
+                st.value[k] = same ? st.value[k] : new_value;
+                st.count_lt[k] = same ? st.count_lt[k] : new_count_lt;
+                st.sum_lt[k] = same ? st.sum_lt[k] : new_sum_lt;
+                st.count_le[k] = same ? st.count_le[k] : new_count_le;
+                st.sum_le[k] = same ? st.sum_le[k] : new_sum_le;
+                st.rank[k] = same ? st.rank[k] : new_rank;
+            };
+            for_greedy_steps<S, 0>(solve);
+            for (uint32_t sweep = 0; sweep < sweeps; ++sweep) for_sweep_levels<S, 1>(solve);
+#pragma unroll
+            for (int k = 1; k + 1 < S; ++k) lv[k] = st.value[k];
+        } else {
+            // S = sum (v - L) over the bucket, T = S / (R - L), level = element of rank #{v <= R} - floor(T)
+            const double total = row_sum_f64<(int)G>(part, lane);
+            const float L = lv[0], R = lv[2];
+            const double T = (total - (double)L * (double)count) / ((double)R - (double)L);  // not used when L == R
             double m = floor(T);
             if (!(m >= 0.0)) m = 0.0;
-            const bool whole = m >= (double)cnt_le_R;
-            uint32_t rank = whole ? 1u : cnt_le_R - (uint32_t)(whole ? 0.0 : m);
-            rank = rank < 1u ? 1u : (rank > count_or_one ? count_or_one : rank);
-            const bool same = ordered && rank == st.rank[k];  // same element as last time
-            if (__ballot(!same) == 0) return;
-            const uint32_t key = row_fetch(x, rank - 1u, first_lane);
-            const float picked = key_to_float(key);
-            uint32_t below = 0, not_above = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                below += x[i] < key ? 1u : 0u;
-                not_above += x[i] <= key ? 1u : 0u;
-            }
-            uint32_t both = below | (not_above << 16);
-            both += dpp_u32<kDppXor1>(both);
-            both += dpp_u32<kDppXor2>(both);
-            both += dpp_u32<kDppHalfMirror>(both);
-            both += dpp_u32<kDppMirror>(both);
-            if constexpr (G == 32u) both += lane_xor<16>(both, lane);
-            const uint32_t c_lt = both & 0xFFFFu, c_le = both >> 16;
-            const double s_lt = row_fetch_f64(before, c_lt, first_lane);
-            const double s_le = s_lt + (double)(c_le - c_lt) * (double)picked;
-            const bool copy_left = !ordered || picked < L;  // the level coincides with the left end
-            const float new_value = copy_left ? L : picked;
-            const uint32_t new_count_lt = copy_left ? cnt_lt_L : c_lt;
-            const double new_sum_lt = copy_left ? sum_lt_L : s_lt;
-            const uint32_t new_count_le = copy_left ? (ordered ? st.count_le[l] : cnt_le_R) : c_le;
-            const double new_sum_le = copy_left ? (ordered ? st.sum_le[l] : sum_le_R) : s_le;
-            const uint32_t new_rank = copy_left ? 0u : rank;
-            st.value[k] = same ? st.value[k] : new_value;
-            st.count_lt[k] = same ? st.count_lt[k] : new_count_lt;
-            st.sum_lt[k] = same ? st.sum_lt[k] : new_sum_lt;
-            st.count_le[k] = same ? st.count_le[k] : new_count_le;
-            st.sum_le[k] = same ? st.sum_le[k] : new_sum_le;
-            st.rank[k] = same ? st.rank[k] : new_rank;
-        };
-        for_greedy_steps<S, 0>(solve);
-        for (uint32_t sweep = 0; sweep < sweeps; ++sweep) for_sweep_levels<S, 1>(solve);
-#pragma unroll
-        for (int k = 1; k + 1 < S; ++k) lv[k] = st.value[k];
-    } else {
-        // S = sum (v - L) over the bucket, T = S / (R - L), level = element of rank #{v <= R} - floor(T)
-        const double total = row_sum_f64<(int)G>(part, lane);
-        const float L = lv[0], R = lv[2];
-        const double T = (total - (double)L * (double)count) / ((double)R - (double)L);  // not used when L == R
-        double m = floor(T);
-        if (!(m >= 0.0)) m = 0.0;
-        if (m > (double)count) m = (double)count;
-        uint32_t rank = m >= (double)count ? 1u : count - (uint32_t)m;
-        rank = rank < 1u ? 1u : rank;
-        const float picked = key_to_float(row_fetch(x, rank - 1u, first_lane));
-        lv[1] = (L < R && !(picked < L)) ? picked : L;
+            if (m > (double)count) m = (double)count;
+            uint32_t rank = m >= (double)count ? 1u : count - (uint32_t)m;
+            rank = rank < 1u ? 1u : rank;
+            const float picked = key_to_float(row_fetch(x, rank - 1u, first_lane));
+            lv[1] = (L < R && !(picked < L)) ? picked : L;
+        }
     }
     if (lane % G == 0u && (FULL || q * D < len)) {
 #pragma unroll
@@ -1800,8 +1818,9 @@ void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t
         case OGQ_ORQ:
             if constexpr (C == 1) {
                 // buckets of 64 and 128 elements without clipping, sorted in registers, several per wavefront
-                if (p->bits >= 2 && p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
-                    if (p->bits == 2) launch_sorted_small<4, 2, kOptimal>(g, n, p, lv, codes, st);
+                if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+                    if (p->bits == 1) launch_sorted_small<2, 1, kOptimal>(g, n, p, lv, codes, st);
+                    else if (p->bits == 2) launch_sorted_small<4, 2, kOptimal>(g, n, p, lv, codes, st);
                     else launch_sorted_small<8, 3, kOptimal>(g, n, p, lv, codes, st);
                     break;
                 }
