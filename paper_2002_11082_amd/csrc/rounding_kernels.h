@@ -1109,7 +1109,7 @@ __global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __re
 }
 
 // ----------------------------------------------------------------------------------------------
-// ORQ and Linear-s for buckets of 64 or 128 elements, NB = 4 or 2 whole buckets per wavefront in the layout of
+// ORQ, Linear-s and BinGrad-pb for buckets of 64 or 128 elements, NB = 4 or 2 whole buckets per wavefront in the layout of
 // even_small_span.  A bucket this small is not grouped into bins: its 4 G keys (G = 64 / NB lanes, 4 registers
 // each) are sorted in registers by a bitonic network whose every compare-exchange is ascending -- the first step of
 // a merge pairs element e with e ^ (run length - 1), i.e. reverses the second run -- so that no step needs a
@@ -1117,7 +1117,9 @@ __global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __re
 // from the sorted registers: the extremes, and either Linear-s's ranks or the elements of the ranks that the optimal
 // condition asks for.  With three levels there is one solve, between the extremes, and it reads the bucket's total
 // alone (sweeps repeat it unchanged); with more, every lane keeps the level records of its bucket and the solves of
-// all buckets of the wavefront run side by side.  Two levels are the extremes and need no sort.  No clipping here.
+// all buckets of the wavefront run side by side.  Two levels are the extremes and need no sort.  BinGrad-pb's level
+// is the positive value at the sign change of its condition, which every element evaluates for itself from the
+// exclusive fp64 prefix of the sorted values.  No clipping here.
 // ----------------------------------------------------------------------------------------------
 constexpr int kDppQuadReverse = 0x1B;  // quad_perm [3,2,1,0]: partner lane ^ 3
 
@@ -1281,7 +1283,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
                                                   uint32_t sweeps, uint64_t seed, uint64_t index_offset,
                                                   float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
-    static_assert(RULE == kLinear || RULE == kOptimal, "rules that read order statistics");
+    static_assert(RULE == kLinear || RULE == kOptimal || (RULE == kPb && S == 2), "rules that read order statistics");
     constexpr uint32_t G = 64u / NB;  // lanes per bucket
     constexpr uint32_t D = 256u / NB;  // elements per bucket
     const uint32_t lane = threadIdx.x & 63u;
@@ -1309,7 +1311,74 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
         if constexpr (RULE == kOptimal && S == 3) part += valid ? (double)value : 0.0;
     }
     float lv[S];
-    if constexpr (S == 2) {
+    if constexpr (RULE == kPb) {
+        // b_1 minimises |b * #{v > 0} - sum_{v >= b} v| over the bucket's positive values.  Every element evaluates the
+        // difference for its own value in its own lane (the sum of the smaller elements is its entry of the exclusive
+        // prefix if it is the first of its value); the difference grows with b, so the minimiser is the first value
+        // where it is not negative, or the distinct value just below.
+        row_sort<(int)G>(x, lane);
+        const uint32_t first_lane = lane & ~(G - 1u);
+        const uint32_t l4 = 4u * (lane & (G - 1u));
+        constexpr uint32_t kZeroKey = 0x80000000u;  // key of +0
+        double before[4], run = 0.0;
+        uint32_t not_positive = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            before[r] = run;
+            run += l4 + r < count ? (double)key_to_float(x[r]) : 0.0;
+            not_positive += x[r] <= kZeroKey ? 1u : 0u;
+        }
+        const double incl = row_inclusive_scan_f64<(int)G>(run);
+        const double lanes_before = incl - run;
+        const double total = lane_fetch_f64(incl, first_lane + G - 1u);
+        not_positive += dpp_u32<kDppXor1>(not_positive);
+        not_positive += dpp_u32<kDppXor2>(not_positive);
+        not_positive += dpp_u32<kDppHalfMirror>(not_positive);
+        not_positive += dpp_u32<kDppMirror>(not_positive);
+        if constexpr (G == 32u) not_positive += lane_xor<16>(not_positive, lane);
+        const uint32_t positives = count - (not_positive < count ? not_positive : count);
+        // last key of the lane in front (none for the first lane of the group: key 0 lies below every positive key)
+        const uint32_t front = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((lane - 1u) << 2), (int)x[3]);
+        double gap[4];
+        uint32_t first_ok = 0xFFFFu, last_first = 0u;  // element indices inside the bucket
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            before[r] += lanes_before;
+            const uint32_t previous = r > 0 ? x[r > 0 ? r - 1 : 0] : (lane == first_lane ? 0u : front);
+            const bool candidate = l4 + r < count && x[r] > kZeroKey && x[r] != previous;  // first of a positive value
+            gap[r] = (double)key_to_float(x[r]) * (double)positives - (total - before[r]);
+            if (candidate && gap[r] >= 0.0) first_ok = umin32(first_ok, l4 + r);
+            if (candidate) last_first = umax32(last_first, l4 + r);
+        }
+        first_ok = umin32(first_ok, dpp_u32<kDppXor1>(first_ok)); last_first = umax32(last_first, dpp_u32<kDppXor1>(last_first));
+        first_ok = umin32(first_ok, dpp_u32<kDppXor2>(first_ok)); last_first = umax32(last_first, dpp_u32<kDppXor2>(last_first));
+        first_ok = umin32(first_ok, dpp_u32<kDppHalfMirror>(first_ok));
+        last_first = umax32(last_first, dpp_u32<kDppHalfMirror>(last_first));
+        first_ok = umin32(first_ok, dpp_u32<kDppMirror>(first_ok)); last_first = umax32(last_first, dpp_u32<kDppMirror>(last_first));
+        if constexpr (G == 32u) {
+            first_ok = umin32(first_ok, lane_xor<16>(first_ok, lane));
+            last_first = umax32(last_first, lane_xor<16>(last_first, lane));
+        }
+        // (the largest value's difference is >= 0 but for rounding: if no element says so, it is the answer)
+        const uint32_t at = first_ok != 0xFFFFu ? first_ok : last_first;
+        const float up = key_to_float(row_fetch(x, at, first_lane));
+        const double gap_up = row_fetch_f64(gap, at, first_lane);
+        // the distinct value just below, which counts if it is positive: its difference sits where that value begins
+        const uint32_t down_key = row_fetch(x, at > 0u ? at - 1u : 0u, first_lane);
+        uint32_t down_at = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) down_at += x[r] < down_key ? 1u : 0u;
+        down_at += dpp_u32<kDppXor1>(down_at);
+        down_at += dpp_u32<kDppXor2>(down_at);
+        down_at += dpp_u32<kDppHalfMirror>(down_at);
+        down_at += dpp_u32<kDppMirror>(down_at);
+        if constexpr (G == 32u) down_at += lane_xor<16>(down_at, lane);
+        const double gap_down = row_fetch_f64(gap, down_at, first_lane);
+        const bool take_down = at > not_positive && fabs(gap_down) <= fabs(gap_up);  // ties take the smaller value
+        const float pb_level = positives > 0u ? (take_down ? key_to_float(down_key) : up) : 0.0f;
+        lv[0] = -pb_level;
+        lv[1] = pb_level;
+    } else if constexpr (S == 2) {
         // two levels are the extremes: no sort, two reductions over the group
         uint32_t low = umin32(umin32(x[0], x[1]), umin32(x[2], x[3])), high = 0u;
 #pragma unroll
@@ -1814,7 +1883,15 @@ void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t
                        hipStream_t st)
 {
     switch (p->scheme) {
-        case OGQ_BINGRAD_PB: launch_orq<C, 2, 1, kPb>(g, n, p, nb, lv, codes, st); break;
+        case OGQ_BINGRAD_PB:
+            if constexpr (C == 1) {
+                if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+                    launch_sorted_small<2, 1, kPb>(g, n, p, lv, codes, st);
+                    break;
+                }
+            }
+            launch_orq<C, 2, 1, kPb>(g, n, p, nb, lv, codes, st);
+            break;
         case OGQ_ORQ:
             if constexpr (C == 1) {
                 // buckets of 64 and 128 elements without clipping, sorted in registers, several per wavefront

@@ -99,13 +99,15 @@ def test_orq_small(bits, d):
                                       tag=f"orq{bits}-{kind}-d{d}-n{n}")
 
 
-@pytest.mark.parametrize("d", [64, 256, 320, 512, 2048, 4096])
+@pytest.mark.parametrize("d", [64, 128, 256, 320, 512, 2048, 4096])
 def test_bingrad_pb_small(d):
     rng = np.random.default_rng(1000 + d)
     for kind in ("normal", "ints", "heavy", "shifted", "const", "zeros"):
-        for n in (1, 2, 65, d - 1, d, 3 * d + 129):
+        # (the longer ones: whole and cut-off groups of the 64- and 128-element buckets that share a wavefront)
+        for n in (1, 2, 3, 65, d - 1, d, d + 1, 3 * d + 129, 1024 + 5 * d, 2048 + 3 * d + 4):
             g = _rng_bucket(rng, n, kind)
-            parity.check_quantize(g, d, 1, ogq.BINGRAD_PB, 0, seed=31 + n, tag=f"bingradpb-{kind}-d{d}-n{n}")
+            parity.check_quantize(g, d, 1, ogq.BINGRAD_PB, 0, seed=31 + n, index_offset=64 * (n % 3),
+                                  tag=f"bingradpb-{kind}-d{d}-n{n}")
             parity.check_quantize(-g, d, 1, ogq.BINGRAD_PB, 0, seed=31 + n, tag=f"bingradpb-neg-{kind}-d{d}-n{n}")
     g = _rng_bucket(rng, 4 * d + 3, "heavy")
     parity.check_quantize(g, d, 1, ogq.BINGRAD_PB, 0, seed=5, clip_factor=2.5, tag=f"bingradpb-clip-d{d}")
