@@ -421,7 +421,11 @@ def test_non_finite_values_stay_inside_their_bucket():
     cases = [(ogq.BINGRAD_B, 1, 512, 2100 * 2048 + 700), (ogq.BINGRAD_B, 1, 2048, 40 * 2048 + 5),
              (ogq.BINGRAD_B, 1, 8192, 9 * 8192), (ogq.SCALED_SIGN, 1, 256, 30 * 2048 + 64),
              (ogq.ORQ, 2, 2048, 40 * 2048 + 5), (ogq.ORQ, 3, 4096, 12 * 4096), (ogq.ORQ_PAPER, 2, 16384, 5 * 16384 + 9),
-             (ogq.BINGRAD_PB, 1, 1024, 33 * 1024), (ogq.EVEN, 2, 512, 70 * 512), (ogq.LINEAR, 3, 2048, 21 * 2048)]
+             (ogq.BINGRAD_PB, 1, 1024, 33 * 1024), (ogq.EVEN, 2, 512, 70 * 512), (ogq.LINEAR, 3, 2048, 21 * 2048),
+             # several buckets per wavefront: the neighbours of a poisoned bucket share its registers' lanes
+             (ogq.EVEN, 2, 64, 41 * 64 + 7), (ogq.ORQ, 2, 128, 37 * 128 + 50), (ogq.ORQ, 1, 64, 29 * 64),
+             (ogq.ORQ_PAPER, 2, 64, 53 * 64 + 1), (ogq.ORQ_PAPER, 4, 128, 19 * 128 + 127),
+             (ogq.BINGRAD_PB, 1, 128, 26 * 128 + 3), (ogq.LINEAR, 3, 64, 44 * 64 + 63)]
     for scheme, bits, d, n in cases:
         g = (rng.standard_t(3, n) * 1e-3).astype(np.float32)
         nb = (n + d - 1) // d
