@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 WORKLOAD_NAMES = ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "pb2", "orq5", "orq3clip", "cfg2clip", "bin512", "sign2",
-                  "tern3", "linear5", "orq3d32k")
+                  "tern3", "linear5", "orq3d32k", "orq3d128")
 
 
 def algorithmic_bytes(n: int, bucket_size: int, bits: int, workers: int, levels_per_bucket: int):
@@ -248,7 +248,9 @@ def main() -> int:
     copy_gbs = 8 * (n - n % 4) / timed(lambda i: ogq.ogq_probe_copy(grads[i % n_buf][0], outs[(i + 1) % n_buf])) / 1e9
 
     two_level_means = wl.scheme in (synth.BINGRAD_B, synth.SCALED_SIGN)
-    if not two_level_means:
+    if not two_level_means and d in (64, 128) and wl.clip_factor == 0:
+        quant_name = "even_small_kernel" if wl.scheme == synth.EVEN else "sorted_small_kernel"
+    elif not two_level_means:
         quant_name = "orq_quantize_kernel" if d <= 2048 else "orq_team_kernel"
     elif d > 2048:
         quant_name = "bingrad_team_kernel"

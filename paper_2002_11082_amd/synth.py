@@ -136,6 +136,8 @@ WORKLOADS = {
                        "BinGrad-b 1-bit on the cfg2 gradient, bucket 512 (the paper's ImageNet bucket size)", data="cfg2"),
     "orq3d32k": Workload("orq3d32k", 25_600_000, 32768, 2, ORQ_PAPER, 0, 1, 9,
                          "ORQ-3 on the cfg3 gradient, bucket 32768 (the largest of the paper's bucket-size sweep)", data="cfg3"),
+    "orq3d128": Workload("orq3d128", 25_600_000, 128, 2, ORQ_PAPER, 0, 1, 10,
+                         "ORQ-3 on the cfg3 gradient, bucket 128 (the smallest of the paper's bucket-size sweep)", data="cfg3"),
     # the level rules the paper compares against, on the same kernels and inputs
     "sign2": Workload("sign2", 25_600_000, 2048, 1, SCALED_SIGN, 0, 1, 0,
                       "Scaled SignSGD per bucket on the cfg2 gradient, bucket 2048", data="cfg2"),
