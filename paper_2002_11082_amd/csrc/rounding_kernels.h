@@ -1109,8 +1109,8 @@ __global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __re
 }
 
 // ----------------------------------------------------------------------------------------------
-// ORQ, Linear-s and BinGrad-pb for buckets of 64 or 128 elements, NB = 4 or 2 whole buckets per wavefront in the layout of
-// even_small_span.  A bucket this small is not grouped into bins: its 4 G keys (G = 64 / NB lanes, 4 registers
+// ORQ, Linear-s and BinGrad-pb for buckets of 64 or 128 elements, NB = 4 or 2 whole buckets per wavefront in the
+// layout of even_small_span.  A bucket this small is not grouped into bins: its 4 G keys (G = 64 / NB lanes, 4 registers
 // each) are sorted in registers by a bitonic network whose every compare-exchange is ascending -- the first step of
 // a merge pairs element e with e ^ (run length - 1), i.e. reverses the second run -- so that no step needs a
 // direction.  Element e = 4 * (lane inside the bucket) + register.  The levels are then order statistics fetched
@@ -1221,6 +1221,35 @@ __device__ __forceinline__ double row_sum_f64(double x, uint32_t lane)
     return x;
 }
 
+template <int G>
+__device__ __forceinline__ uint32_t row_sum_u32(uint32_t x, uint32_t lane)
+{
+    x += dpp_u32<kDppXor1>(x);
+    x += dpp_u32<kDppXor2>(x);
+    x += dpp_u32<kDppHalfMirror>(x);
+    x += dpp_u32<kDppMirror>(x);
+    if constexpr (G == 32) x += lane_xor<16>(x, lane);
+    return x;
+}
+
+// Minimum over the group of G lanes, in every lane of the group.
+template <int G>
+__device__ __forceinline__ uint32_t row_min_u32(uint32_t x, uint32_t lane)
+{
+    x = umin32(x, dpp_u32<kDppXor1>(x));
+    x = umin32(x, dpp_u32<kDppXor2>(x));
+    x = umin32(x, dpp_u32<kDppHalfMirror>(x));
+    x = umin32(x, dpp_u32<kDppMirror>(x));
+    if constexpr (G == 32) x = umin32(x, lane_xor<16>(x, lane));
+    return x;
+}
+
+template <int G>
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t x, uint32_t lane)
+{
+    return ~row_min_u32<G>(~x, lane);
+}
+
 // Inclusive scan over the lanes of every group of G lanes (G = 16 or 32).
 template <int G>
 __device__ __forceinline__ double row_inclusive_scan_f64(double x)
@@ -1262,7 +1291,8 @@ __device__ __forceinline__ void for_greedy_steps(Solve&& solve)
 {
     constexpr GreedyOrder order = greedy_order<S>();
     if constexpr (STEP < order.count) {
-        constexpr uint32_t e = STEP < 5 ? (uint32_t)(order.packed[0] >> (12 * STEP)) : (uint32_t)(order.packed[1] >> (12 * (STEP - 5)));
+        constexpr uint32_t e =
+            STEP < 5 ? (uint32_t)(order.packed[0] >> (12 * STEP)) : (uint32_t)(order.packed[1] >> (12 * (STEP - 5)));
         solve(std::integral_constant<int, (int)(e & 15u)>{}, std::integral_constant<int, (int)((e >> 4) & 15u)>{},
               std::integral_constant<int, (int)((e >> 8) & 15u)>{});
         for_greedy_steps<S, STEP + 1>(solve);
@@ -1331,11 +1361,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
         const double incl = row_inclusive_scan_f64<(int)G>(run);
         const double lanes_before = incl - run;
         const double total = lane_fetch_f64(incl, first_lane + G - 1u);
-        not_positive += dpp_u32<kDppXor1>(not_positive);
-        not_positive += dpp_u32<kDppXor2>(not_positive);
-        not_positive += dpp_u32<kDppHalfMirror>(not_positive);
-        not_positive += dpp_u32<kDppMirror>(not_positive);
-        if constexpr (G == 32u) not_positive += lane_xor<16>(not_positive, lane);
+        not_positive = row_sum_u32<(int)G>(not_positive, lane);
         const uint32_t positives = count - (not_positive < count ? not_positive : count);
         // last key of the lane in front (none for the first lane of the group: key 0 lies below every positive key)
         const uint32_t front = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((lane - 1u) << 2), (int)x[3]);
@@ -1350,15 +1376,8 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
             if (candidate && gap[r] >= 0.0) first_ok = umin32(first_ok, l4 + r);
             if (candidate) last_first = umax32(last_first, l4 + r);
         }
-        first_ok = umin32(first_ok, dpp_u32<kDppXor1>(first_ok)); last_first = umax32(last_first, dpp_u32<kDppXor1>(last_first));
-        first_ok = umin32(first_ok, dpp_u32<kDppXor2>(first_ok)); last_first = umax32(last_first, dpp_u32<kDppXor2>(last_first));
-        first_ok = umin32(first_ok, dpp_u32<kDppHalfMirror>(first_ok));
-        last_first = umax32(last_first, dpp_u32<kDppHalfMirror>(last_first));
-        first_ok = umin32(first_ok, dpp_u32<kDppMirror>(first_ok)); last_first = umax32(last_first, dpp_u32<kDppMirror>(last_first));
-        if constexpr (G == 32u) {
-            first_ok = umin32(first_ok, lane_xor<16>(first_ok, lane));
-            last_first = umax32(last_first, lane_xor<16>(last_first, lane));
-        }
+        first_ok = row_min_u32<(int)G>(first_ok, lane);
+        last_first = row_max_u32<(int)G>(last_first, lane);
         // (the largest value's difference is >= 0 but for rounding: if no element says so, it is the answer)
         const uint32_t at = first_ok != 0xFFFFu ? first_ok : last_first;
         const float up = key_to_float(row_fetch(x, at, first_lane));
@@ -1368,11 +1387,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
         uint32_t down_at = 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) down_at += x[r] < down_key ? 1u : 0u;
-        down_at += dpp_u32<kDppXor1>(down_at);
-        down_at += dpp_u32<kDppXor2>(down_at);
-        down_at += dpp_u32<kDppHalfMirror>(down_at);
-        down_at += dpp_u32<kDppMirror>(down_at);
-        if constexpr (G == 32u) down_at += lane_xor<16>(down_at, lane);
+        down_at = row_sum_u32<(int)G>(down_at, lane);
         const double gap_down = row_fetch_f64(gap, down_at, first_lane);
         const bool take_down = at > not_positive && fabs(gap_down) <= fabs(gap_up);  // ties take the smaller value
         const float pb_level = positives > 0u ? (take_down ? key_to_float(down_key) : up) : 0.0f;
@@ -1383,16 +1398,8 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
         uint32_t low = umin32(umin32(x[0], x[1]), umin32(x[2], x[3])), high = 0u;
 #pragma unroll
         for (int k = 0; k < 4; ++k) high = umax32(high, x[k] == 0xFFFFFFFFu ? 0u : x[k]);
-        low = umin32(low, dpp_u32<kDppXor1>(low)); high = umax32(high, dpp_u32<kDppXor1>(high));
-        low = umin32(low, dpp_u32<kDppXor2>(low)); high = umax32(high, dpp_u32<kDppXor2>(high));
-        low = umin32(low, dpp_u32<kDppHalfMirror>(low)); high = umax32(high, dpp_u32<kDppHalfMirror>(high));
-        low = umin32(low, dpp_u32<kDppMirror>(low)); high = umax32(high, dpp_u32<kDppMirror>(high));
-        if constexpr (G == 32u) {
-            low = umin32(low, lane_xor<16>(low, lane));
-            high = umax32(high, lane_xor<16>(high, lane));
-        }
-        lv[0] = key_to_float(low);
-        lv[1] = key_to_float(high);
+        lv[0] = key_to_float(row_min_u32<(int)G>(low, lane));
+        lv[1] = key_to_float(row_max_u32<(int)G>(high, lane));
     } else {
         row_sort<(int)G>(x, lane);
 
@@ -1402,7 +1409,8 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
         lv[S - 1] = key_to_float(row_fetch(x, last, first_lane));
         if constexpr (RULE == kLinear) {
 #pragma unroll
-            for (int k = 1; k + 1 < S; ++k) lv[k] = key_to_float(row_fetch(x, ((uint32_t)k * last) / (uint32_t)(S - 1), first_lane));
+            for (int k = 1; k + 1 < S; ++k)
+                lv[k] = key_to_float(row_fetch(x, ((uint32_t)k * last) / (uint32_t)(S - 1), first_lane));
         } else if constexpr (S > 3) {
             // The solves of orq_solve_levels, every lane keeping the records of its own bucket.  What a solve needs
             // around a picked element comes from the sorted registers: the counts of smaller and of not larger keys
@@ -1458,12 +1466,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
                     below += x[i] < key ? 1u : 0u;
                     not_above += x[i] <= key ? 1u : 0u;
                 }
-                uint32_t both = below | (not_above << 16);
-                both += dpp_u32<kDppXor1>(both);
-                both += dpp_u32<kDppXor2>(both);
-                both += dpp_u32<kDppHalfMirror>(both);
-                both += dpp_u32<kDppMirror>(both);
-                if constexpr (G == 32u) both += lane_xor<16>(both, lane);
+                const uint32_t both = row_sum_u32<(int)G>(below | (not_above << 16), lane);  // two counts of at most 128
                 const uint32_t c_lt = both & 0xFFFFu, c_le = both >> 16;
                 const double s_lt = row_fetch_f64(before, c_lt, first_lane);
                 const double s_le = s_lt + (double)(c_le - c_lt) * (double)picked;
