@@ -248,7 +248,7 @@ def main() -> int:
     copy_gbs = 8 * (n - n % 4) / timed(lambda i: ogq.ogq_probe_copy(grads[i % n_buf][0], outs[(i + 1) % n_buf])) / 1e9
 
     two_level_means = wl.scheme in (synth.BINGRAD_B, synth.SCALED_SIGN)
-    if not two_level_means and d in (64, 128) and wl.clip_factor == 0:
+    if not two_level_means and d in (64, 128):
         quant_name = "even_small_kernel" if wl.scheme == synth.EVEN else "sorted_small_kernel"
     elif not two_level_means:
         quant_name = "orq_quantize_kernel" if d <= 2048 else "orq_team_kernel"

@@ -1046,17 +1046,42 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(C == 8 ? 
         orq_bucket<C, S, BITS, false, CLIP, RULE>(lds, grad + begin, len, begin, bucket, sweeps, clip, seed, index_offset, levels, codes32);
 }
 
+// Clipping when a wavefront holds NB whole buckets (lane l: elements 4l .. 4l+3 of the wavefront's 256, bucket
+// l / G with G = 64 / NB): clip_in_registers with the sums taken over the bucket's group of lanes.
+template <int NB, bool FULL>
+__device__ __forceinline__ void clip_small_buckets(float (&v)[4], uint32_t len, float clip, uint32_t lane)
+{
+    constexpr uint32_t G = 64u / NB, D = 256u / NB;
+    const uint32_t q = lane / G;
+    uint32_t count = D;
+    if constexpr (!FULL) count = q * D < len ? (len - q * D < D ? len - q * D : D) : 1u;  // (no element: nothing is stored)
+    clip_in_registers<4>(
+        v, count, clip, [&](int j) { return FULL || 4u * lane + j < len; },
+        [&](double x) {
+            x += dpp_f64<kDppXor1>(x);
+            x += dpp_f64<kDppXor2>(x);
+            x += dpp_f64<kDppHalfMirror>(x);
+            x += dpp_f64<kDppMirror>(x);
+            if constexpr (G == 32u) {
+                const uint64_t u = (uint64_t)__double_as_longlong(x);
+                const uint32_t lo = lane_xor<16>((uint32_t)u, lane), hi = lane_xor<16>((uint32_t)(u >> 32), lane);
+                x += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+            }
+            return x;
+        });
+}
+
 // ----------------------------------------------------------------------------------------------
 // Evenly spaced levels (QSGD-s, TernGrad) for buckets of 64 or 128 elements: one wavefront takes 256 consecutive
 // elements, i.e. NB = 4 or 2 whole buckets (lane l holds elements 4l .. 4l+3, bucket l / G of the wavefront with
 // G = 64 / NB lanes per bucket), instead of leaving three quarters or half of its lanes idle.  The only statistic of
 // the rule, the largest magnitude, is reduced inside each group of G lanes; every lane then holds the levels of its
-// own bucket, which is all the encoder needs.  No clipping here.
+// own bucket, which is all the encoder needs.
 // ----------------------------------------------------------------------------------------------
 template <int S, int BITS, int NB, bool FULL>
 __device__ __forceinline__ void even_small_span(const float* __restrict__ g, uint32_t len, size_t begin, uint32_t first_bucket,
-                                                uint64_t seed, uint64_t index_offset, float* __restrict__ levels,
-                                                uint32_t* __restrict__ codes32)
+                                                float clip, uint64_t seed, uint64_t index_offset,
+                                                float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
     constexpr uint32_t G = 64u / NB;           // lanes per bucket
     constexpr uint32_t D = 256u / NB;          // elements per bucket
@@ -1071,6 +1096,7 @@ __device__ __forceinline__ void even_small_span(const float* __restrict__ g, uin
 #pragma unroll
         for (int k = 0; k < 4; ++k) v[0][k] = 4u * lane + k < len ? g[4u * lane + k] : 0.0f;
     }
+    if (clip > 0.0f) clip_small_buckets<NB, FULL>(v[0], len, clip, lane);
     // largest magnitude of the lane's bucket (padding holds 0)
     uint32_t mag = 0;
 #pragma unroll
@@ -1093,9 +1119,9 @@ __device__ __forceinline__ void even_small_span(const float* __restrict__ g, uin
 }
 
 template <int S, int BITS, int NB>
-__global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __restrict__ grad, size_t n, uint64_t seed,
-                                                               uint64_t index_offset, float* __restrict__ levels,
-                                                               uint32_t* __restrict__ codes32)
+__global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __restrict__ grad, size_t n, float clip,
+                                                               uint64_t seed, uint64_t index_offset,
+                                                               float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
     const size_t span = (size_t)blockIdx.x * 4u + (threadIdx.x >> 6);  // 256 elements each
     const size_t begin = span * 256u;
@@ -1103,9 +1129,10 @@ __global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __re
     const size_t rest = n - begin;
     const uint32_t first_bucket = (uint32_t)(span * NB);
     if (rest >= 256u)
-        even_small_span<S, BITS, NB, true>(grad + begin, 256u, begin, first_bucket, seed, index_offset, levels, codes32);
+        even_small_span<S, BITS, NB, true>(grad + begin, 256u, begin, first_bucket, clip, seed, index_offset, levels, codes32);
     else
-        even_small_span<S, BITS, NB, false>(grad + begin, (uint32_t)rest, begin, first_bucket, seed, index_offset, levels, codes32);
+        even_small_span<S, BITS, NB, false>(grad + begin, (uint32_t)rest, begin, first_bucket, clip, seed, index_offset, levels,
+                                            codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1119,7 +1146,7 @@ __global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __re
 // alone (sweeps repeat it unchanged); with more, every lane keeps the level records of its bucket and the solves of
 // all buckets of the wavefront run side by side.  Two levels are the extremes and need no sort.  BinGrad-pb's level
 // is the positive value at the sign change of its condition, which every element evaluates for itself from the
-// exclusive fp64 prefix of the sorted values.  No clipping here.
+// exclusive fp64 prefix of the sorted values.
 // ----------------------------------------------------------------------------------------------
 constexpr int kDppQuadReverse = 0x1B;  // quad_perm [3,2,1,0]: partner lane ^ 3
 
@@ -1310,7 +1337,7 @@ __device__ __forceinline__ void for_sweep_levels(Solve&& solve)
 
 template <int S, int BITS, int NB, bool FULL, int RULE>
 __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, uint32_t len, size_t begin, uint32_t first_bucket,
-                                                  uint32_t sweeps, uint64_t seed, uint64_t index_offset,
+                                                  uint32_t sweeps, float clip, uint64_t seed, uint64_t index_offset,
                                                   float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
     static_assert(RULE == kLinear || RULE == kOptimal || (RULE == kPb && S == 2), "rules that read order statistics");
@@ -1327,6 +1354,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
 #pragma unroll
         for (int k = 0; k < 4; ++k) v[0][k] = 4u * lane + k < len ? g[4u * lane + k] : 0.0f;
     }
+    if (clip > 0.0f) clip_small_buckets<NB, FULL>(v[0], len, clip, lane);
     const uint32_t q = lane / G;  // bucket of this lane inside the wavefront
     uint32_t count = D;           // elements of that bucket (the gradient may end inside or before it)
     if constexpr (!FULL) count = q * D < len ? (len - q * D < D ? len - q * D : D) : 0u;
@@ -1511,7 +1539,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
 
 template <int S, int BITS, int NB, int RULE>
 __global__ __launch_bounds__(4 * kWave) void sorted_small_kernel(const float* __restrict__ grad, size_t n, uint32_t sweeps,
-                                                                 uint64_t seed, uint64_t index_offset,
+                                                                 float clip, uint64_t seed, uint64_t index_offset,
                                                                  float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
     const size_t span = (size_t)blockIdx.x * 4u + (threadIdx.x >> 6);  // 256 elements each
@@ -1520,11 +1548,11 @@ __global__ __launch_bounds__(4 * kWave) void sorted_small_kernel(const float* __
     const size_t rest = n - begin;
     const uint32_t first_bucket = (uint32_t)(span * NB);
     if (rest >= 256u)
-        sorted_small_span<S, BITS, NB, true, RULE>(grad + begin, 256u, begin, first_bucket, sweeps, seed, index_offset, levels,
-                                                   codes32);
+        sorted_small_span<S, BITS, NB, true, RULE>(grad + begin, 256u, begin, first_bucket, sweeps, clip, seed, index_offset,
+                                                   levels, codes32);
     else
-        sorted_small_span<S, BITS, NB, false, RULE>(grad + begin, (uint32_t)rest, begin, first_bucket, sweeps, seed, index_offset,
-                                                    levels, codes32);
+        sorted_small_span<S, BITS, NB, false, RULE>(grad + begin, (uint32_t)rest, begin, first_bucket, sweeps, clip, seed,
+                                                    index_offset, levels, codes32);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1828,11 +1856,11 @@ void launch_even_small(const float* g, size_t n, const ogq_params_t* p, float* l
     const size_t spans = (n + 255u) / 256u;
     const dim3 grid((uint32_t)((spans + 3u) / 4u)), block(4 * kWave);
     if (p->bucket_size == 64u)
-        hipLaunchKernelGGL((even_small_kernel<S, BITS, 4>), grid, block, 0, st, g, n, p->seed, p->index_offset, lv,
-                           static_cast<uint32_t*>(codes));
+        hipLaunchKernelGGL((even_small_kernel<S, BITS, 4>), grid, block, 0, st, g, n, p->clip_factor, p->seed, p->index_offset,
+                           lv, static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((even_small_kernel<S, BITS, 2>), grid, block, 0, st, g, n, p->seed, p->index_offset, lv,
-                           static_cast<uint32_t*>(codes));
+        hipLaunchKernelGGL((even_small_kernel<S, BITS, 2>), grid, block, 0, st, g, n, p->clip_factor, p->seed, p->index_offset,
+                           lv, static_cast<uint32_t*>(codes));
 }
 
 template <int S, int BITS, int RULE>
@@ -1841,11 +1869,11 @@ void launch_sorted_small(const float* g, size_t n, const ogq_params_t* p, float*
     const size_t spans = (n + 255u) / 256u;
     const dim3 grid((uint32_t)((spans + 3u) / 4u)), block(4 * kWave);
     if (p->bucket_size == 64u)
-        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 4, RULE>), grid, block, 0, st, g, n, p->level_iters, p->seed,
-                           p->index_offset, lv, static_cast<uint32_t*>(codes));
+        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 4, RULE>), grid, block, 0, st, g, n, p->level_iters, p->clip_factor,
+                           p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 2, RULE>), grid, block, 0, st, g, n, p->level_iters, p->seed,
-                           p->index_offset, lv, static_cast<uint32_t*>(codes));
+        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 2, RULE>), grid, block, 0, st, g, n, p->level_iters, p->clip_factor,
+                           p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
 }
 
 template <int C, int RULE>
@@ -1853,8 +1881,8 @@ void launch_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32
                          hipStream_t st)
 {
     if constexpr (C == 1 && (RULE == kOptimal || RULE == kLinear)) {
-        // buckets of 64 and 128 elements without clipping, sorted in registers, several per wavefront
-        if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+        // buckets of 64 and 128 elements, sorted in registers, several per wavefront
+        if (p->bucket_size == 64u || p->bucket_size == 128u) {
             switch (p->bits) {
                 case 2: launch_sorted_small<3, 2, RULE>(g, n, p, lv, codes, st); break;
                 case 3: launch_sorted_small<5, 3, RULE>(g, n, p, lv, codes, st); break;
@@ -1864,8 +1892,8 @@ void launch_paper_counts(const float* g, size_t n, const ogq_params_t* p, uint32
         }
     }
     if constexpr (C == 1 && RULE == kEven) {
-        // buckets of 64 and 128 elements without clipping: several buckets per wavefront
-        if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+        // buckets of 64 and 128 elements: several buckets per wavefront
+        if (p->bucket_size == 64u || p->bucket_size == 128u) {
             switch (p->bits) {
                 case 2: launch_even_small<3, 2>(g, n, p, lv, codes, st); break;
                 case 3: launch_even_small<5, 3>(g, n, p, lv, codes, st); break;
@@ -1888,7 +1916,7 @@ void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t
     switch (p->scheme) {
         case OGQ_BINGRAD_PB:
             if constexpr (C == 1) {
-                if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+                if (p->bucket_size == 64u || p->bucket_size == 128u) {
                     launch_sorted_small<2, 1, kPb>(g, n, p, lv, codes, st);
                     break;
                 }
@@ -1897,8 +1925,8 @@ void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t
             break;
         case OGQ_ORQ:
             if constexpr (C == 1) {
-                // buckets of 64 and 128 elements without clipping, sorted in registers, several per wavefront
-                if (p->clip_factor == 0.0f && (p->bucket_size == 64u || p->bucket_size == 128u)) {
+                // buckets of 64 and 128 elements, sorted in registers, several per wavefront
+                if (p->bucket_size == 64u || p->bucket_size == 128u) {
                     if (p->bits == 1) launch_sorted_small<2, 1, kOptimal>(g, n, p, lv, codes, st);
                     else if (p->bits == 2) launch_sorted_small<4, 2, kOptimal>(g, n, p, lv, codes, st);
                     else launch_sorted_small<8, 3, kOptimal>(g, n, p, lv, codes, st);
