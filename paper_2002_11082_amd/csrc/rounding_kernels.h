@@ -1175,17 +1175,27 @@ __device__ __forceinline__ void sort_pair(uint32_t& a, uint32_t& b)
     b = mx;
 }
 
+// Median of three (v_med3_u32): with bound = 0 the smaller, with bound = 0xFFFFFFFF the larger of x and y.
+__device__ __forceinline__ uint32_t smaller_or_larger(uint32_t x, uint32_t y, uint32_t bound)
+{
+    return umax32(umin32(x, y), umin32(umax32(x, y), bound));
+}
+
+// 0 in the lanes whose bit BIT is clear (they keep the smaller key of a pair), 0xFFFFFFFF in the others.
+template <int BIT>
+__device__ __forceinline__ uint32_t upper_lanes(uint32_t lane)
+{
+    return (lane & (uint32_t)BIT) ? 0xFFFFFFFFu : 0u;
+}
+
 // The steps of a merge that pair lanes J apart (J = M / 2 ... 1), register by register.
 template <int J>
 __device__ __forceinline__ void row_sort_across(uint32_t (&x)[4], uint32_t lane)
 {
     if constexpr (J >= 1) {
-        const bool lower = (lane & (uint32_t)J) == 0;
+        const uint32_t bound = upper_lanes<J>(lane);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t y = lane_xor<J>(x[r], lane);
-            x[r] = lower ? umin32(x[r], y) : umax32(x[r], y);
-        }
+        for (int r = 0; r < 4; ++r) x[r] = smaller_or_larger(x[r], lane_xor<J>(x[r], lane), bound);
         row_sort_across<J / 2>(x, lane);
     }
 }
@@ -1195,12 +1205,12 @@ template <int M, int G>
 __device__ __forceinline__ void row_sort_merge(uint32_t (&x)[4], uint32_t lane)
 {
     if constexpr (2 * M <= G) {
-        const bool lower = (lane & (uint32_t)M) == 0;
+        const uint32_t bound = upper_lanes<M>(lane);
         uint32_t y[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) y[r] = lane_reverse<M>(x[3 - r], lane);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) x[r] = lower ? umin32(x[r], y[r]) : umax32(x[r], y[r]);
+        for (int r = 0; r < 4; ++r) x[r] = smaller_or_larger(x[r], y[r], bound);
         row_sort_across<M / 2>(x, lane);
         sort_pair(x[0], x[2]);
         sort_pair(x[1], x[3]);
