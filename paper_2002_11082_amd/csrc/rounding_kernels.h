@@ -182,34 +182,71 @@ __device__ __forceinline__ double wave_inclusive_scan_f64(double x)
     return x;
 }
 
-// Ascending bitonic sort of one key per lane across the 64 lanes.
-template <int K, int DIST>
-__device__ __forceinline__ uint32_t bitonic_step(uint32_t x, uint32_t lane)
+// Ascending bitonic sorts in registers.  Every compare-exchange is ascending: the first step of a merge pairs
+// element e with e ^ (run length - 1), i.e. meets the second run in reverse, the others pair e with e ^ J; the lane
+// whose bit (run length / 2, or J) is clear keeps the smaller key.  So no step needs a direction, a step is one
+// cross-lane move and one median of three, and every row of 16 lanes (half of the wavefront) is sorted ascending
+// on its own after 10 (15) of the 21 steps.
+constexpr int kDppQuadReverse = 0x1B;  // quad_perm [3,2,1,0]: partner lane ^ 3
+
+// Value held by lane (lane ^ (2 M - 1)): every group of 2 M lanes in reverse order.
+template <int M>
+__device__ __forceinline__ uint32_t lane_reverse(uint32_t x, uint32_t lane)
 {
-    const uint32_t y = lane_xor<DIST>(x, lane);
-    const bool ascending = (lane & (uint32_t)K) == 0;
-    const bool lower = (lane & (uint32_t)DIST) == 0;
-    const uint32_t mn = umin32(x, y), mx = umax32(x, y);
-    return (ascending == lower) ? mn : mx;
+    if constexpr (M == 1) {
+        return dpp_u32<kDppXor1>(x);
+    } else if constexpr (M == 2) {
+        return dpp_u32<kDppQuadReverse>(x);
+    } else if constexpr (M == 4) {
+        return dpp_u32<kDppHalfMirror>(x);
+    } else if constexpr (M == 8) {
+        return dpp_u32<kDppMirror>(x);
+    } else if constexpr (M == 16) {
+        return lane_xor<16>(dpp_u32<kDppMirror>(x), lane);
+    } else {
+        static_assert(M == 32, "groups of at most 64 lanes");
+        return lane_xor<32>(lane_xor<16>(dpp_u32<kDppMirror>(x), lane), lane);
+    }
+}
+
+// Median of three (v_med3_u32): with bound = 0 the smaller, with bound = 0xFFFFFFFF the larger of x and y.
+__device__ __forceinline__ uint32_t smaller_or_larger(uint32_t x, uint32_t y, uint32_t bound)
+{
+    return umax32(umin32(x, y), umin32(umax32(x, y), bound));
+}
+
+// 0 in the lanes whose bit BIT is clear (they keep the smaller key of a pair), 0xFFFFFFFF in the others.
+template <int BIT>
+__device__ __forceinline__ uint32_t upper_lanes(uint32_t lane)
+{
+    return (lane & (uint32_t)BIT) ? 0xFFFFFFFFu : 0u;
+}
+
+// One key per lane: merges sorted runs of M lanes into runs of 2 M.
+template <int M>
+__device__ __forceinline__ uint32_t wave_sort_merge(uint32_t x, uint32_t lane)
+{
+    x = smaller_or_larger(x, lane_reverse<M>(x, lane), upper_lanes<M>(lane));
+    if constexpr (M >= 32) x = smaller_or_larger(x, lane_xor<16>(x, lane), upper_lanes<16>(lane));
+    if constexpr (M >= 16) x = smaller_or_larger(x, lane_xor<8>(x, lane), upper_lanes<8>(lane));
+    if constexpr (M >= 8) x = smaller_or_larger(x, lane_xor<4>(x, lane), upper_lanes<4>(lane));
+    if constexpr (M >= 4) x = smaller_or_larger(x, lane_xor<2>(x, lane), upper_lanes<2>(lane));
+    if constexpr (M >= 2) x = smaller_or_larger(x, lane_xor<1>(x, lane), upper_lanes<1>(lane));
+    return x;
 }
 
 // `count` lanes (the first ones) hold keys, the others 0xFFFFFFFF: with at most 16 (32) keys only the first
-// row (half) of the wavefront has to be sorted, which ends the network after 10 (15) of its 21 steps; the
-// direction of the last merge is ascending in the first row (half) either way.
+// row (half) of the wavefront has to be sorted.
 __device__ __forceinline__ uint32_t wave_sort_u32(uint32_t x, uint32_t lane, uint32_t count)
 {
-    x = bitonic_step<2, 1>(x, lane);
-    x = bitonic_step<4, 2>(x, lane);   x = bitonic_step<4, 1>(x, lane);
-    x = bitonic_step<8, 4>(x, lane);   x = bitonic_step<8, 2>(x, lane);   x = bitonic_step<8, 1>(x, lane);
-    x = bitonic_step<16, 8>(x, lane);  x = bitonic_step<16, 4>(x, lane);  x = bitonic_step<16, 2>(x, lane);
-    x = bitonic_step<16, 1>(x, lane);
+    x = wave_sort_merge<1>(x, lane);
+    x = wave_sort_merge<2>(x, lane);
+    x = wave_sort_merge<4>(x, lane);
+    x = wave_sort_merge<8>(x, lane);
     if (count <= 16u) return x;
-    x = bitonic_step<32, 16>(x, lane); x = bitonic_step<32, 8>(x, lane);  x = bitonic_step<32, 4>(x, lane);
-    x = bitonic_step<32, 2>(x, lane);  x = bitonic_step<32, 1>(x, lane);
+    x = wave_sort_merge<16>(x, lane);
     if (count <= 32u) return x;
-    x = bitonic_step<64, 32>(x, lane); x = bitonic_step<64, 16>(x, lane); x = bitonic_step<64, 8>(x, lane);
-    x = bitonic_step<64, 4>(x, lane);  x = bitonic_step<64, 2>(x, lane);  x = bitonic_step<64, 1>(x, lane);
-    return x;
+    return wave_sort_merge<32>(x, lane);
 }
 
 // The bucket element of a given rank, with the counts and sums of the bucket elements strictly
@@ -1148,44 +1185,11 @@ __global__ __launch_bounds__(4 * kWave) void even_small_kernel(const float* __re
 // is the positive value at the sign change of its condition, which every element evaluates for itself from the
 // exclusive fp64 prefix of the sorted values.
 // ----------------------------------------------------------------------------------------------
-constexpr int kDppQuadReverse = 0x1B;  // quad_perm [3,2,1,0]: partner lane ^ 3
-
-// Value held by lane (lane ^ (2 M - 1)): every group of 2 M lanes in reverse order.
-template <int M>
-__device__ __forceinline__ uint32_t lane_reverse(uint32_t x, uint32_t lane)
-{
-    if constexpr (M == 1) {
-        return dpp_u32<kDppXor1>(x);
-    } else if constexpr (M == 2) {
-        return dpp_u32<kDppQuadReverse>(x);
-    } else if constexpr (M == 4) {
-        return dpp_u32<kDppHalfMirror>(x);
-    } else if constexpr (M == 8) {
-        return dpp_u32<kDppMirror>(x);
-    } else {
-        static_assert(M == 16, "groups of at most 32 lanes");
-        return lane_xor<16>(dpp_u32<kDppMirror>(x), lane);
-    }
-}
-
 __device__ __forceinline__ void sort_pair(uint32_t& a, uint32_t& b)
 {
     const uint32_t mn = umin32(a, b), mx = umax32(a, b);
     a = mn;
     b = mx;
-}
-
-// Median of three (v_med3_u32): with bound = 0 the smaller, with bound = 0xFFFFFFFF the larger of x and y.
-__device__ __forceinline__ uint32_t smaller_or_larger(uint32_t x, uint32_t y, uint32_t bound)
-{
-    return umax32(umin32(x, y), umin32(umax32(x, y), bound));
-}
-
-// 0 in the lanes whose bit BIT is clear (they keep the smaller key of a pair), 0xFFFFFFFF in the others.
-template <int BIT>
-__device__ __forceinline__ uint32_t upper_lanes(uint32_t lane)
-{
-    return (lane & (uint32_t)BIT) ? 0xFFFFFFFFu : 0u;
 }
 
 // The steps of a merge that pair lanes J apart (J = M / 2 ... 1), register by register.
