@@ -159,7 +159,7 @@ const char* ogq_strerror(int status)
     switch (status) {
         case OGQ_OK: return "ok";
         case OGQ_ERR_NULL_POINTER: return "a required pointer is NULL";
-        case OGQ_ERR_BUCKET_SIZE: return "bucket_size must be a multiple of 64 in [64, 4096]";
+        case OGQ_ERR_BUCKET_SIZE: return "bucket_size must be a multiple of 64 in [64, 32768]";
         case OGQ_ERR_BITS: return "bits not supported by the scheme (BinGrad-b / -pb: 1, ORQ: 1..3, ORQ_PAPER: 2..4)";
         case OGQ_ERR_SCHEME: return "unknown scheme";
         case OGQ_ERR_NUM_WORKERS: return "num_workers must be in [1, 64]";
