@@ -105,6 +105,7 @@ struct OrqLds {
     uint32_t lvl_count_lt[S_];
     uint32_t lvl_count_le[S_];
     uint32_t lvl_rank[S_];
+    double cancel_bound;  // what rounding can add to a difference of two prefix sums: 2^-44 * len * largest magnitude
 };
 
 __device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 6); }
@@ -550,7 +551,19 @@ __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k,
     if (!copy_left) {
         // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
         const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
-        const double T = Ssum / ((double)R - (double)L);
+        const double width = (double)R - (double)L;
+        double T = Ssum / width;
+        // The prefix sums cancel in S.  Where T is an integer within what their rounding can add (exactly an integer,
+        // for one, when every element above L up to R equals R), S is summed again term by term, which is exact
+        // whenever the terms are few or alike, and floor(T) is taken from that.
+        if (fabs(Ssum - rint(T) * width) <= uniform_f64(lds.cancel_bound)) {
+            double part = 0.0;
+            for (uint32_t i = lane; i < len; i += kWave) {
+                const float x = __uint_as_float(lds.grouped[skewed(i)]);
+                part += (L <= x && x <= R) ? (double)x - (double)L : 0.0;
+            }
+            T = wave_sum(part) / width;
+        }
         double m = floor(T);
         if (!(m >= 0.0)) m = 0.0;
         rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
@@ -1022,6 +1035,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
             }
         }
         if (lane == 0u) {
+            lds.cancel_bound = 0x1p-44 * (double)len * (double)__uint_as_float(mag_max);
             // the bottom level is only ever the left end of a solve
             lds.lvl_count_lt[0] = 0u;
             lds.lvl_sum_lt[0] = 0.0;
@@ -1484,6 +1498,7 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
                 st.rank[k] = 0u;
             }
             const uint32_t count_or_one = count > 0u ? count : 1u;
+            const double cancel_bound = 0x1p-44 * (double)count * (double)fmaxf(fabsf(lv[0]), fabsf(lv[S - 1]));
             auto solve = [&](auto kc, auto lc, auto rc) {
                 constexpr int k = decltype(kc)::value, l = decltype(lc)::value, r = decltype(rc)::value;
                 const float L = st.value[l], R = st.value[r];
@@ -1492,7 +1507,20 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
                 const bool ordered = L < R;
                 // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
                 const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
-                const double T = Ssum / ((double)R - (double)L);  // not used when L == R
+                const double width = (double)R - (double)L;
+                double T = Ssum / width;  // not used when L == R
+                // (as in orq_solve_one: an integer T within the rounding of the cancelling prefix sums is summed directly)
+                const bool cancelled = ordered && fabs(Ssum - rint(T) * width) <= cancel_bound;
+                if (__ballot(cancelled) != 0) {
+                    double part = 0.0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float value = key_to_float(x[i]);
+                        part += (l4 + i < count && L <= value && value <= R) ? (double)value - (double)L : 0.0;
+                    }
+                    const double direct = row_sum_f64<(int)G>(part, lane) / width;
+                    T = cancelled ? direct : T;
+                }
                 double m = floor(T);
                 if (!(m >= 0.0)) m = 0.0;
                 const bool whole = m >= (double)cnt_le_R;
@@ -1534,7 +1562,19 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
             // S = sum (v - L) over the bucket, T = S / (R - L), level = element of rank #{v <= R} - floor(T)
             const double total = row_sum_f64<(int)G>(part, lane);
             const float L = lv[0], R = lv[2];
-            const double T = (total - (double)L * (double)count) / ((double)R - (double)L);  // not used when L == R
+            const double Ssum = total - (double)L * (double)count, width = (double)R - (double)L;
+            double T = Ssum / width;  // not used when L == R
+            // (as in orq_solve_one: an integer T within the rounding of the cancelling sums is summed directly)
+            const bool cancelled =
+                L < R && fabs(Ssum - rint(T) * width) <= 0x1p-44 * (double)count * (double)fmaxf(fabsf(L), fabsf(R));
+            if (__ballot(cancelled) != 0) {
+                double direct = 0.0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    direct += 4u * (lane & (G - 1u)) + i < count ? (double)key_to_float(x[i]) - (double)L : 0.0;
+                direct = row_sum_f64<(int)G>(direct, lane) / width;
+                T = cancelled ? direct : T;
+            }
             double m = floor(T);
             if (!(m >= 0.0)) m = 0.0;
             if (m > (double)count) m = (double)count;
@@ -1592,6 +1632,7 @@ struct OrqTeamLds {
     uint32_t lvl_count_lt[10];
     uint32_t lvl_count_le[10];
     uint32_t lvl_rank[10];
+    double cancel_bound;  // what rounding can add to a difference of two prefix sums: 2^-44 * len * largest magnitude
     TeamSlot slots[2][W];
 };
 
@@ -1778,6 +1819,7 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
                 lds.lvl_sum_lt[0] = 0.0;
                 lds.lvl_count_le[0] = 0u;
                 lds.lvl_sum_le[0] = 0.0;
+                lds.cancel_bound = 0x1p-44 * (double)len * (double)__uint_as_float(mag_max);
                 lds.lvl_count_le[S - 1] = len;
                 lds.lvl_sum_le[S - 1] = total;
                 lds.lvl_count_lt[S - 1] = len;

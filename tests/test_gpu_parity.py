@@ -414,6 +414,31 @@ def test_random_value_distributions():
                               tag=f"dist-{trial}")
 
 
+def test_integer_t_where_the_prefix_sums_cancel():
+    """A level solve whose T = S / (R - L) is an integer while S, taken as a difference of prefix sums, carries their
+    rounding: floor(T) must not follow that error.  Built so that the second solve of a four-level bucket lies
+    between the second largest and the largest value (T = 1 exactly: the only element above L is R) with thousands of
+    unlike values of large magnitude below L; also the heavy-tailed buckets of a working-file search for solves whose
+    T is an integer in the oracle's arithmetic."""
+    for seed in range(40):
+        rng = np.random.default_rng(500 + seed)
+        d = int(rng.choice([128, 512, 2048, 3072, 4096, 8192]))
+        bucket = (-1.0e6 * (1.0 + 1.0e-3 * rng.random(d))).astype(np.float32)
+        bucket[rng.integers(0, d)] = np.float32(rng.uniform(1.0, 9.0))
+        where = rng.integers(0, d)
+        bucket[where] = np.float32(rng.uniform(1.0, 2.0) * 10.0 ** rng.integers(6, 31))
+        g = np.concatenate([bucket, bucket[::-1], bucket[: d // 2 + 7]])
+        for scheme, bits, sweeps in ((ogq.ORQ, 2, 0), (ogq.ORQ, 2, 2), (ogq.ORQ, 3, 1), (ogq.ORQ_PAPER, 3, 1)):
+            parity.check_quantize(g, d, bits, scheme, sweeps, seed=seed, tag=f"integer-T-built{seed}-s{scheme}b{bits}-d{d}")
+    for seed in (1, 11, 14, 41, 77, 95, 120, 122):
+        rng = np.random.default_rng(seed)
+        d = int(rng.choice([128, 512, 2048, 3072, 4096]))
+        bucket = (rng.lognormal(0, 3, d) * rng.choice([-1, 1], d)).astype(np.float32)
+        g = np.concatenate([bucket, bucket[::-1], bucket[: d // 2 + 7]])
+        for scheme, bits in ((ogq.ORQ, 3), (ogq.ORQ, 2), (ogq.ORQ_PAPER, 3)):
+            parity.check_quantize(g, d, bits, scheme, 1, seed=seed, tag=f"integer-T-seed{seed}-s{scheme}b{bits}-d{d}")
+
+
 def test_non_finite_values_stay_inside_their_bucket():
     """NaN and infinities give unspecified levels and codes for their own bucket only: every call returns, and the
     buckets without them still match the oracle (every kernel family and bucket-size class)."""
