@@ -17,8 +17,12 @@
  *     from the thread-local code read by ogq_last_hip_error().
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream)
  *     and the call returns without synchronising.
- *   - Return value: OGQ_OK (0) or a negative ogq_status_t.  On error nothing was enqueued and
- *     no output byte was written.  The library never throws and never aborts.
+ *   - Return value: OGQ_OK (0) or a negative ogq_status_t.  On an argument error (every code but
+ *     OGQ_ERR_LAUNCH) nothing was enqueued and no output byte was written.  OGQ_ERR_LAUNCH means the HIP
+ *     runtime refused a kernel launch of this call (its own return code, not the thread's sticky last
+ *     error); nothing is enqueued after the refused launch, but a call that takes two launches
+ *     (OGQ_BINGRAD_B / OGQ_SCALED_SIGN with a bucket size dividing 2048, without clipping, when n is not
+ *     a multiple of 2048) may already have enqueued its first one.  The library never throws and never aborts.
  *   - Input values must be finite.  Non-finite input gives unspecified levels and codes but no
  *     out-of-bounds access.
  *   - n == 0 is a successful no-op.
@@ -44,7 +48,8 @@ typedef enum {
     OGQ_ERR_INDEX_OFFSET = -7,  /* index_offset is not a multiple of 64 */
     OGQ_ERR_LAUNCH = -8,        /* the HIP runtime refused the launch (ogq_last_hip_error()) */
     OGQ_ERR_SIZE = -9,          /* n is too large for the 32-bit bucket grid (n/bucket_size >= 2^31) */
-    OGQ_ERR_CLIP = -10          /* clip_factor is negative or not finite */
+    OGQ_ERR_CLIP = -10,         /* clip_factor is negative or not finite */
+    OGQ_ERR_RESERVED = -11      /* the reserved field of the parameters is not 0 */
 } ogq_status_t;
 
 typedef enum {

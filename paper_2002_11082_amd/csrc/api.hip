@@ -32,6 +32,12 @@ uint32_t levels_per_bucket(uint32_t scheme, uint32_t bits)
     return 0u;
 }
 
+hipError_t& launch_status()
+{
+    static thread_local hipError_t status = hipSuccess;
+    return status;
+}
+
 }  // namespace ogq
 
 namespace {
@@ -47,6 +53,7 @@ int check_params(const ogq_params_t* p, bool quantize)
         return OGQ_ERR_BUCKET_SIZE;
     if (p->scheme > OGQ_LINEAR) return OGQ_ERR_SCHEME;
     if (ogq::levels_per_bucket(p->scheme, p->bits) == 0) return OGQ_ERR_BITS;
+    if (p->reserved != 0) return OGQ_ERR_RESERVED;
     if (quantize) {
         if (p->index_offset % 64 != 0) return OGQ_ERR_INDEX_OFFSET;
         if (!(p->clip_factor >= 0.0f) || !(p->clip_factor <= 3.0e38f)) return OGQ_ERR_CLIP;
@@ -54,9 +61,13 @@ int check_params(const ogq_params_t* p, bool quantize)
     return OGQ_OK;
 }
 
-int finish_launch()
+// Every entry point that launches calls begin_launches() before its first launch and returns finish_launches():
+// the status is the one the runtime returned for these launches, not the thread's sticky last error.
+void begin_launches() { ogq::launch_status() = hipSuccess; }
+
+int finish_launches()
 {
-    const hipError_t e = hipGetLastError();
+    const hipError_t e = ogq::launch_status();
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
         return OGQ_ERR_LAUNCH;
@@ -101,6 +112,7 @@ int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params, floa
     const uint32_t nb = (uint32_t)nb64;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const uint32_t d = params->bucket_size;
+    begin_launches();
     if (params->scheme == OGQ_BINGRAD_B || params->scheme == OGQ_SCALED_SIGN) {
         ogq::launch_two_level(d_grad, n, params, d_levels, d_codes, st);
     } else {
@@ -115,7 +127,7 @@ int ogq_quantize(const float* d_grad, size_t n, const ogq_params_t* params, floa
                                                        : ogq::launch_rounding_w8;
         launch(d_grad, n, params, nb, d_levels, d_codes, st);
     }
-    return finish_launch();
+    return finish_launches();
 }
 
 int ogq_dequantize_average(const void* const* d_codes, const float* const* d_levels, uint32_t num_workers, size_t n,
@@ -132,8 +144,9 @@ int ogq_dequantize_average(const void* const* d_codes, const float* const* d_lev
         if (!aligned(d_codes[w], 16) || !aligned(d_levels[w], 16)) return OGQ_ERR_ALIGNMENT;
     }
     if (ogq_num_buckets(n, params) >= (1ull << 31)) return OGQ_ERR_SIZE;
+    begin_launches();
     ogq::launch_decode(d_codes, d_levels, num_workers, n, params, d_out, static_cast<hipStream_t>(hip_stream));
-    return finish_launch();
+    return finish_launches();
 }
 
 int ogq_probe_read(const float* d_src, size_t n, float* d_sink, void* hip_stream)
@@ -141,8 +154,9 @@ int ogq_probe_read(const float* d_src, size_t n, float* d_sink, void* hip_stream
     if (!d_src || !d_sink) return OGQ_ERR_NULL_POINTER;
     if (!aligned(d_src, 16)) return OGQ_ERR_ALIGNMENT;
     if (n == 0) return OGQ_OK;
+    begin_launches();
     ogq::launch_probe_read(d_src, n, d_sink, static_cast<hipStream_t>(hip_stream));
-    return finish_launch();
+    return finish_launches();
 }
 
 int ogq_probe_copy(const float* d_src, float* d_dst, size_t n, void* hip_stream)
@@ -150,8 +164,9 @@ int ogq_probe_copy(const float* d_src, float* d_dst, size_t n, void* hip_stream)
     if (!d_src || !d_dst) return OGQ_ERR_NULL_POINTER;
     if (!aligned(d_src, 16) || !aligned(d_dst, 16)) return OGQ_ERR_ALIGNMENT;
     if (n == 0) return OGQ_OK;
+    begin_launches();
     ogq::launch_probe_copy(d_src, d_dst, n, static_cast<hipStream_t>(hip_stream));
-    return finish_launch();
+    return finish_launches();
 }
 
 const char* ogq_strerror(int status)
@@ -168,6 +183,7 @@ const char* ogq_strerror(int status)
         case OGQ_ERR_LAUNCH: return "HIP kernel launch failed";
         case OGQ_ERR_SIZE: return "n is too large for one call";
         case OGQ_ERR_CLIP: return "clip_factor must be finite and not negative";
+        case OGQ_ERR_RESERVED: return "the reserved field of the parameters must be 0";
         default: return "unknown status";
     }
 }

@@ -448,7 +448,7 @@ void launch_bingrad(const float* g, size_t n, const ogq_params_t* p, uint32_t nb
     const dim3 grid((nb + kBinGradWaves - 1) / kBinGradWaves), block(kWave * kBinGradWaves);
     const bool clip = p->clip_factor > 0.0f, sign = p->scheme == OGQ_SCALED_SIGN;
 #define OGQ_LAUNCH(CLIP, SIGN)                                                                                        \
-    hipLaunchKernelGGL((bingrad_quantize_kernel<E, CLIP, SIGN>), grid, block, 0, st, g, n, p->bucket_size,           \
+    launch_kernel((bingrad_quantize_kernel<E, CLIP, SIGN>), grid, block, st, g, n, p->bucket_size,           \
                        p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes))
     if (sign) {
         if (clip) OGQ_LAUNCH(true, true);
@@ -467,7 +467,7 @@ void launch_bingrad_team(const float* g, size_t n, const ogq_params_t* p, uint32
     const dim3 grid(nb), block(W * kWave);
     const bool clip = p->clip_factor > 0.0f, sign = p->scheme == OGQ_SCALED_SIGN;
 #define OGQ_LAUNCH(CLIP, SIGN)                                                                               \
-    hipLaunchKernelGGL((bingrad_team_kernel<W, E, CLIP, SIGN>), grid, block, 0, st, g, n, p->bucket_size,   \
+    launch_kernel((bingrad_team_kernel<W, E, CLIP, SIGN>), grid, block, st, g, n, p->bucket_size,   \
                        p->level_iters, p->clip_factor, nb, lv, static_cast<uint64_t*>(codes))
     if constexpr (E <= 32) {  // 64 registers of data leave no room for the clipping passes: the caller picks E = 32
         if (clip) {
@@ -487,9 +487,9 @@ void launch_bingrad_chunks_of(const float* g, uint32_t chunks, const ogq_params_
 {
     const dim3 grid((chunks + kBinGradWaves - 1) / kBinGradWaves), block(kWave * kBinGradWaves);
     if (p->scheme == OGQ_SCALED_SIGN)
-        hipLaunchKernelGGL((bingrad_chunk_kernel<NB, true>), grid, block, 0, st, g, chunks, p->level_iters, lv, words);
+        launch_kernel((bingrad_chunk_kernel<NB, true>), grid, block, st, g, chunks, p->level_iters, lv, words);
     else
-        hipLaunchKernelGGL((bingrad_chunk_kernel<NB, false>), grid, block, 0, st, g, chunks, p->level_iters, lv, words);
+        launch_kernel((bingrad_chunk_kernel<NB, false>), grid, block, st, g, chunks, p->level_iters, lv, words);
 }
 
 void launch_bingrad_chunks(const float* g, uint32_t chunks, const ogq_params_t* p, float* lv, void* codes, hipStream_t st)

@@ -246,7 +246,7 @@ void launch_decode(const void* const* d_codes, const float* const* d_levels, uin
     const uint32_t span_elements = kSpanWords * 64;
     const uint32_t fixed_wpb = d % span_elements == 0 ? (uint32_t)kSpanWords : (span_elements % d == 0 ? wpb : 0u);
 #define OGQ_LAUNCH_DEQUANT_WPB(BITS, S, WPB)                                                                      \
-    hipLaunchKernelGGL((dequantize_average_kernel<BITS, S, WPB>), grid, block, 0, st, ptrs, num_workers, n, wpb, \
+    launch_kernel((dequantize_average_kernel<BITS, S, WPB>), grid, block, st, ptrs, num_workers, n, wpb, \
                        total_words, inv, d_out)
 #define OGQ_LAUNCH_DEQUANT(BITS, S)                                \
     do {                                                           \
@@ -273,13 +273,13 @@ void launch_decode(const void* const* d_codes, const float* const* d_levels, uin
 
 void launch_probe_read(const float* d_src, size_t n, float* d_sink, hipStream_t st)
 {
-    hipLaunchKernelGGL(probe_read_kernel, dim3(kProbeBlocks), dim3(kBlock), 0, st,
+    launch_kernel(probe_read_kernel, dim3(kProbeBlocks), dim3(kBlock), st,
                        reinterpret_cast<const float4*>(d_src), n / 4, d_sink);
 }
 
 void launch_probe_copy(const float* d_src, float* d_dst, size_t n, hipStream_t st)
 {
-    hipLaunchKernelGGL(probe_copy_kernel, dim3(kProbeBlocks), dim3(kBlock), 0, st,
+    launch_kernel(probe_copy_kernel, dim3(kProbeBlocks), dim3(kBlock), st,
                        reinterpret_cast<const float4*>(d_src), reinterpret_cast<float4*>(d_dst), n / 4);
 }
 

@@ -1,5 +1,5 @@
 // Internal header of libogq: the host-side launchers each kernel source exports to the C ABI in api.hip.
-// A launcher only enqueues; the caller picks up launch errors with hipGetLastError.
+// A launcher only enqueues, through launch_kernel below, which keeps the status the runtime returns for that launch.
 #ifndef OGQ_LAUNCH_H
 #define OGQ_LAUNCH_H
 
@@ -7,9 +7,35 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "ogq.h"
 
 namespace ogq {
+
+// Status of the launches of the current entry-point call on this thread (api.hip clears it on entry and reads it
+// before returning).  It is the value hipLaunchKernel itself returns, so an error that some earlier call of the
+// process left in the runtime's per-thread error state is neither mistaken for ours nor cleared.
+hipError_t& launch_status();
+
+template <class... P, size_t... I>
+inline hipError_t launch_with(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, std::tuple<P...>& params,
+                              std::index_sequence<I...>)
+{
+    void* pointers[] = {static_cast<void*>(&std::get<I>(params))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, pointers, 0, st);
+}
+
+// Enqueues kernel<<<grid, block, 0, st>>>(args...).  After a failed launch the later launches of the same call are
+// left out.
+template <class... P, class... A>
+inline void launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, A&&... args)
+{
+    if (launch_status() != hipSuccess) return;
+    std::tuple<P...> params(static_cast<P>(std::forward<A>(args))...);
+    launch_status() = launch_with(kernel, grid, block, st, params, std::index_sequence_for<P...>{});
+}
 
 // Levels per bucket, 0 for a scheme / bits combination that does not exist.
 uint32_t levels_per_bucket(uint32_t scheme, uint32_t bits);

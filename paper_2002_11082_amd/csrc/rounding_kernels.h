@@ -9,6 +9,7 @@
 #include <type_traits>
 
 #include "device_common.h"
+#include "launch.h"
 
 namespace ogq {
 
@@ -1897,11 +1898,11 @@ template <int C, int S, int BITS, int RULE = kOptimal>
 void launch_orq(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
     if (p->clip_factor > 0.0f)
-        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, true, RULE>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+        launch_kernel((orq_quantize_kernel<C, S, BITS, true, RULE>), dim3(nb), dim3(kWave), st, g, n, p->bucket_size,
                            p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
                            static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((orq_quantize_kernel<C, S, BITS, false, RULE>), dim3(nb), dim3(kWave), 0, st, g, n, p->bucket_size,
+        launch_kernel((orq_quantize_kernel<C, S, BITS, false, RULE>), dim3(nb), dim3(kWave), st, g, n, p->bucket_size,
                            p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv,
                            static_cast<uint32_t*>(codes));
 }
@@ -1912,10 +1913,10 @@ void launch_even_small(const float* g, size_t n, const ogq_params_t* p, float* l
     const size_t spans = (n + 255u) / 256u;
     const dim3 grid((uint32_t)((spans + 3u) / 4u)), block(4 * kWave);
     if (p->bucket_size == 64u)
-        hipLaunchKernelGGL((even_small_kernel<S, BITS, 4>), grid, block, 0, st, g, n, p->clip_factor, p->seed, p->index_offset,
+        launch_kernel((even_small_kernel<S, BITS, 4>), grid, block, st, g, n, p->clip_factor, p->seed, p->index_offset,
                            lv, static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((even_small_kernel<S, BITS, 2>), grid, block, 0, st, g, n, p->clip_factor, p->seed, p->index_offset,
+        launch_kernel((even_small_kernel<S, BITS, 2>), grid, block, st, g, n, p->clip_factor, p->seed, p->index_offset,
                            lv, static_cast<uint32_t*>(codes));
 }
 
@@ -1925,10 +1926,10 @@ void launch_sorted_small(const float* g, size_t n, const ogq_params_t* p, float*
     const size_t spans = (n + 255u) / 256u;
     const dim3 grid((uint32_t)((spans + 3u) / 4u)), block(4 * kWave);
     if (p->bucket_size == 64u)
-        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 4, RULE>), grid, block, 0, st, g, n, p->level_iters, p->clip_factor,
+        launch_kernel((sorted_small_kernel<S, BITS, 4, RULE>), grid, block, st, g, n, p->level_iters, p->clip_factor,
                            p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
     else
-        hipLaunchKernelGGL((sorted_small_kernel<S, BITS, 2, RULE>), grid, block, 0, st, g, n, p->level_iters, p->clip_factor,
+        launch_kernel((sorted_small_kernel<S, BITS, 2, RULE>), grid, block, st, g, n, p->level_iters, p->clip_factor,
                            p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
 }
 
@@ -2005,7 +2006,7 @@ void launch_orq_levels(const float* g, size_t n, const ogq_params_t* p, uint32_t
 template <int W, int C, int S, int BITS, int RULE = kOptimal>
 void launch_orq_team(const float* g, size_t n, const ogq_params_t* p, uint32_t nb, float* lv, void* codes, hipStream_t st)
 {
-    hipLaunchKernelGGL((orq_team_kernel<W, C, S, BITS, RULE>), dim3(nb), dim3(W * kWave), 0, st, g, n, p->bucket_size,
+    launch_kernel((orq_team_kernel<W, C, S, BITS, RULE>), dim3(nb), dim3(W * kWave), st, g, n, p->bucket_size,
                        p->level_iters, p->clip_factor, nb, p->seed, p->index_offset, lv, static_cast<uint32_t*>(codes));
 }
 

@@ -102,6 +102,8 @@ def check_quantize(g: np.ndarray, bucket_size: int, bits: int, scheme: int, leve
               "code_mismatches": int(diff.size), "code_mismatches_at_boundary": excused,
               "levels_bit_equal": bool(np.array_equal(lv_g, lv_r))}
     print(f"[parity] {tag} report {report}", flush=True)
+    if buckets is None:
+        report["oracle_levels"], report["oracle_codes"] = lv_ref, codes_ref  # what the oracle computed, for reuse
     assert bad_buckets.size == 0, (tag, "levels differ in buckets", sel[bad_buckets][:10],
                                    lv_g[bad_buckets][:3], lv_r[bad_buckets][:3])
     assert diff.size == excused, (tag, "code mismatches away from a decision boundary", diff[:10])

@@ -99,8 +99,11 @@ def test_argument_validation_happens_before_any_launch(lib):
     assert d([A], [A], 100, ok, 0) == -1
     assert d([A + 8], [A], 100, ok, A) == -6
     assert d([A], [A], 100, ogq.make_params(2048, 5, ogq.ORQ), A) == -3
-    for code in range(-10, 1):
-        assert ogq.ogq_strerror(code)
+    bad = ogq.make_params(2048, 2, ogq.ORQ)
+    bad.reserved = 1                                                    # documented as "must be 0"
+    assert q(A, 100, bad, A, A) == -11 and d([A], [A], 100, bad, A) == -11
+    for code in range(-11, 1):
+        assert ogq.ogq_strerror(code) and ogq.ogq_strerror(code) != "unknown status"
     assert lib.ogq_quantize(A, 100, None, A, A, None) == -1
 
 

@@ -144,14 +144,15 @@ def test_orq_paper_level_counts_small(bits, d):
                                       tag=f"orqpaper{bits}-{kind}-d{d}-n{n}-sw{sweeps}")
 
 
-def test_orq_paper_five_levels_resnet50_size_sampled():
+def test_orq_paper_five_levels_resnet50_size():
     # ORQ-5 as in the paper's tables (bucket 2048, no clipping; and bucket 512 with clipping 2.5 as on ImageNet)
     wl = synth.WORKLOADS["cfg3"]
     g = wl.gradient()
     for d, clip in ((2048, 0.0), (512, 2.5)):
         nb = (g.size + d - 1) // d
-        lv, codes, rep = parity.check_quantize(g, d, 3, ogq.ORQ_PAPER, 0, seed=8, buckets=_sample(nb, 400, d),
-                                               clip_factor=clip, tag=f"orq5-d{d}-clip{clip}")
+        lv, codes, rep = parity.check_quantize(g, d, 3, ogq.ORQ_PAPER, 0, seed=8, clip_factor=clip,
+                                               tag=f"orq5-d{d}-clip{clip}")
+        assert rep["buckets_checked"] == nb
         params = ogq.make_params(d, 3, ogq.ORQ_PAPER)
         out = ogq.ogq_dequantize_average([codes], [lv], g.size, params)
         torch.cuda.synchronize()
@@ -210,8 +211,7 @@ def _rounding_error(x, levels):
 
 
 def test_comparison_rules_resnet50_size_and_error_ordering():
-    """The three multi-level rules at full size on one gradient (sampled buckets against the oracle, decode
-    included), and the ordering of their expected rounding errors from the device's own level tables
+    """The three multi-level rules at full size on one gradient (every bucket against the oracle, decode on a sample), and the ordering of their expected rounding errors from the device's own level tables
     (Section 5.1: ORQ has the smallest error for its number of levels)."""
     wl = synth.WORKLOADS["cfg3"]
     g = wl.gradient()
@@ -219,8 +219,8 @@ def test_comparison_rules_resnet50_size_and_error_ordering():
     nb = (g.size + d - 1) // d
     tables = {}
     for scheme in (ogq.ORQ_PAPER, ogq.EVEN, ogq.LINEAR):
-        lv, codes, rep = parity.check_quantize(g, d, bits, scheme, 0, seed=21, buckets=_sample(nb, 200, scheme),
-                                               tag=f"rule{scheme}-cfg3")
+        lv, codes, rep = parity.check_quantize(g, d, bits, scheme, 0, seed=21, tag=f"rule{scheme}-cfg3")
+        assert rep["buckets_checked"] == nb
         tables[scheme] = lv[:nb * s].cpu().numpy().reshape(nb, s)
         if scheme != ogq.ORQ_PAPER:
             out = ogq.ogq_dequantize_average([codes], [lv], g.size, ogq.make_params(d, bits, scheme))
@@ -285,8 +285,8 @@ def test_buckets_above_4096(scheme, bits, d):
 
 
 def test_bucket_size_sweep_of_the_paper_at_resnet50_size():
-    """ORQ-3 and TernGrad-noclip over the bucket sizes of the paper's CIFAR-10 sweep (128 .. 32768), sampled
-    buckets against the oracle; the expected rounding error per element must grow with the bucket size for
+    """ORQ-3 and TernGrad-noclip over the bucket sizes of the paper's CIFAR-10 sweep (128 .. 32768), every
+    bucket against the oracle; the expected rounding error per element must grow with the bucket size for
     both and stay lower for ORQ-3 (the trend behind the accuracy table of Section 5.1)."""
     wl = synth.WORKLOADS["cfg3"]
     g = wl.gradient()[:8_000_000]
@@ -296,7 +296,8 @@ def test_bucket_size_sweep_of_the_paper_at_resnet50_size():
         nb = (g.size + d - 1) // d
         for scheme in err:
             picks = _sample(nb, max(8, 65536 // d), d + scheme)
-            lv, codes, rep = parity.check_quantize(g, d, 2, scheme, 0, seed=13, buckets=picks, tag=f"sweep-s{scheme}-d{d}")
+            lv, codes, rep = parity.check_quantize(g, d, 2, scheme, 0, seed=13, tag=f"sweep-s{scheme}-d{d}")
+            assert rep["buckets_checked"] == nb
             table = lv[:nb * 3].cpu().numpy().reshape(nb, 3)
             e, cnt = 0.0, 0
             for b in picks:
@@ -633,30 +634,41 @@ def test_decode_average_many_identical_workers():
 # the benchmark configurations at full size
 # ------------------------------------------------------------------------------------------------
 def _end_to_end(wl, g_list, sample_buckets):
+    """Quantize every worker's gradient, decode-average the packed streams, compare both with the oracle.
+    sample_buckets = None compares every bucket (whole-vector oracle calls); a list compares those buckets."""
     n, d, bits = g_list[0].size, wl.bucket_size, wl.bits
-    dev_levels, dev_codes, lv_ref, w_ref = [], [], [], []
+    dev_levels, dev_codes, q = [], [], []
+    nb = (n + d - 1) // d
     for w, g in enumerate(g_list):
         lv, codes, rep = parity.check_quantize(g, d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w),
-                                               buckets=sample_buckets, tag=f"{wl.name}-w{w}")
+                                               buckets=sample_buckets, tag=f"{wl.name}-w{w}", clip_factor=wl.clip_factor)
+        assert rep["buckets_checked"] == (nb if sample_buckets is None else len(set(sample_buckets)))
         dev_levels.append(lv)
         dev_codes.append(codes)
+        if sample_buckets is None:  # the oracle's own levels and packed words of this worker
+            q.append((rep["oracle_levels"], oracle.pack(rep["oracle_codes"], bits)))
     params = ogq.make_params(d, bits, wl.scheme)
+    stride = ogq.ogq_levels_per_bucket(params)
     out = ogq.ogq_dequantize_average(dev_codes, dev_levels, n, params)
     torch.cuda.synchronize()
     out = out.cpu().numpy()
-    # expected average on the sampled buckets, from oracle streams only
-    nb = (n + d - 1) // d
-    sel = range(nb) if sample_buckets is None else sorted(set(sample_buckets))
+    if sample_buckets is None:
+        # expected average of the whole vector, from oracle streams only
+        ref = oracle.dequantize_average([x[1] for x in q], [x[0] for x in q], n, d, bits, stride)
+        scale = parity.term_scale([x[0] for x in q], [x[1] for x in q], n, d, bits, stride)
+        parity.check_average(out, ref, scale, tag=f"{wl.name}-all-{nb}-buckets")
+        return
+    sel = sorted(set(sample_buckets))
     for b in sel:
         lo, hi = b * d, min((b + 1) * d, n)
-        q = [oracle.quantize(g[lo:hi], d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w), lo)
+        q = [oracle.quantize(g[lo:hi], d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w), lo, wl.clip_factor)
              for w, g in enumerate(g_list)]
-        ref = oracle.dequantize_average([x[1] for x in q], [x[0] for x in q], hi - lo, d, bits)
-        scale = parity.term_scale([x[0] for x in q], [x[1] for x in q], hi - lo, d, bits)
+        ref = oracle.dequantize_average([x[1] for x in q], [x[0] for x in q], hi - lo, d, bits, stride)
+        scale = parity.term_scale([x[0] for x in q], [x[1] for x in q], hi - lo, d, bits, stride)
         denom = np.maximum(np.abs(ref.astype(np.float64)), scale)
         err = np.abs(out[lo:hi].astype(np.float64) - ref.astype(np.float64))
         assert np.all(err <= parity.AVG_RTOL * denom), (wl.name, b, np.flatnonzero(err > parity.AVG_RTOL * denom)[:5])
-    print(f"[parity] {wl.name} decode-average checked on {len(list(sel))} buckets", flush=True)
+    print(f"[parity] {wl.name} decode-average checked on {len(sel)} buckets", flush=True)
 
 
 def _sample(nb, count, seed):
@@ -673,27 +685,37 @@ def test_cfg1_bingrad_1m_full_compare():
 
 def test_cfg2_bingrad_resnet50_size():
     wl = synth.WORKLOADS["cfg2"]
-    g = wl.gradient()
-    # every bucket's levels and codes are compared; the decode on a sample
-    parity.check_quantize(g, wl.bucket_size, wl.bits, wl.scheme, wl.level_iters, tag="cfg2-all")
-    _end_to_end(wl, [g], _sample(12500, 300, 1))
+    _end_to_end(wl, [wl.gradient()], None)
 
 
 def test_cfg3_orq2_mixture():
+    """Every one of the 12,500 buckets: levels, codes and the decoded average."""
     wl = synth.WORKLOADS["cfg3"]
-    g = wl.gradient()
-    _end_to_end(wl, [g], _sample(12500, 1500, 2))
+    _end_to_end(wl, [wl.gradient()], None)
 
 
 def test_cfg4_orq3_vgg19_shape():
+    """Every one of the 35,084 buckets (the last one holds 32 elements)."""
     wl = synth.WORKLOADS["cfg4"]
-    g = wl.gradient()
-    nb = (wl.n + wl.bucket_size - 1) // wl.bucket_size
-    _end_to_end(wl, [g], _sample(nb, 600, 3))
+    _end_to_end(wl, [wl.gradient()], None)
 
 
 def test_cfg5_eight_workers_decode_average():
+    """Every one of the 8 x 29,834 buckets, and the average of the eight decoded streams."""
     wl = synth.WORKLOADS["cfg5"]
-    gs = [wl.gradient(w) for w in range(wl.workers)]
+    _end_to_end(wl, [wl.gradient(w) for w in range(wl.workers)], None)
+
+
+@pytest.mark.parametrize("name", ["orq5", "orq3clip", "tern3", "linear5", "orq3d32k", "orq3d128", "sign2", "cfg2clip", "bin512"])
+def test_further_bench_workloads_every_bucket(name):
+    """The other workloads bench.py knows, whose oracle is linear in the bucket size: every bucket of the gradient."""
+    wl = synth.WORKLOADS[name]
+    _end_to_end(wl, [wl.gradient(w) for w in range(wl.workers)], None)
+
+
+def test_pb2_bench_workload_sampled():
+    """BinGrad-pb on the ResNet-50-sized gradient.  The oracle's level search is quadratic in the bucket size
+    (every positive value is tried against a full pass over the bucket), so 400 of the 12,500 buckets are compared."""
+    wl = synth.WORKLOADS["pb2"]
     nb = (wl.n + wl.bucket_size - 1) // wl.bucket_size
-    _end_to_end(wl, gs, _sample(nb, 250, 5))
+    _end_to_end(wl, [wl.gradient()], _sample(nb, 400, 6))
