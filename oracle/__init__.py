@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.ogq_oracle_bingrad_pb_level.restype = ctypes.c_float
         L.ogq_oracle_qstar.argtypes = [vp, sz, ctypes.c_float, ctypes.c_float]
         L.ogq_oracle_qstar.restype = ctypes.c_float
+        L.ogq_oracle_exact_sign.argtypes = [vp, vp, sz]
+        L.ogq_oracle_exact_sign.restype = ctypes.c_int
         L.ogq_oracle_orq_levels_bucket.argtypes = [vp, sz, u32, u32, vp]
         L.ogq_oracle_orq_levels_bucket.restype = None
         L.ogq_oracle_scaled_sign_bucket.argtypes = [vp, sz, vp]
@@ -125,6 +127,14 @@ def bingrad_pb_level(g) -> np.float32:
 def qstar(sorted_x, L, R) -> np.float32:
     x = _f32(sorted_x)
     return np.float32(lib().ogq_oracle_qstar(_ptr(x), x.size, float(np.float32(L)), float(np.float32(R))))
+
+
+def exact_sign(values, coefficients) -> int:
+    """Sign (-1, 0, +1) of sum_i coefficients[i] * values[i], exactly; |coefficient| < 2^20."""
+    v = _f32(values)
+    c = np.ascontiguousarray(coefficients, dtype=np.int64)
+    assert v.shape == c.shape and v.ndim == 1
+    return int(lib().ogq_oracle_exact_sign(_ptr(v), _ptr(c), v.size))
 
 
 def orq_levels_bucket(g, s: int, sweeps: int = 0) -> np.ndarray:

@@ -8,11 +8,14 @@
  *
  * Source: "Optimal Gradient Quantization Condition for Communication-Efficient Distributed
  * Training" (Xu, Huo, Huang; arXiv 2002.11082).  Each function names the passage it follows.
- * Arithmetic is double precision over the fp32 inputs, except the stochastic-rounding test,
- * which decides an integer code and is therefore taken in fp32 exactly as the device takes it.
+ * Arithmetic is double precision over the fp32 inputs, except (a) the stochastic-rounding test,
+ * which decides an integer code and is therefore taken in fp32 exactly as the device takes it, and
+ * (b) the floor of the right-hand side of the discrete optimal condition, which decides which
+ * bucket element becomes a level and is taken in exact (multi-word integer) arithmetic.
  *
- * Pins (see tests/test_oracle_*.py): Philox known-answer vectors; Q* against exhaustive
- * minimisation of the discrete rounding error in exact rationals; s=3 global optimum; sweeps
+ * Pins (see tests/test_oracle_*.py): Philox known-answer vectors; the exact sums against Python's
+ * rationals; Q* against exhaustive minimisation of the discrete rounding error in exact rationals
+ * and, at bucket sizes of 2048 .. 32768 elements, against floor(T) taken in exact rationals; s=3 global optimum; sweeps
  * never increase the error and end coordinate-wise optimal; uniform data gives the midpoint
  * (Remark after Theorem 1); endpoints are min/max (Corollary 1); BinGrad-b levels are the
  * conditional means, reduce to Scaled SignSGD on +-paired data and converge to 1-D 2-means;
@@ -152,6 +155,63 @@ float ogq_oracle_bingrad_pb_level(const float* g, size_t n)
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Exact sums of fp32 values with small integer coefficients.  The floor of T = S / (R - L) below
+ * decides which bucket element becomes a level, so it is taken in exact arithmetic: every fp32
+ * value is an integer multiple of 2^-149, and a sum  c_1 v_1 + c_2 v_2 + ...  with |c_i| < 2^20 is
+ * held as a signed fixed-point number in limbs of 32 bits (each limb an int64, so that tens of
+ * thousands of partial products can be added before carries are propagated).
+ *     value = sum_i limb[i] * 2^(32 i - 149)
+ * ---------------------------------------------------------------------------------------- */
+enum { EXACT_LIMBS = 12 };  /* 278 bits for |v| < 2^129 as multiples of 2^-149, 20 bits for the coefficient */
+typedef struct { int64_t limb[EXACT_LIMBS]; } exact_sum_t;
+
+static void exact_clear(exact_sum_t* a) { memset(a->limb, 0, sizeof a->limb); }
+
+/* a += c * v */
+static void exact_add(exact_sum_t* a, float v, int64_t c)
+{
+    uint32_t bits;
+    memcpy(&bits, &v, sizeof bits);
+    uint32_t biased = (bits >> 23) & 0xFFu, fraction = bits & 0x7FFFFFu;
+    /* |v| = mantissa * 2^(position - 149): subnormals have position 0 and no hidden bit */
+    uint64_t mantissa = biased ? (fraction | 0x800000u) : fraction;
+    uint32_t position = biased ? biased - 1u : 0u;
+    int negative = ((bits >> 31) != 0) != (c < 0);
+    uint64_t magnitude = mantissa * (uint64_t)(c < 0 ? -c : c);         /* < 2^44 */
+    unsigned __int128 shifted = (unsigned __int128)magnitude << (position % 32u);  /* < 2^76 */
+    uint32_t first = position / 32u;                                   /* <= 7, so first + 2 < EXACT_LIMBS */
+    for (int k = 0; k < 3; ++k) {
+        int64_t piece = (int64_t)(uint32_t)(shifted >> (32 * k));
+        a->limb[first + k] += negative ? -piece : piece;
+    }
+}
+
+/* sign of the value: -1, 0 or +1 (carries are propagated on a copy) */
+static int exact_sign(const exact_sum_t* a)
+{
+    int64_t limb[EXACT_LIMBS];
+    int64_t carry = 0;
+    for (int i = 0; i < EXACT_LIMBS; ++i) {
+        int64_t t = a->limb[i] + carry;
+        carry = t >> 32;                  /* floor division by 2^32 (arithmetic shift) */
+        limb[i] = t - carry * 4294967296; /* in [0, 2^32) */
+    }
+    if (carry < 0) return -1;             /* what is left above the top limb carries the sign */
+    if (carry > 0) return 1;
+    for (int i = 0; i < EXACT_LIMBS; ++i) if (limb[i] != 0) return 1;
+    return 0;
+}
+
+/* Test hook for the pins: sign of sum_i coefficient[i] * value[i], exactly. */
+int ogq_oracle_exact_sign(const float* value, const int64_t* coefficient, size_t count)
+{
+    exact_sum_t a;
+    exact_clear(&a);
+    for (size_t i = 0; i < count; ++i) exact_add(&a, value[i], coefficient[i]);
+    return exact_sign(&a);
+}
+
+/* ------------------------------------------------------------------------------------------
  * ORQ: one solve of the optimal condition for the middle level of three (Theorem 1, in the
  * simplified form of the second remark and its discrete version).
  *
@@ -164,24 +224,39 @@ float ogq_oracle_bingrad_pb_level(const float* g, size_t n)
  * "count above b_k equals the right-hand side", resolved to the exact minimiser.  When the
  * slope is exactly zero on an interval every point of it is optimal; the lower end is taken.
  *
+ * T is a ratio of two sums of fp32 values, i.e. a rational number, and floor(T) = the largest
+ * integer m with S - m (R-L) >= 0 is found in exact arithmetic (the expression is
+ * sum_{L<=v<=R} v - (c - m) L - m R with c the number of elements in [L,R], and does not grow
+ * with m), so that the level does not depend on the order or precision of a floating-point sum.
+ *
  * x[0..n) must be sorted ascending.  Returns the level value.
  * ---------------------------------------------------------------------------------------- */
 float ogq_oracle_qstar(const float* x, size_t n, float L, float R)
 {
     if (!(L < R)) return L;
-    double S = 0.0;
-    size_t count_le_R = 0;
+    exact_sum_t inside_sum;
+    exact_clear(&inside_sum);
+    size_t count_le_R = 0, inside = 0;
     for (size_t t = 0; t < n; ++t) {
         if (x[t] <= R) {
             ++count_le_R;
-            if (x[t] >= L) S += (double)x[t] - (double)L;
+            if (x[t] >= L) { exact_add(&inside_sum, x[t], 1); ++inside; }
         }
     }
-    double T = S / ((double)R - (double)L);
-    double m = floor(T);                       /* how many elements may lie above b */
+    /* floor(T): m = 0 gives S >= 0, m = inside gives sum_{[L,R]} (v - R) <= 0 */
+    size_t lo = 0, hi = inside;
+    while (lo < hi) {
+        size_t mid = lo + (hi - lo + 1) / 2;
+        exact_sum_t excess = inside_sum;                          /* S - mid (R - L) */
+        exact_add(&excess, L, -(int64_t)(inside - mid));
+        exact_add(&excess, R, -(int64_t)mid);
+        if (exact_sign(&excess) >= 0) lo = mid;
+        else hi = mid - 1;
+    }
+    size_t m = lo;                             /* how many elements may lie above b */
     size_t rank;                               /* 1-based rank of b among the sorted bucket */
-    if (m >= (double)count_le_R) rank = 1;
-    else rank = count_le_R - (size_t)m;
+    if (m >= count_le_R) rank = 1;
+    else rank = count_le_R - m;
     if (rank < 1) rank = 1;
     float b = x[rank - 1];
     if (b < L) b = L;

@@ -215,3 +215,110 @@ def test_greedy_structure_for_power_of_two_levels_rounds_the_middle_index_down()
     b5 = oracle.qstar(x, b3, x[-1])
     want = [x[0], b1, oracle.qstar(x, b1, b3), b3, oracle.qstar(x, b3, b5), b5, oracle.qstar(x, b5, x[-1]), x[-1]]
     assert list(lv) == want
+
+
+# ------------------------------------------------------------------------------------------------
+# floor(T) of the discrete optimal condition (second remark after Theorem 1) in exact arithmetic
+# ------------------------------------------------------------------------------------------------
+def _as_integer(v):
+    """An fp32 value as an integer multiple of 2^-149 (exact)."""
+    return int(Fraction(float(np.float32(v))) * 2 ** 149)
+
+
+def test_exact_sums_against_rationals():
+    """The oracle's multi-word sums: sign of sum c_i v_i for values anywhere in the fp32 range (subnormals, 1e-38 next to
+    1e38, sums that cancel exactly or leave one unit of 2^-149) against Python integers."""
+    rng = np.random.default_rng(5)
+    for trial in range(400):
+        k = int(rng.integers(1, 40))
+        exponents = rng.integers(-149, 128, k)
+        values = (rng.uniform(1, 2, k) * 2.0 ** exponents.astype(np.float64) * rng.choice([-1, 1], k)).astype(np.float32)
+        values[~np.isfinite(values)] = np.float32(3.0e38)
+        coeff = rng.integers(-(1 << 19), 1 << 19, k)
+        if trial % 4 == 0:  # append the terms that cancel the sum exactly, then break the tie by one smallest unit
+            values = np.concatenate([values, values])
+            coeff = np.concatenate([coeff, -coeff])
+            if trial % 8 == 0:
+                values = np.concatenate([values, [np.float32(1e-45)]])
+                coeff = np.concatenate([coeff, [(-1) ** (trial // 8)]])
+        expected = sum(int(c) * _as_integer(v) for v, c in zip(values, coeff))
+        assert oracle.exact_sign(values, coeff) == (expected > 0) - (expected < 0), trial
+    assert oracle.exact_sign([0.0, -0.0], [5, -7]) == 0
+    assert oracle.exact_sign([np.float32(1e-45)], [-1]) == -1
+    big = np.full(32768, 3.0e38, np.float32)
+    assert oracle.exact_sign(np.concatenate([big, -big, [np.float32(1e-45)]]), np.ones(65537, np.int64)) == 1
+
+
+def _expected_qstar(x, L, R):
+    """The solve with floor(T) in exact integers: x sorted fp32, L < R bucket values."""
+    xi = [_as_integer(v) for v in x]
+    Li, Ri = _as_integer(L), _as_integer(R)
+    count_le_R = sum(1 for v in xi if v <= Ri)
+    S = sum(v - Li for v in xi if Li <= v <= Ri)
+    m = S // (Ri - Li)            # Python's floor division of integers is exact
+    rank = max(1, count_le_R - m)
+    b = x[rank - 1]
+    return b if b >= L else L
+
+
+@pytest.mark.parametrize("n", [2048, 4096, 8192, 32768])
+def test_qstar_floor_is_exact_at_real_bucket_sizes(n):
+    """At the bucket sizes of the hot path the level is the element of rank #{v <= R} - floor(T) with floor(T) exact,
+    whatever a floating-point sum of the terms would give: buckets whose T is exactly an integer (where a sum that is one
+    rounding low picks the neighbouring element), heavy tails with a dynamic range of 2^30 and more, values next to the
+    ends of the fp32 range, and ordinary data."""
+    rng = np.random.default_rng(n)
+    cases = []
+    # T exactly an integer: the only element above L is R, thousands of unlike large values below L
+    x = (-1.0e6 * (1.0 + 1.0e-3 * rng.random(n))).astype(np.float32)
+    x[0], x[1] = np.float32(rng.uniform(1, 9)), np.float32(rng.uniform(1, 2) * 1e20)
+    x = np.sort(x)
+    cases.append((x, x[-2], x[-1]))
+    cases.append((x, x[0], x[-1]))
+    # T exactly an integer with many unlike terms: inside [L,R] pairs (L + a_i, R - a_i) contribute R - L each
+    a = np.sort(rng.uniform(0.01, 0.4, n // 4)).astype(np.float32)
+    L, R = np.float32(1.0), np.float32(2.0)
+    pairs = np.concatenate([L + a, R - a])          # exact in fp32 for these magnitudes? keep only exact pairs
+    ok = np.array([_as_integer(p) + _as_integer(q) == _as_integer(L) + _as_integer(R) for p, q in zip(L + a, R - a)])
+    pairs = np.concatenate([(L + a)[ok], (R - a)[ok]])
+    below = (-rng.lognormal(0, 3, n - pairs.size - 2)).astype(np.float32)
+    x = np.sort(np.concatenate([below, [L, R], pairs]).astype(np.float32))
+    cases.append((x, L, R))
+    # heavy tails
+    for scale in (1.0, 1e-30, 1e25):
+        x = np.sort((rng.lognormal(0, 4, n) * rng.choice([-1, 1], n) * scale).astype(np.float32))
+        x = x[np.isfinite(x)]
+        cases.append((x, x[0], x[-1]))
+        i, j = sorted(rng.choice(x.size, 2, replace=False))
+        cases.append((x, x[i], x[j]))
+        cases.append((x, x[x.size // 2], x[-1]))
+    # subnormal values next to ordinary ones
+    x = np.sort(np.concatenate([rng.normal(0, 1e-40, n // 2), rng.normal(0, 1e-3, n - n // 2)]).astype(np.float32))
+    cases.append((x, x[0], x[-1]))
+    cases.append((x, x[n // 4], x[3 * n // 4]))
+    # ordinary data and integers (ties)
+    x = np.sort(rng.normal(0, 1e-3, n).astype(np.float32))
+    cases.append((x, x[0], x[-1]))
+    x = np.sort(rng.integers(-50, 51, n).astype(np.float32))
+    cases.append((x, x[0], x[-1]))
+    cases.append((x, np.float32(-7), np.float32(12)))
+    for x, L, R in cases:
+        if L < R:
+            assert oracle.qstar(x, L, R) == _expected_qstar(x, L, R), (n, L, R)
+
+
+def test_a_floating_point_sum_would_pick_the_neighbour():
+    """Why the floor is exact: a bucket where T = 3 exactly, but the terms v - L added one by one in double precision
+    (in sorted order) come out below 3 (R - L), so that floor(T) would be 2 and the level one element too high."""
+    L, R = np.float32(0.0), np.float32(1.0)
+    # 2^54 + 1 spread over terms that a running double sum cannot hold: many tiny terms after a large one
+    tiny = np.full(4096, 2.0 ** -54, np.float32)           # 4096 * 2^-54 = 2^-42
+    x = np.sort(np.concatenate([[L], tiny, [np.float32(1.0 - 2.0 ** -24)], [np.float32(2.0 ** -24 - 2.0 ** -42)],
+                                [R, R]]).astype(np.float32))
+    # S = 2^-42 + (1 - 2^-24) + (2^-24 - 2^-42) + 1 + 1 = 3 exactly
+    assert sum(_as_integer(v) for v in x) == 3 * _as_integer(R)
+    running = 0.0
+    for v in x[::-1]:                                       # largest first: the tiny terms are lost one by one
+        running += float(v)
+    assert running < 3.0
+    assert oracle.qstar(x, L, R) == _expected_qstar(x, L, R)
