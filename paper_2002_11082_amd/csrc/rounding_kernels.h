@@ -88,6 +88,10 @@ constexpr GreedyOrder greedy_order()
     return o;
 }
 
+// Limbs of the exact sums behind floor(T) (exact_floor_t below): value = sum_i limb[i] * 2^(32 i - 149); |v| < 2^129
+// and |coefficient| < 2^20 fit.
+constexpr int kExactLimbs = 11;
+
 // LDS of one bucket: D = element capacity, B = number of bins.
 template <int D_, int B_, int S_>
 struct OrqLds {
@@ -106,7 +110,8 @@ struct OrqLds {
     uint32_t lvl_count_lt[S_];
     uint32_t lvl_count_le[S_];
     uint32_t lvl_rank[S_];
-    double cancel_bound;  // what rounding can add to a difference of two prefix sums: 2^-44 * len * largest magnitude
+    double sum_error_bound;  // 0 when every fp64 sum of the bucket is exact (see floor_t_from_sums)
+    unsigned long long exact_limb[1][kExactLimbs];  // workspace of exact_floor_t
 };
 
 __device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 6); }
@@ -412,6 +417,156 @@ __device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t r
     return pick_in_span<Lds::BLOCK, SUMS>(lds, first, next - first, rank, lane);
 }
 
+// ----------------------------------------------------------------------------------------------
+// floor(T) of the discrete optimal condition (second remark after Theorem 1), T = S / (R - L) with
+// S = sum over the bucket elements v in [L, R] of (v - L).  The floor decides which element becomes the level, so it
+// is the exact one: the largest integer m with S - m (R - L) >= 0.
+//
+// Fast path.  The sums a solve reads are fp64 sums of fp32 values.  They are exact, whatever their order, when every
+// non-zero element of the bucket is at most safe_binades(len) binades below the largest magnitude M < 2^(E+1): every
+// element is then a multiple of q = 2^(E - safe - 23), every intermediate value (prefix sums below len * M, S and
+// m (R - L) below 4 len M) is a multiple of q below 2^53 q, so no addition, difference or product ever rounds.  With
+// S exact, floor(S / (R - L)) is corrected by at most one through the sign of the exact rest S - m (R - L).  A bucket
+// with smaller non-zero elements ("tiny" ones: they sit in the two centre bins of the grouping) keeps the same
+// arithmetic, but a rest within sum_error_bound of 0 or of R - L does not decide; the bound covers 256 roundings of
+// half a unit in the last place of a value below 4 len M, more than any prefix sum here goes through.
+//
+// Exact path (undecided solves only).  Every fp32 value is an integer multiple of 2^-149: the elements in [L, R] are
+// added up as signed fixed-point numbers in 11 limbs of 32 payload bits (64-bit LDS atomics; a limb takes at most
+// 32768 pieces below 2^32 before the carries are propagated), and m is searched with the sign of
+// sum - (c - m) L - m R, c the number of elements in [L, R], which does not grow with m.
+// ----------------------------------------------------------------------------------------------
+
+__host__ __device__ constexpr uint32_t ceil_log2(uint32_t n)
+{
+    uint32_t k = 0;
+    while ((1u << k) < n) ++k;
+    return k;
+}
+
+// How many binades below the largest magnitude a non-zero element may lie for all fp64 sums of a bucket of at most
+// `capacity` elements to be exact: capacity * 4 M / q <= 2^53 with q = 2^(E - safe - 23) and M < 2^(E+1).
+__host__ __device__ constexpr uint32_t safe_binades(uint32_t capacity) { return 28u - ceil_log2(capacity); }
+
+// What the fp64 sums of a bucket with tiny elements can be off by: 2^(ceil_log2(capacity) + E - 44), E the
+// unbiased exponent of the largest magnitude (at least the smallest normal double).
+__device__ __forceinline__ double sum_error_bound_of(uint32_t mag_max_bits, uint32_t capacity)
+{
+    const int field = 1023 + ((int)(mag_max_bits >> 23) - 127) + (int)ceil_log2(capacity) - 44;
+    return __longlong_as_double((long long)(uint64_t)(field < 1 ? 1 : field) << 52);
+}
+
+// Cuts |c * v| into the three 32-bit pieces that go to limbs first, first + 1, first + 2.  first <= 7.
+struct ExactPieces {
+    uint32_t first;
+    bool negative;
+    uint64_t piece[3];
+};
+
+__device__ __forceinline__ ExactPieces exact_pieces(float v, long long c)
+{
+    const uint32_t bits = __float_as_uint(v);
+    const uint32_t biased = (bits >> 23) & 0xFFu, fraction = bits & 0x7FFFFFu;
+    // |v| = mantissa * 2^(position - 149); subnormals have position 0 and no hidden bit
+    const uint64_t mantissa = biased ? (fraction | 0x800000u) : fraction;
+    const uint32_t position = biased ? biased - 1u : 0u;
+    const uint64_t magnitude = mantissa * (uint64_t)(c < 0 ? -c : c);  // below 2^44
+    const uint32_t shift = position & 31u;
+    const uint64_t low = magnitude << shift;                          // bits 0 .. 63 of magnitude << shift
+    const uint64_t high = shift > 20u ? magnitude >> (64u - shift) : 0ull;  // bits 64 .. 74
+    ExactPieces p;
+    p.first = position >> 5;
+    p.negative = ((bits >> 31) != 0u) != (c < 0);
+    p.piece[0] = low & 0xFFFFFFFFull;
+    p.piece[1] = low >> 32;
+    p.piece[2] = high;
+    return p;
+}
+
+// limb (LDS, shared by the lanes of the group) += v
+__device__ __forceinline__ void exact_add_shared(unsigned long long* limb, float v)
+{
+    const ExactPieces p = exact_pieces(v, 1);
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+        if (p.piece[k] != 0ull) atomicAdd(&limb[p.first + k], p.negative ? 0ull - p.piece[k] : p.piece[k]);  // signed, mod 2^64
+}
+
+// The piece of p that belongs to limb i.
+__device__ __forceinline__ long long exact_piece_of(const ExactPieces& p, uint32_t i)
+{
+    const uint32_t k = i - p.first;  // 0, 1, 2 for the three limbs the value touches
+    const uint64_t piece = k == 0u ? p.piece[0] : k == 1u ? p.piece[1] : k == 2u ? p.piece[2] : 0ull;
+    return p.negative ? -(long long)piece : (long long)piece;
+}
+
+// sum (the limbs) + cl * L + cr * R >= 0 ?  The limbs are only read.  (A rolled loop over the limbs: this rare path
+// must not raise the register count of the kernels it is inlined into.)
+__device__ __forceinline__ bool exact_not_negative(const unsigned long long* limb, float L, long long cl, float R,
+                                                   long long cr)
+{
+    const ExactPieces pl = exact_pieces(L, cl), pr = exact_pieces(R, cr);
+    long long carry = 0;
+#pragma unroll 1
+    for (uint32_t i = 0; i < (uint32_t)kExactLimbs; ++i) {
+        const long long t = (long long)limb[i] + exact_piece_of(pl, i) + exact_piece_of(pr, i) + carry;
+        carry = t >> 32;  // floor division by 2^32
+    }
+    return carry >= 0;  // what is left above the top limb carries the sign
+}
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// floor(T), exactly.  Called by all lanes that hold the bucket (a wavefront, or the group of lanes of a small bucket)
+// with the same limb array, L < R, count_in = #{L <= v <= R} and a first guess; each_of_mine(f) runs f(x) on the bucket
+// elements this lane answers for; lane_in_group counts the calling lanes from 0.
+template <class EachFn>
+__device__ __forceinline__ uint32_t exact_floor_t(unsigned long long* limb, uint32_t lane_in_group, float L, float R,
+                                                  uint32_t count_in, uint32_t guess, EachFn each_of_mine)
+{
+    if (lane_in_group < (uint32_t)kExactLimbs) limb[lane_in_group] = 0ull;
+    wave_lds_sync();
+    each_of_mine([&](float x) {
+        if (L <= x && x <= R) exact_add_shared(limb, x);
+    });
+    wave_lds_sync();
+    // S - m (R - L) = sum - (count_in - m) L - m R; the first two probes sit at the guess
+    uint32_t lo = 0u, hi = count_in;  // m = 0 fits: S >= 0
+    uint32_t probe = guess < count_in ? guess : count_in;
+    if (probe == 0u) probe = hi > 0u ? 1u : 0u;
+    for (int step = 0; lo < hi; ++step) {
+        const uint32_t mid = step == 0 ? probe : (step == 1 && lo == probe && probe < hi) ? probe + 1u
+                                                                                         : lo + (hi - lo + 1u) / 2u;
+        if (exact_not_negative(limb, L, -(long long)(count_in - mid), R, -(long long)mid)) lo = mid;
+        else hi = mid - 1u;
+    }
+    wave_lds_sync();  // every lane is through with the limbs before a later call clears them
+    return lo;
+}
+
+// floor(T) of one solve from the fp64 sums (see above): Ssum = the sums' S, width = R - L > 0 in fp64, bound = the
+// bucket's sum_error_bound (0: every sum is exact).  Returns false when the sums do not decide; m is then the guess for
+// exact_floor_t.
+__device__ __forceinline__ bool floor_t_from_sums(double Ssum, double width, uint32_t count_in, double bound, double& m)
+{
+    m = floor(Ssum / width);
+    if (!(m >= 0.0)) m = 0.0;  // (also catches NaN from non-finite input)
+    if (m > (double)count_in) m = (double)count_in;
+    const double rest = Ssum - m * width;
+    if (bound == 0.0) {
+        // exact sums, exact rest: the rounding of the quotient can be off by one
+        if (rest < 0.0) m -= 1.0;
+        else if (rest >= width) m += 1.0;
+        if (!(m >= 0.0)) m = 0.0;
+        return true;
+    }
+    return rest > bound && width - rest > bound;
+}
+
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // Runs f(c, all) for the chunks c (256 elements each) that hold at least one of the `len` valid elements.  `all` is a
@@ -517,6 +672,31 @@ __device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (
     }
 }
 
+// Whether the bucket holds a non-zero element more than safe_binades(capacity) binades below its largest magnitude
+// (mag_max = its bit pattern), i.e. whether its fp64 sums may round.  Such elements sit in the bins next to zero: the
+// two centre bins, which take everything below the binned range, and above 4096 elements also the lowest regular bins.
+// Called by one whole wavefront once the bucket is grouped; the result is wave-uniform.
+template <int HALF, int SHIFT, class Lds>
+__device__ __forceinline__ bool any_tiny_element(const Lds& lds, uint32_t capacity, uint32_t mag_max, uint32_t t_low,
+                                                 uint32_t lane)
+{
+    const uint32_t safe = safe_binades(capacity);
+    const uint32_t biased = mag_max >> 23;
+    if (biased <= safe) return false;  // every element is a multiple of 2^-149 and the sums stay below 2^53 of those
+    const uint32_t mag_safe = (biased - safe) << 23;  // bit pattern of the smallest safe magnitude
+    const uint32_t t_safe = mag_safe >> SHIFT;
+    uint32_t bins = t_safe > t_low ? t_safe - t_low : 1u;  // bins per sign that may hold smaller elements
+    bins = bins > (uint32_t)HALF ? (uint32_t)HALF : bins;
+    const uint32_t first = uniform_u32(lds.bin_start[(uint32_t)HALF - bins]);
+    const uint32_t last = uniform_u32(lds.bin_start[(uint32_t)HALF + bins]);
+    bool tiny = false;
+    for (uint32_t i = first + lane; i < last; i += kWave) {
+        const uint32_t magnitude = lds.grouped[skewed(i)] & 0x7FFFFFFFu;
+        tiny = tiny || (magnitude != 0u && magnitude < mag_safe);
+    }
+    return __ballot(tiny) != 0;
+}
+
 // Where the levels come from; all rules share the random-rounding encoder.
 //   kOptimal: ORQ (Theorem 1, Algorithm 1).
 //   kPb: BinGrad-pb (Section 3.2): two levels -b_1, +b_1 from the scheme's optimal condition instead of the
@@ -551,22 +731,17 @@ __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k,
     uint32_t rank = 0;
     if (!copy_left) {
         // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
-        const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
+        const uint32_t count_in = cnt_le_R - cnt_lt_L;
+        const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)count_in;
         const double width = (double)R - (double)L;
-        double T = Ssum / width;
-        // The prefix sums cancel in S.  Where T is an integer within what their rounding can add (exactly an integer,
-        // for one, when every element above L up to R equals R), S is summed again term by term, which is exact
-        // whenever the terms are few or alike, and floor(T) is taken from that.
-        if (fabs(Ssum - rint(T) * width) <= uniform_f64(lds.cancel_bound)) {
-            double part = 0.0;
-            for (uint32_t i = lane; i < len; i += kWave) {
-                const float x = __uint_as_float(lds.grouped[skewed(i)]);
-                part += (L <= x && x <= R) ? (double)x - (double)L : 0.0;
-            }
-            T = wave_sum(part) / width;
+        double m;
+        if (!floor_t_from_sums(Ssum, width, count_in, uniform_f64(lds.sum_error_bound), m)) {
+            // the fp64 sums do not decide floor(T): exact sums of the elements in [L, R] (rare)
+            m = (double)exact_floor_t(lds.exact_limb[(threadIdx.x >> 6) & (sizeof(lds.exact_limb) / sizeof(lds.exact_limb[0]) - 1u)],
+                                      lane, L, R, count_in, (uint32_t)m, [&](auto add) {
+                for (uint32_t i = lane; i < len; i += kWave) add(__uint_as_float(lds.grouped[skewed(i)]));
+            });
         }
-        double m = floor(T);
-        if (!(m >= 0.0)) m = 0.0;
         rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
         rank = rank < 1u ? 1u : (rank > len ? len : rank);
         if (rank == last_rank) return;  // same element as last time
@@ -1036,7 +1211,6 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
             }
         }
         if (lane == 0u) {
-            lds.cancel_bound = 0x1p-44 * (double)len * (double)__uint_as_float(mag_max);
             // the bottom level is only ever the left end of a solve
             lds.lvl_count_lt[0] = 0u;
             lds.lvl_sum_lt[0] = 0.0;
@@ -1050,6 +1224,11 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
+        if constexpr (RULE == kOptimal && S > 2) {
+            const bool tiny = any_tiny_element<HALF, SHIFT>(lds, (uint32_t)D, mag_max, t_low, lane);
+            if (lane == 0u) lds.sum_error_bound = tiny ? sum_error_bound_of(mag_max, (uint32_t)D) : 0.0;
+            wave_lds_sync();
+        }
         const uint32_t zeros = PB ? wave_sum_u32(lane_zeros) : 0u;
         pb_level = orq_solve_levels<S, RULE>(
             lds, [&](uint32_t rank) { return pick_rank<D, B, S, SUMS>(lds, my_start, rank, lane); },
@@ -1367,7 +1546,8 @@ __device__ __forceinline__ void for_sweep_levels(Solve&& solve)
 template <int S, int BITS, int NB, bool FULL, int RULE>
 __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, uint32_t len, size_t begin, uint32_t first_bucket,
                                                   uint32_t sweeps, float clip, uint64_t seed, uint64_t index_offset,
-                                                  float* __restrict__ levels, uint32_t* __restrict__ codes32)
+                                                  float* __restrict__ levels, uint32_t* __restrict__ codes32,
+                                                  unsigned long long* exact_limbs)
 {
     static_assert(RULE == kLinear || RULE == kOptimal || (RULE == kPb && S == 2), "rules that read order statistics");
     constexpr uint32_t G = 64u / NB;  // lanes per bucket
@@ -1464,6 +1644,22 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
         const uint32_t last = count > 0u ? count - 1u : 0u;
         lv[0] = key_to_float(row_fetch(x, 0u, first_lane));
         lv[S - 1] = key_to_float(row_fetch(x, last, first_lane));
+        // Whether the fp64 sums of this lane's bucket are exact (floor_t_from_sums: no non-zero element more than
+        // safe_binades(D) binades below the largest magnitude), and the bucket's workspace for exact_floor_t.
+        double error_bound = 0.0;
+        unsigned long long* limb = exact_limbs + ((threadIdx.x >> 6) * NB + q) * kExactLimbs;
+        if constexpr (RULE == kOptimal) {
+            const uint32_t mag_max = umax32(__float_as_uint(lv[0]) & 0x7FFFFFFFu, __float_as_uint(lv[S - 1]) & 0x7FFFFFFFu);
+            const uint32_t biased = mag_max >> 23;
+            const uint32_t mag_safe = biased > safe_binades(D) ? (biased - safe_binades(D)) << 23 : 0u;
+            uint32_t tiny = 0u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t magnitude = __float_as_uint(key_to_float(x[i])) & 0x7FFFFFFFu;
+                if (4u * (lane & (G - 1u)) + i < count && magnitude != 0u && magnitude < mag_safe) tiny = 1u;
+            }
+            if (row_max_u32<(int)G>(tiny, lane) != 0u) error_bound = sum_error_bound_of(mag_max, D);
+        }
         if constexpr (RULE == kLinear) {
 #pragma unroll
             for (int k = 1; k + 1 < S; ++k)
@@ -1499,7 +1695,6 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
                 st.rank[k] = 0u;
             }
             const uint32_t count_or_one = count > 0u ? count : 1u;
-            const double cancel_bound = 0x1p-44 * (double)count * (double)fmaxf(fabsf(lv[0]), fabsf(lv[S - 1]));
             auto solve = [&](auto kc, auto lc, auto rc) {
                 constexpr int k = decltype(kc)::value, l = decltype(lc)::value, r = decltype(rc)::value;
                 const float L = st.value[l], R = st.value[r];
@@ -1507,23 +1702,19 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
                 const double sum_lt_L = st.sum_lt[l], sum_le_R = st.sum_le[r];
                 const bool ordered = L < R;
                 // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
-                const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)(cnt_le_R - cnt_lt_L);
+                const uint32_t count_in = cnt_le_R - cnt_lt_L;
+                const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)count_in;
                 const double width = (double)R - (double)L;
-                double T = Ssum / width;  // not used when L == R
-                // (as in orq_solve_one: an integer T within the rounding of the cancelling prefix sums is summed directly)
-                const bool cancelled = ordered && fabs(Ssum - rint(T) * width) <= cancel_bound;
-                if (__ballot(cancelled) != 0) {
-                    double part = 0.0;
+                double m;  // not used when L == R
+                const bool decided = floor_t_from_sums(Ssum, width, count_in, error_bound, m);
+                if (ordered && !decided) {
+                    // (as in orq_solve_one: exact sums where the fp64 sums do not decide; only the lanes of such buckets)
+                    m = (double)exact_floor_t(limb, lane & (G - 1u), L, R, count_in, (uint32_t)m, [&](auto add) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float value = key_to_float(x[i]);
-                        part += (l4 + i < count && L <= value && value <= R) ? (double)value - (double)L : 0.0;
-                    }
-                    const double direct = row_sum_f64<(int)G>(part, lane) / width;
-                    T = cancelled ? direct : T;
+                        for (int i = 0; i < 4; ++i)
+                            if (l4 + i < count) add(key_to_float(x[i]));
+                    });
                 }
-                double m = floor(T);
-                if (!(m >= 0.0)) m = 0.0;
                 const bool whole = m >= (double)cnt_le_R;
                 uint32_t rank = whole ? 1u : cnt_le_R - (uint32_t)(whole ? 0.0 : m);
                 rank = rank < 1u ? 1u : (rank > count_or_one ? count_or_one : rank);
@@ -1564,20 +1755,16 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
             const double total = row_sum_f64<(int)G>(part, lane);
             const float L = lv[0], R = lv[2];
             const double Ssum = total - (double)L * (double)count, width = (double)R - (double)L;
-            double T = Ssum / width;  // not used when L == R
-            // (as in orq_solve_one: an integer T within the rounding of the cancelling sums is summed directly)
-            const bool cancelled =
-                L < R && fabs(Ssum - rint(T) * width) <= 0x1p-44 * (double)count * (double)fmaxf(fabsf(L), fabsf(R));
-            if (__ballot(cancelled) != 0) {
-                double direct = 0.0;
+            double m;  // not used when L == R
+            const bool decided = floor_t_from_sums(Ssum, width, count, error_bound, m);
+            if (L < R && !decided) {
+                // (as in orq_solve_one: exact sums where the fp64 sums do not decide; only the lanes of such buckets)
+                m = (double)exact_floor_t(limb, lane & (G - 1u), L, R, count, (uint32_t)m, [&](auto add) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    direct += 4u * (lane & (G - 1u)) + i < count ? (double)key_to_float(x[i]) - (double)L : 0.0;
-                direct = row_sum_f64<(int)G>(direct, lane) / width;
-                T = cancelled ? direct : T;
+                    for (int i = 0; i < 4; ++i)
+                        if (4u * (lane & (G - 1u)) + i < count) add(key_to_float(x[i]));
+                });
             }
-            double m = floor(T);
-            if (!(m >= 0.0)) m = 0.0;
             if (m > (double)count) m = (double)count;
             uint32_t rank = m >= (double)count ? 1u : count - (uint32_t)m;
             rank = rank < 1u ? 1u : rank;
@@ -1597,6 +1784,7 @@ __global__ __launch_bounds__(4 * kWave) void sorted_small_kernel(const float* __
                                                                  float clip, uint64_t seed, uint64_t index_offset,
                                                                  float* __restrict__ levels, uint32_t* __restrict__ codes32)
 {
+    __shared__ unsigned long long exact_limbs[4 * NB * kExactLimbs];  // workspace of exact_floor_t per wavefront and bucket
     const size_t span = (size_t)blockIdx.x * 4u + (threadIdx.x >> 6);  // 256 elements each
     const size_t begin = span * 256u;
     if (begin >= n) return;
@@ -1604,10 +1792,10 @@ __global__ __launch_bounds__(4 * kWave) void sorted_small_kernel(const float* __
     const uint32_t first_bucket = (uint32_t)(span * NB);
     if (rest >= 256u)
         sorted_small_span<S, BITS, NB, true, RULE>(grad + begin, 256u, begin, first_bucket, sweeps, clip, seed, index_offset,
-                                                   levels, codes32);
+                                                   levels, codes32, exact_limbs);
     else
         sorted_small_span<S, BITS, NB, false, RULE>(grad + begin, (uint32_t)rest, begin, first_bucket, sweeps, clip, seed,
-                                                    index_offset, levels, codes32);
+                                                    index_offset, levels, codes32, exact_limbs);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1633,7 +1821,8 @@ struct OrqTeamLds {
     uint32_t lvl_count_lt[10];
     uint32_t lvl_count_le[10];
     uint32_t lvl_rank[10];
-    double cancel_bound;  // what rounding can add to a difference of two prefix sums: 2^-44 * len * largest magnitude
+    double sum_error_bound;  // 0 when every fp64 sum of the bucket is exact (see floor_t_from_sums)
+    unsigned long long exact_limb[2][kExactLimbs];  // workspace of exact_floor_t, one per solving wavefront
     TeamSlot slots[2][W];
 };
 
@@ -1820,7 +2009,6 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
                 lds.lvl_sum_lt[0] = 0.0;
                 lds.lvl_count_le[0] = 0u;
                 lds.lvl_sum_le[0] = 0.0;
-                lds.cancel_bound = 0x1p-44 * (double)len * (double)__uint_as_float(mag_max);
                 lds.lvl_count_le[S - 1] = len;
                 lds.lvl_sum_le[S - 1] = total;
                 lds.lvl_count_lt[S - 1] = len;
@@ -1829,6 +2017,14 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
             if (tid < (uint32_t)S) {
                 lds.lvl_value[tid] = key_to_float(tid == (uint32_t)(S - 1) ? key_max : key_min);
                 lds.lvl_rank[tid] = 0u;
+            }
+        }
+        if constexpr (RULE == kOptimal && S > 2) {
+            // (the grouped values and the bin starts have been complete since the barrier after the scatter)
+            if (wave == 0u) {
+                const bool tiny = any_tiny_element<HALF, SHIFT>(lds, (uint32_t)OrqTeamLds<W, C>::D, mag_max, t_low, lane);
+                if (lane == 0u)
+                    lds.sum_error_bound = tiny ? sum_error_bound_of(mag_max, (uint32_t)OrqTeamLds<W, C>::D) : 0.0;
             }
         }
         __syncthreads();

@@ -440,6 +440,32 @@ def test_integer_t_where_the_prefix_sums_cancel():
             parity.check_quantize(g, d, bits, scheme, 1, seed=seed, tag=f"integer-T-seed{seed}-s{scheme}b{bits}-d{d}")
 
 
+@pytest.mark.parametrize("d", [64, 128, 512, 2048, 4096, 8192, 32768])
+def test_symmetric_buckets_where_t_is_exactly_an_integer(d):
+    """A bucket that holds -v for every v has S = (len / 2) (R - L) between its extremes: T is an integer, the optimum is
+    flat and the lower end must be taken whatever a floating-point sum of the terms gives.  With values spread over
+    more binades than the fp64 sums hold exactly (log-normal, tiny values next to large ones) the kernels have to decide
+    floor(T) with their exact sums; with a narrow spread the fp64 sums are exact themselves.  Both against the oracle,
+    whose floor(T) is exact by construction."""
+    rng = np.random.default_rng(900 + d)
+    halves = [
+        rng.lognormal(0, 4, d // 2),                                              # dynamic range far beyond 2^30
+        np.concatenate([rng.normal(0, 1, d // 2 - 8), rng.normal(0, 1e-30, 8)]),  # a few tiny values
+        rng.normal(0, 1e-3, d // 2),                                              # narrow: exact fp64 sums
+        rng.integers(1, 40, d // 2).astype(np.float64),                           # many equal values
+        np.concatenate([rng.normal(0, 1e-40, d // 4), rng.normal(0, 1e-3, d // 2 - d // 4)]),  # subnormals
+    ]
+    buckets = []
+    for h in halves:
+        h = np.abs(h).astype(np.float32)
+        bucket = np.concatenate([h, -h])
+        rng.shuffle(bucket)
+        buckets.append(bucket)
+    g = np.concatenate(buckets + [buckets[0][: d // 2 + 6]])
+    for scheme, bits, sweeps in ((ogq.ORQ_PAPER, 2, 0), (ogq.ORQ, 2, 2), (ogq.ORQ, 3, 1), (ogq.ORQ_PAPER, 3, 1), (ogq.ORQ_PAPER, 4, 0)):
+        parity.check_quantize(g, d, bits, scheme, sweeps, seed=d, tag=f"symmetric-s{scheme}b{bits}-d{d}")
+
+
 def test_non_finite_values_stay_inside_their_bucket():
     """NaN and infinities give unspecified levels and codes for their own bucket only: every call returns, and the
     buckets without them still match the oracle (every kernel family and bucket-size class)."""
