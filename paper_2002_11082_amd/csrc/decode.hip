@@ -1,5 +1,7 @@
 // libogq, decode + average kernel (server step of Algorithm 2 of arXiv 2002.11082) and the bandwidth probes,
 // for MI355X (gfx950).
+#include <type_traits>
+
 #include "device_common.h"
 #include "launch.h"
 
@@ -16,6 +18,12 @@ struct WorkerPtrs {
 };
 
 constexpr int kSpanWords = 16;  // one wavefront decodes 16 packed word groups = 1024 elements
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
 
 // Level selected by the packed words of one 64-element group: the words are the lane masks of the
 // selects.  S = 2^BITS levels: a full binary tree; S = 2^(BITS-1) + 1 levels (the paper's counts):
@@ -71,6 +79,72 @@ __device__ __forceinline__ void load_levels(const float* __restrict__ table, flo
     for (int k = 0; k < S; ++k) asm("v_mov_b32 %0, %1" : "=v"(lv[k]) : "s"(s[k]));
 }
 
+// ----------------------------------------------------------------------------------------------
+// The span's code bits, turned so that every lane holds the bits of its own elements.  A span's code words are
+// 16 * BITS rows of 64 bits (row = word group * BITS + bit plane, one bit per element of the group).  Lane 32 h + r
+// loads the half h (32 elements) of rows r, r + 32, ...; a 32 x 32 bit-matrix transpose inside each half of the
+// wavefront (five butterfly steps: the partner lane's word, rotated, replaces half of the bits) then leaves, in lane
+// 32 h + b, bit `row` of the result = code bit of element 32 h + b of that row's group: the level index of group j
+// sits at bits BITS j .. BITS j + BITS - 1 and indexes the bucket's level table in LDS directly.
+// ----------------------------------------------------------------------------------------------
+struct BitTranspose {
+    uint32_t take[5];  // bits a lane takes from its partner at lane distance 16, 8, 4, 2, 1
+    uint32_t turn[5];  // right rotation that brings the partner's bits into place
+};
+
+__device__ __forceinline__ BitTranspose bit_transpose_setup(uint32_t lane)
+{
+    BitTranspose t;
+    constexpr uint32_t kLow[5] = {0x0000FFFFu, 0x00FF00FFu, 0x0F0F0F0Fu, 0x33333333u, 0x55555555u};
+#pragma unroll
+    for (int s = 0; s < 5; ++s) {
+        const uint32_t j = 16u >> s;
+        const bool upper = (lane & j) != 0u;
+        // the lower lane of a pair keeps its low blocks and takes the partner's low blocks as its high blocks; the upper
+        // lane keeps its high blocks and takes the partner's high blocks as its low blocks
+        t.take[s] = upper ? kLow[s] : kLow[s] << j;
+        t.turn[s] = upper ? j : 32u - j;
+    }
+    return t;
+}
+
+template <int DIST, int STEP>
+__device__ __forceinline__ uint32_t bit_transpose_step(uint32_t x, const BitTranspose& t, uint32_t lane)
+{
+    const uint32_t y = lane_xor<DIST>(x, lane);
+    const uint32_t turned = __builtin_amdgcn_alignbit(y, y, t.turn[STEP]);
+    return (t.take[STEP] & turned) | (~t.take[STEP] & x);  // v_bfi_b32
+}
+
+__device__ __forceinline__ uint32_t bit_transpose(uint32_t x, const BitTranspose& t, uint32_t lane)
+{
+    x = bit_transpose_step<16, 0>(x, t, lane);
+    x = bit_transpose_step<8, 1>(x, t, lane);
+    x = bit_transpose_step<4, 2>(x, t, lane);
+    x = bit_transpose_step<2, 3>(x, t, lane);
+    return bit_transpose_step<1, 4>(x, t, lane);
+}
+
+// Level index of word group J from the turned code bits (R registers of 32 rows each).
+template <int BITS, int J, int R>
+__device__ __forceinline__ uint32_t level_index(const uint32_t (&turned)[R])
+{
+    constexpr int kFirst = BITS * J, kReg = kFirst / 32, kShift = kFirst % 32;
+    uint32_t bits = turned[kReg] >> kShift;
+    if constexpr (kShift + BITS > 32) bits |= turned[kReg + 1] << (32 - kShift);
+    return bits & ((1u << BITS) - 1u);
+}
+
+// Runs f(J, index of word group J) for the 16 word groups of a span; an index has BITS bits.
+template <int BITS, int J, int R, class F>
+__device__ __forceinline__ void for_each_group(const uint32_t (&turned)[R], F&& f)
+{
+    if constexpr (J < kSpanWords) {
+        f(std::integral_constant<int, J>{}, level_index<BITS, J>(turned));
+        for_each_group<BITS, J + 1>(turned, f);
+    }
+}
+
 // WPB = packed word groups per bucket when the span splits into whole buckets at fixed places: 16 = the
 // span lies in one bucket (bucket_size is a multiple of 1024; its index is word0 / words_per_bucket),
 // 1, 2, 4 or 8 = bucket_size 64 .. 512, the span holds 16 / WPB buckets whose level tables are
@@ -96,62 +170,177 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
 
     if (WPB > 0 && whole) {
         // Every element of the span exists and its buckets lie at fixed places: the span's code words and level
-        // tables are fetched with vector loads (lane i takes dword i), for several workers at once so that their
-        // trips to HBM overlap, and reach the scalar registers through v_readlane.  (Scalar loads, which deliver the
-        // lane masks directly, keep too few bytes in flight per wavefront once the streams come from HBM instead of
-        // the last-level cache.)
-        constexpr int kTables = WPB > 0 ? kSpanWords / WPB : 1;
-        constexpr int R = (32 * BITS + 63) / 64;        // registers for the 32 * BITS dwords of code words
-        constexpr int LR = (kTables * S + 63) / 64;     // registers for the kTables * S level values
-        constexpr uint32_t BATCH = R + LR > 2 ? 4 : 8;  // workers in flight
-        const uint32_t first_bucket = WPB == kSpanWords ? word0 / words_per_bucket : word0 / (uint32_t)(WPB > 0 ? WPB : 1);
-        for (uint32_t w0 = 0; w0 < num_workers; w0 += BATCH) {
-            uint32_t code_reg[BATCH][R];
-            float level_reg[BATCH][LR];
+        // tables are fetched with vector loads (one dword per lane and register), for several workers at once so
+        // that their trips to HBM overlap.  The code bits are turned into per-lane level indices (bit_transpose), the
+        // level tables go to a table in LDS that belongs to this wavefront, and an element's level is one LDS read.
+        // (Scalar loads, which would deliver the words as lane masks for a select tree, keep too few bytes in flight
+        // per wavefront once the streams come from HBM instead of the last-level cache; moving vector-loaded words
+        // to scalar registers costs two v_readlane per word.)
+        constexpr int kWpb = WPB > 0 ? WPB : 1;
+        constexpr int kTables = kSpanWords / kWpb;
+        const BitTranspose turn = bit_transpose_setup(lane);
+        const uint32_t half = lane >> 5, row = lane & 31u;
+        const uint32_t first_bucket = WPB == kSpanWords ? word0 / words_per_bucket : word0 / (uint32_t)kWpb;
+        const uint32_t wave = uniform_u32(threadIdx.x >> 6);
+        bool combined = false;
+        if constexpr (kTables <= 2) {
+          if (num_workers > 1u) {
+            combined = true;
+            // Several workers per look-up: K workers' indices of an element form one index of K * BITS bits into a
+            // table that holds, in fp64, the sum of the K levels for every combination of their indices (built once per
+            // span from the K level tables).  One LDS read and one fp64 addition then serve K workers.  The rows of
+            // code bits are fetched so that one transpose leaves the K * BITS bits of an element side by side: row
+            // (group j, worker i, plane p) is number j * K * BITS + i * BITS + p.
+            constexpr int K = BITS >= 4 ? 1 : 6 / BITS;           // workers per look-up
+            constexpr int IDX = K * BITS;                         // index bits of a look-up: 6, or 4 for 4-bit codes
+            constexpr int ENTRIES = 1 << IDX;                     // at most 64: one table entry per lane
+            constexpr int RR = kSpanWords * IDX / 32;             // registers of turned code bits per look-up
+            constexpr uint32_t FLIGHT = 3;                        // look-ups whose loads are in flight together
+            constexpr int RAW = K * kTables * S;                  // level values of the K workers of a look-up
+            static_assert(RAW <= 64 && ENTRIES <= 64, "one lane per level value and per table entry");
+            constexpr int WD = 2 * kSpanWords * BITS;             // dwords of one worker's code words of the span
+            constexpr int WR = (WD + 63) / 64;                    // registers that fetch them, one dword per lane
+            __shared__ double sum_tables[kWavesPerBlock][FLIGHT][kTables][ENTRIES];
+            __shared__ float raw_levels[kWavesPerBlock][FLIGHT][RAW];
+            __shared__ uint32_t staged_codes[kWavesPerBlock][FLIGHT][K][WD];
+            const uint32_t lookups = (num_workers + K - 1) / K;
+            for (uint32_t g0 = 0; g0 < lookups; g0 += FLIGHT) {
+                // every worker's code words and level tables with plain coalesced loads (the worker is wave-uniform)
+                uint32_t fetched[FLIGHT][K][WR];
+                float level_reg[FLIGHT][K];
 #pragma unroll
-            for (uint32_t b = 0; b < BATCH; ++b) {
+                for (uint32_t f = 0; f < FLIGHT; ++f)
 #pragma unroll
-                for (int k = 0; k < R; ++k) code_reg[b][k] = 0u;
+                    for (int i = 0; i < K; ++i) {
+                        const uint32_t w = (g0 + f) * K + i;
 #pragma unroll
-                for (int k = 0; k < LR; ++k) level_reg[b][k] = 0.0f;
-                if (w0 + b < num_workers) {
-                    const uint32_t* c32 = reinterpret_cast<const uint32_t*>(ptrs.codes[w0 + b] + (size_t)word0 * BITS);
-                    const float* tables = ptrs.levels[w0 + b] + (size_t)first_bucket * S;
+                        for (int k = 0; k < WR; ++k) fetched[f][i][k] = 0u;  // a worker that does not exist: index 0 ...
+                        level_reg[f][i] = 0.0f;                              // ... of a table of zeros
+                        if (w < num_workers) {
+                            const uint32_t* c32 = reinterpret_cast<const uint32_t*>(ptrs.codes[w] + (size_t)word0 * BITS);
 #pragma unroll
-                    for (int k = 0; k < R; ++k) {
-                        const uint32_t i = 64u * k + lane;
-                        if (i < 32u * BITS) code_reg[b][k] = c32[i];
+                            for (int k = 0; k < WR; ++k)
+                                if (64u * k + lane < (uint32_t)WD) fetched[f][i][k] = c32[64u * k + lane];
+                            if (lane < (uint32_t)(kTables * S)) level_reg[f][i] = ptrs.levels[w][(size_t)first_bucket * S + lane];
+                        }
                     }
+                wave_lds_fence();  // the reads of the round before are done
 #pragma unroll
-                    for (int k = 0; k < LR; ++k) {
-                        const uint32_t i = 64u * k + lane;
-                        if (i < (uint32_t)(kTables * S)) level_reg[b][k] = tables[i];
+                for (uint32_t f = 0; f < FLIGHT; ++f) {
+                    if ((g0 + f) * K >= num_workers) continue;  // (wave-uniform) no such look-up
+#pragma unroll
+                    for (int i = 0; i < K; ++i) {
+#pragma unroll
+                        for (int k = 0; k < WR; ++k)
+                            if (64u * k + lane < (uint32_t)WD) staged_codes[wave][f][i][64u * k + lane] = fetched[f][i][k];
+                        if (lane < (uint32_t)(kTables * S)) raw_levels[wave][f][i * (kTables * S) + lane] = level_reg[f][i];
+                    }
+                }
+                wave_lds_fence();
+                // the rows in the order of the look-up index: row (group j, worker i, plane p) is number j * IDX + i * BITS + p
+                uint32_t code_reg[FLIGHT][RR];
+#pragma unroll
+                for (int q = 0; q < RR; ++q) {
+                    const uint32_t r = 32u * q + row;  // row of code bits this lane takes its half of
+                    const uint32_t j = r / IDX, rem = r % IDX, i = rem / BITS, plane = rem % BITS;
+#pragma unroll
+                    for (uint32_t f = 0; f < FLIGHT; ++f) {
+                        code_reg[f][q] = 0u;
+                        if ((g0 + f) * K < num_workers) code_reg[f][q] = staged_codes[wave][f][i][2u * (j * BITS + plane) + half];
+                    }
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (uint32_t f = 0; f < FLIGHT; ++f) {
+                    if ((g0 + f) * K < num_workers && lane < (uint32_t)ENTRIES) {
+#pragma unroll
+                        for (int t = 0; t < kTables; ++t) {
+                            double sum = 0.0;
+#pragma unroll
+                            for (int i = 0; i < K; ++i) {
+                                uint32_t index = (lane >> (i * BITS)) & ((1u << BITS) - 1u);
+                                index = index < (uint32_t)S ? index : (uint32_t)(S - 1);  // (an index that never occurs)
+                                sum += (double)raw_levels[wave][f][(i * kTables + t) * S + index];
+                            }
+                            sum_tables[wave][f][t][lane] = sum;
+                        }
+                    }
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (uint32_t f = 0; f < FLIGHT; ++f) {
+                    if ((g0 + f) * K < num_workers) {
+                        uint32_t turned[RR];
+#pragma unroll
+                        for (int q = 0; q < RR; ++q) turned[q] = bit_transpose(code_reg[f][q], turn, lane);
+                        for_each_group<IDX, 0>(turned, [&](auto j, uint32_t index) {
+                            acc[decltype(j)::value] += sum_tables[wave][f][decltype(j)::value / kWpb][index];
+                        });
                     }
                 }
             }
+          }
+        }
+        if (!combined) {
+            // One worker per look-up: fp32 level tables in LDS.  A single worker's average is its level itself.
+            constexpr int R = (kSpanWords * BITS + 31) / 32;  // registers for the 16 * BITS rows of code bits
+            constexpr int LR = (kTables * S + 63) / 64;       // registers for the kTables * S level values
+            constexpr uint32_t BATCH = R + LR > 2 ? 4 : 8;    // workers whose loads are in flight together
+            __shared__ float level_tables[kWavesPerBlock][BATCH * kTables * S];
+            float* my_tables = level_tables[wave];
+            const bool one_worker = num_workers == 1u;
+            for (uint32_t w0 = 0; w0 < num_workers; w0 += BATCH) {
+                uint32_t code_reg[BATCH][R];
+                float level_reg[BATCH][LR];
 #pragma unroll
-            for (uint32_t b = 0; b < BATCH; ++b) {
-                if (w0 + b < num_workers) {
+                for (uint32_t b = 0; b < BATCH; ++b) {
 #pragma unroll
-                    for (int t = 0; t < kTables; ++t) {
-                        float lv[S];
+                    for (int k = 0; k < R; ++k) code_reg[b][k] = 0u;
 #pragma unroll
-                        for (int k = 0; k < S; ++k) {
-                            const int at = t * S + k;
-                            lv[k] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(level_reg[b][at / 64]), at % 64));
+                    for (int k = 0; k < LR; ++k) level_reg[b][k] = 0.0f;
+                    if (w0 + b < num_workers) {
+                        const uint32_t* c32 = reinterpret_cast<const uint32_t*>(ptrs.codes[w0 + b] + (size_t)word0 * BITS);
+                        const float* tables = ptrs.levels[w0 + b] + (size_t)first_bucket * S;
+#pragma unroll
+                        for (int k = 0; k < R; ++k) {
+                            const uint32_t r = 32u * k + row;  // row of code bits this lane fetches its half of
+                            if (r < (uint32_t)(kSpanWords * BITS)) code_reg[b][k] = c32[2u * r + half];
                         }
 #pragma unroll
-                        for (int j = t * (WPB > 0 ? WPB : 1); j < (t + 1) * (WPB > 0 ? WPB : 1); ++j) {
-                            bool bit[4] = {false, false, false, false};
-#pragma unroll
-                            for (int p = 0; p < BITS; ++p) {
-                                const int d0 = 2 * (j * BITS + p), d1 = d0 + 1;
-                                const uint32_t lo = __builtin_amdgcn_readlane(code_reg[b][d0 / 64], d0 % 64);
-                                const uint32_t hi = __builtin_amdgcn_readlane(code_reg[b][d1 / 64], d1 % 64);
-                                bit[p] = __builtin_amdgcn_inverse_ballot_w64(((uint64_t)hi << 32) | lo);
-                            }
-                            acc[j] += (double)select_from_bits<BITS, S>(bit, lv);
+                        for (int k = 0; k < LR; ++k) {
+                            const uint32_t i = 64u * k + lane;
+                            if (i < (uint32_t)(kTables * S)) level_reg[b][k] = tables[i];
                         }
+                    }
+                }
+                wave_lds_fence();  // the reads of the batch before are done
+#pragma unroll
+                for (uint32_t b = 0; b < BATCH; ++b) {
+#pragma unroll
+                    for (int k = 0; k < LR; ++k) {
+                        const uint32_t i = 64u * k + lane;
+                        if (i < (uint32_t)(kTables * S)) my_tables[b * (kTables * S) + i] = level_reg[b][k];
+                    }
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (uint32_t b = 0; b < BATCH; ++b) {
+                    if (w0 + b < num_workers) {
+                        uint32_t turned[R];
+#pragma unroll
+                        for (int k = 0; k < R; ++k) turned[k] = bit_transpose(code_reg[b][k], turn, lane);
+                        const float* table = my_tables + b * (kTables * S);
+                        if (one_worker) {
+                            float* __restrict__ o1 = out + (size_t)word0 * 64 + lane;
+                            for_each_group<BITS, 0>(turned, [&](auto j, uint32_t index) {
+                                // written once, never re-read here
+                                __builtin_nontemporal_store(table[(decltype(j)::value / kWpb) * S + index], o1 + 64 * decltype(j)::value);
+                            });
+                            return;
+                        }
+                        for_each_group<BITS, 0>(turned, [&](auto j, uint32_t index) {
+                            acc[decltype(j)::value] += (double)table[(decltype(j)::value / kWpb) * S + index];
+                        });
                     }
                 }
             }
