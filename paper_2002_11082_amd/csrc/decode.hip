@@ -113,7 +113,8 @@ __device__ __forceinline__ uint32_t bit_transpose_step(uint32_t x, const BitTran
 {
     const uint32_t y = lane_xor<DIST>(x, lane);
     const uint32_t turned = __builtin_amdgcn_alignbit(y, y, t.turn[STEP]);
-    return (t.take[STEP] & turned) | (~t.take[STEP] & x);  // v_bfi_b32
+    // take ? turned : x, bit by bit, in one instruction (v_bitop3_b32, truth table 0xCA)
+    return __builtin_amdgcn_bitop3_b32(t.take[STEP], turned, x, 0xCA);
 }
 
 __device__ __forceinline__ uint32_t bit_transpose(uint32_t x, const BitTranspose& t, uint32_t lane)
@@ -130,9 +131,16 @@ template <int BITS, int J, int R>
 __device__ __forceinline__ uint32_t level_index(const uint32_t (&turned)[R])
 {
     constexpr int kFirst = BITS * J, kReg = kFirst / 32, kShift = kFirst % 32;
-    uint32_t bits = turned[kReg] >> kShift;
-    if constexpr (kShift + BITS > 32) bits |= turned[kReg + 1] << (32 - kShift);
-    return bits & ((1u << BITS) - 1u);
+    uint32_t index;
+    if constexpr (kShift + BITS <= 32) {
+        index = __builtin_amdgcn_ubfe(turned[kReg], (uint32_t)kShift, (uint32_t)BITS);  // one v_bfe_u32
+    } else {
+        index = __builtin_amdgcn_alignbit(turned[kReg + 1], turned[kReg], (uint32_t)kShift) & ((1u << BITS) - 1u);
+    }
+    // (kept as it is: folded into the address arithmetic, the extraction turns into a shift, a mask and an addition
+    // instead of this bit-field extract and one shift-and-add)
+    asm("" : "+v"(index));
+    return index;
 }
 
 // Runs f(J, index of word group J) for the 16 word groups of a span; an index has BITS bits.

@@ -548,23 +548,46 @@ __device__ __forceinline__ uint32_t exact_floor_t(unsigned long long* limb, uint
     return lo;
 }
 
+// The two forms the kernels call, as real functions: inlined into every level solve, this rare path cost the kernels
+// 3 to 20 % of their speed (code size, registers) without ever running.
+//   bucket grouped in LDS: the calling lanes take the positions lane, lane + stride, ... below len
+static __device__ __attribute__((noinline)) uint32_t exact_floor_t_grouped(unsigned long long* limb, const uint32_t* grouped,
+                                                                   uint32_t len, uint32_t lane, uint32_t stride, float L,
+                                                                   float R, uint32_t count_in, uint32_t guess)
+{
+    return exact_floor_t(limb, lane, L, R, count_in, guess, [&](auto add) {
+        for (uint32_t i = lane; i < len; i += stride) add(__uint_as_float(grouped[skewed(i)]));
+    });
+}
+
+//   small bucket in registers: every lane of the bucket's group brings four elements, `valid` of which exist
+static __device__ __attribute__((noinline)) uint32_t exact_floor_t_registers(unsigned long long* limb, uint32_t lane_in_group,
+                                                                     float L, float R, uint32_t count_in, uint32_t guess,
+                                                                     float x0, float x1, float x2, float x3, uint32_t valid)
+{
+    return exact_floor_t(limb, lane_in_group, L, R, count_in, guess, [&](auto add) {
+        if (valid > 0u) add(x0);
+        if (valid > 1u) add(x1);
+        if (valid > 2u) add(x2);
+        if (valid > 3u) add(x3);
+    });
+}
+
 // floor(T) of one solve from the fp64 sums (see above): Ssum = the sums' S, width = R - L > 0 in fp64, bound = the
 // bucket's sum_error_bound (0: every sum is exact).  Returns false when the sums do not decide; m is then the guess for
-// exact_floor_t.
-__device__ __forceinline__ bool floor_t_from_sums(double Ssum, double width, uint32_t count_in, double bound, double& m)
+// exact_floor_t.  The common case costs a division, a floor, a fused multiply-add for the rest and two comparisons;
+// a rest of exactly 0 (T an integer) or outside [0, width) takes the second branch.
+__device__ __forceinline__ bool floor_t_from_sums(double Ssum, double width, double bound, double& m)
 {
-    m = floor(Ssum / width);
-    if (!(m >= 0.0)) m = 0.0;  // (also catches NaN from non-finite input)
-    if (m > (double)count_in) m = (double)count_in;
-    const double rest = Ssum - m * width;
-    if (bound == 0.0) {
-        // exact sums, exact rest: the rounding of the quotient can be off by one
-        if (rest < 0.0) m -= 1.0;
-        else if (rest >= width) m += 1.0;
-        if (!(m >= 0.0)) m = 0.0;
-        return true;
-    }
-    return rest > bound && width - rest > bound;
+    m = fmax(floor(Ssum / width), 0.0);  // (NaN from non-finite input becomes 0)
+    const double rest = __builtin_fma(-m, width, Ssum);  // exact when bound == 0: m * width has at most 41 bits
+    if (rest > bound && width - rest > bound) return true;
+    if (bound != 0.0) return false;
+    // exact sums, exact rest: the rounding of the quotient can have put m one off
+    if (rest < 0.0) m -= 1.0;
+    else if (rest >= width) m += 1.0;
+    m = fmax(m, 0.0);
+    return true;
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -735,12 +758,11 @@ __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k,
         const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)count_in;
         const double width = (double)R - (double)L;
         double m;
-        if (!floor_t_from_sums(Ssum, width, count_in, uniform_f64(lds.sum_error_bound), m)) {
+        if (!floor_t_from_sums(Ssum, width, uniform_f64(lds.sum_error_bound), m)) {
             // the fp64 sums do not decide floor(T): exact sums of the elements in [L, R] (rare)
-            m = (double)exact_floor_t(lds.exact_limb[(threadIdx.x >> 6) & (sizeof(lds.exact_limb) / sizeof(lds.exact_limb[0]) - 1u)],
-                                      lane, L, R, count_in, (uint32_t)m, [&](auto add) {
-                for (uint32_t i = lane; i < len; i += kWave) add(__uint_as_float(lds.grouped[skewed(i)]));
-            });
+            m = (double)exact_floor_t_grouped(
+                lds.exact_limb[(threadIdx.x >> 6) & (sizeof(lds.exact_limb) / sizeof(lds.exact_limb[0]) - 1u)], lds.grouped, len,
+                lane, kWave, L, R, count_in, (uint32_t)m);
         }
         rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
         rank = rank < 1u ? 1u : (rank > len ? len : rank);
@@ -831,34 +853,61 @@ constexpr TeamGreedy team_greedy()
     return g;
 }
 
-// The greedy steps are unrolled (their level indices are compile-time constants: measured 7 % faster on 8 levels
-// than one loop over a packed table).
+// One wavefront's greedy steps packed for a run-time loop: 12 bits (k | l << 4 | r << 8) per step, five steps per word.
+struct TeamSteps {
+    uint64_t packed[2][2];  // [wavefront][word]
+};
+
+template <int S>
+constexpr TeamSteps team_steps(bool with_sweeps)
+{
+    const TeamGreedy g = team_greedy<S>();
+    TeamSteps t{{{0, 0}, {0, 0}}};
+    for (int w = 0; w < 2; ++w)
+        for (int step = 0; step < g.steps; ++step) {
+            uint64_t e = g.entry[w][step];
+            if (w == 0 && with_sweeps) {  // head start of the first sweep
+                if (g.head_step[0] == step) e = 1u | (0u << 4) | (2u << 8);
+                if (g.head_step[1] == step) e = 2u | (1u << 4) | (3u << 8);
+            }
+            t.packed[w][step / 5] |= e << (12 * (step % 5));
+        }
+    return t;
+}
+
+// The solves run in one loop over the steps, so that the kernel holds the solve routine (with its selection in crowded
+// bins and its exact sums) once: unrolled, an eight-level kernel no longer fits the instruction cache.
 template <int S, class Lds, class PickFn>
 __device__ __forceinline__ void orq_team_solve(Lds& lds, PickFn pick, uint32_t wave, uint32_t len, uint32_t sweeps,
                                                uint32_t lane)
 {
     constexpr TeamGreedy greedy = team_greedy<S>();
+    constexpr TeamSteps plain = team_steps<S>(false), ahead = team_steps<S>(true);
     constexpr uint32_t INTERIOR = S - 2;
-#pragma unroll
-    for (int step = 0; step < greedy.steps; ++step) {
-        if (wave < 2u) {
-            const uint32_t e = wave == 0u ? greedy.entry[0][step] : greedy.entry[1][step];
-            if (e != 0u) orq_solve_one(lds, pick, e & 15u, (e >> 4) & 15u, (e >> 8) & 15u, len, lane);
-            if (wave == 0u && sweeps > 0u) {  // head start of the first sweep
-                if (greedy.head_step[0] == step) orq_solve_one(lds, pick, 1u, 0u, 2u, len, lane);
-                if (greedy.head_step[1] == step) orq_solve_one(lds, pick, 2u, 1u, 3u, len, lane);
-            }
+    static_assert(greedy.steps <= 10, "two words of five steps");
+    const uint32_t mine = wave < 2u ? wave : 0u;
+    const uint64_t word0 = sweeps > 0u ? ahead.packed[mine][0] : plain.packed[mine][0];
+    const uint64_t word1 = sweeps > 0u ? ahead.packed[mine][1] : plain.packed[mine][1];
+    // steps of the sweeps: two sweeps at a time take INTERIOR + 2 steps, a last single one INTERIOR; the first pair
+    // starts greedy.head steps in (those solves ran beside the greedy ones)
+    const uint32_t pairs = sweeps / 2u, single = sweeps & 1u;
+    const uint32_t sweep_steps = pairs * (INTERIOR + 2u) + single * INTERIOR;
+    const uint32_t head = sweeps > 0u ? (uint32_t)greedy.head : 0u;
+    const uint32_t total = (uint32_t)greedy.steps + (sweep_steps > head ? sweep_steps - head : 0u);
+    for (uint32_t step = 0; step < total; ++step) {
+        uint32_t e = 0u;
+        if (step < (uint32_t)greedy.steps) {
+            e = (uint32_t)((step < 5u ? word0 >> (12u * step) : word1 >> (12u * (step - 5u))) & 0xFFFu);
+        } else {
+            const uint32_t u = step - (uint32_t)greedy.steps + head;  // step among all sweep steps
+            const uint32_t pair_index = u / (INTERIOR + 2u);
+            const bool in_pair = pair_index < pairs;
+            const uint32_t t = in_pair ? u - pair_index * (INTERIOR + 2u) : u - pairs * (INTERIOR + 2u);
+            if (wave == 0u && t < INTERIOR) e = (t + 1u) | (t << 4) | ((t + 2u) << 8);
+            if (wave == 1u && in_pair && t >= 2u) e = (t - 1u) | ((t - 2u) << 4) | (t << 8);
         }
+        if (wave < 2u && e != 0u) orq_solve_one(lds, pick, e & 15u, (e >> 4) & 15u, (e >> 8) & 15u, len, lane);
         __syncthreads();
-    }
-    for (uint32_t s = 0; s < sweeps; s += 2u) {
-        const bool pair = s + 1u < sweeps;
-        const uint32_t steps = INTERIOR + (pair ? 2u : 0u);
-        for (uint32_t t = (s == 0u ? (uint32_t)greedy.head : 0u); t < steps; ++t) {
-            if (wave == 0u && t < INTERIOR) orq_solve_one(lds, pick, t + 1u, t, t + 2u, len, lane);
-            if (wave == 1u && pair && t >= 2u) orq_solve_one(lds, pick, t - 1u, t - 2u, t, len, lane);
-            __syncthreads();
-        }
     }
 }
 
@@ -1706,14 +1755,12 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
                 const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)count_in;
                 const double width = (double)R - (double)L;
                 double m;  // not used when L == R
-                const bool decided = floor_t_from_sums(Ssum, width, count_in, error_bound, m);
+                const bool decided = floor_t_from_sums(Ssum, width, error_bound, m);
                 if (ordered && !decided) {
                     // (as in orq_solve_one: exact sums where the fp64 sums do not decide; only the lanes of such buckets)
-                    m = (double)exact_floor_t(limb, lane & (G - 1u), L, R, count_in, (uint32_t)m, [&](auto add) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (l4 + i < count) add(key_to_float(x[i]));
-                    });
+                    m = (double)exact_floor_t_registers(limb, lane & (G - 1u), L, R, count_in, (uint32_t)m, key_to_float(x[0]),
+                                                        key_to_float(x[1]), key_to_float(x[2]), key_to_float(x[3]),
+                                                        count > l4 ? count - l4 : 0u);
                 }
                 const bool whole = m >= (double)cnt_le_R;
                 uint32_t rank = whole ? 1u : cnt_le_R - (uint32_t)(whole ? 0.0 : m);
@@ -1756,14 +1803,13 @@ __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, u
             const float L = lv[0], R = lv[2];
             const double Ssum = total - (double)L * (double)count, width = (double)R - (double)L;
             double m;  // not used when L == R
-            const bool decided = floor_t_from_sums(Ssum, width, count, error_bound, m);
+            const bool decided = floor_t_from_sums(Ssum, width, error_bound, m);
             if (L < R && !decided) {
                 // (as in orq_solve_one: exact sums where the fp64 sums do not decide; only the lanes of such buckets)
-                m = (double)exact_floor_t(limb, lane & (G - 1u), L, R, count, (uint32_t)m, [&](auto add) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (4u * (lane & (G - 1u)) + i < count) add(key_to_float(x[i]));
-                });
+                const uint32_t mine = 4u * (lane & (G - 1u));
+                m = (double)exact_floor_t_registers(limb, lane & (G - 1u), L, R, count, (uint32_t)m, key_to_float(x[0]),
+                                                    key_to_float(x[1]), key_to_float(x[2]), key_to_float(x[3]),
+                                                    count > mine ? count - mine : 0u);
             }
             if (m > (double)count) m = (double)count;
             uint32_t rank = m >= (double)count ? 1u : count - (uint32_t)m;
