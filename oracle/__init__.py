@@ -16,6 +16,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ogq_oracle.c")
 _LIB = os.path.join(_HERE, "libogq_oracle.so")
+# A test may point the loader at another build of the same source (the sanitizer build of tests/test_sanitizers.py).
+_OVERRIDE = os.environ.get("OGQ_ORACLE_LIBRARY")
 
 BINGRAD_B = 0
 ORQ = 1
@@ -41,8 +43,9 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        if not _OVERRIDE:
+            build()
+        L = ctypes.CDLL(_OVERRIDE or _LIB)
         u32, u64, sz = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
         vp = ctypes.c_void_p
         L.ogq_oracle_philox4x32_10.argtypes = [vp, vp, vp]

@@ -6,7 +6,8 @@ import ctypes
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libogq.so")
+# OGQ_LIBRARY names another build of the same C ABI (e.g. a host build with sanitizers for the argument checks).
+LIB_PATH = os.environ.get("OGQ_LIBRARY") or os.path.join(_PKG, "libogq.so")
 
 BINGRAD_B = 0
 ORQ = 1
