@@ -84,10 +84,10 @@ def wavefronts_per_bucket(two_level_means: bool, d: int) -> int:
 class Measurement:
     """Device buffers and marshalled C-ABI arguments of one workload, and the timing loops over them."""
 
-    def __init__(self, name: str, torch, np, ogq, synth, dev, stream, buffers: int = 0):
+    def __init__(self, name: str, torch, np, ogq, synth, dev, stream, buffers: int = 0, elements: int = 0):
         self.torch, self.ogq = torch, ogq
         self.wl = wl = synth.WORKLOADS[name]
-        self.n, self.d, self.bits, self.W = wl.n, wl.bucket_size, wl.bits, wl.workers
+        self.n, self.d, self.bits, self.W = elements or wl.n, wl.bucket_size, wl.bits, wl.workers
         n, d, bits, W = self.n, self.d, self.bits, self.W
         self.grad_bytes = 4 * n * W
         self.n_buf = buffers or max(2, -(-(1 << 30) // self.grad_bytes) + 1)
@@ -95,7 +95,7 @@ class Measurement:
             self.n_buf = max(self.n_buf, 10)
         # Buffer 0 is the workload's own seeded gradient(s); the others hold the same values rolled by a
         # different amount (same distribution, different bytes at every address).
-        self.host = [wl.gradient(w) for w in range(W)]
+        self.host = [wl.gradient(w, n) for w in range(W)]
         self.grads = [[torch.from_numpy(np.roll(h, 7919 * b) if b else h).to(dev) for h in self.host]
                       for b in range(self.n_buf)]
         self.params = [ogq.make_params(d, bits, wl.scheme, wl.level_iters, wl.philox_seed(w), 0, wl.clip_factor)
@@ -257,9 +257,12 @@ class Measurement:
         buckets = (self.n + self.d - 1) // self.d
         lane_ops = valu_per_wave * 64 * wavefronts_per_bucket(self.two_level_means, self.d) * buckets
         achieved = lane_ops / (q_ms * 1e-3) / 1e12
+        simds = 256 * 4
         e = {"bound": "alu", "kernel": self.quant_name, "achieved": round(achieved, 2), "peak": ALU_PEAK_TLANEOPS,
              "unit": "T lane-op/s", "frac": round(achieved / ALU_PEAK_TLANEOPS, 4),
              "valu_instructions_per_wavefront": valu_per_wave,
+             # the launch time spread over the VALU instructions a SIMD issues: the kernel's own issue rate
+             "ns_per_valu_instruction_and_simd": round(q_ms * 1e6 * simds / (lane_ops / 64), 3),
              "source": "profiles/valu_instructions.txt (recorded counter run); every instruction counted as one issue slot, "
                        "although fp64, 32-bit multiply and conversion instructions take about 1.7 slots"}
         busy = read_note("valu_busy.txt", f"{workload}:{self.quant_name}")
@@ -282,6 +285,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--buffers", type=int, default=0, help="distinct input buffers (0 = enough for 1 GB)")
+    ap.add_argument("--elements", type=int, default=0,
+                    help="gradient length per worker instead of the workload's own (its recipe at another size, for size scans)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true",
                     help="skip the per-kernel figures of the other four configurations")
@@ -310,7 +315,7 @@ def main() -> int:
     torch.cuda.set_stream(stream)
 
     # ---- the headline workload: K whole steps, then each kernel on its own -------------------------------
-    m = Measurement(args.workload, torch, np, ogq, synth, dev, stream, args.buffers)
+    m = Measurement(args.workload, torch, np, ogq, synth, dev, stream, args.buffers, args.elements)
     wl, n, d, bits, W = m.wl, m.n, m.d, m.bits, m.W
     ms_per_step, gpu_ms_per_step = m.time_steps(args.steps, args.warmup, args.graph)
     q_ms, warm_ms, cold_ms = m.time_kernels(args.steps)
@@ -343,7 +348,7 @@ def main() -> int:
         "gpu_ms_per_step": round(gpu_ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 data, f64 sums", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: {wl.description}", "n": n, "bucket_size": d, "bits": bits,
+        "config": {"workload": f"{wl.name}: {wl.description}" + (f" (recipe at {n} elements)" if args.elements else ""), "n": n, "bucket_size": d, "bits": bits,
                    "workers": W, "level_iters": wl.level_iters, "clip_factor": wl.clip_factor,
                    "input_buffers": m.n_buf, "decoder_input_sets": m.n_sets,
                    "launch": "one HIP graph of the K steps" if args.graph else "direct"},

@@ -49,10 +49,10 @@ __device__ __forceinline__ void bingrad_bucket(Team team, uint32_t first_element
     float largest = wave_max(mag);
     team.sum_and_max(total, largest);
     float b0 = (float)(total / (double)len);  // threshold starts at the bucket mean
-    // The upper sum is taken as total - lower sum.  Both are fp64 sums of at most 4096 fp32 values
-    // (error below 2^-53 * n^2 * max|v| each, and exact for any bucket whose values span fewer than
-    // ~18 binades), so the difference is trusted unless it is tiny against the largest element; such
-    // a bucket sums its upper side directly.
+    // The upper sum is taken as total - lower sum.  Both are fp64 sums of the bucket's n <= 32768 fp32 values
+    // (error below 2^-53 * n^2 * max|v| each, and exact for any bucket whose non-zero values span at most
+    // 28 - log2(n) binades: 17 for 2048 elements, 13 for 32768), so the difference is trusted unless it is tiny
+    // against the largest element; such a bucket sums its upper side directly.
     const float trust_above = 1e-3f * largest;
 
     double b_lo = 0.0, b_hi = 0.0;

@@ -575,19 +575,24 @@ static __device__ __attribute__((noinline)) uint32_t exact_floor_t_registers(uns
 
 // floor(T) of one solve from the fp64 sums (see above): Ssum = the sums' S, width = R - L > 0 in fp64, bound = the
 // bucket's sum_error_bound (0: every sum is exact).  Returns false when the sums do not decide; m is then the guess for
-// exact_floor_t.  The common case costs a division, a floor, a fused multiply-add for the rest and two comparisons;
-// a rest of exactly 0 (T an integer) or outside [0, width) takes the second branch.
+// exact_floor_t.  The quotient only proposes m (a reciprocal and a product instead of a division: any m whose rest
+// S - m width lies inside (bound, width - bound) is the floor); the common case costs the reciprocal, a product, a
+// floor, a fused multiply-add for the rest and two comparisons.  A rest of exactly 0 (T an integer) or outside
+// [0, width) takes the second branch, which moves m by one where the quotient's rounding asks for it.
 __device__ __forceinline__ bool floor_t_from_sums(double Ssum, double width, double bound, double& m)
 {
-    m = fmax(floor(Ssum / width), 0.0);  // (NaN from non-finite input becomes 0)
-    const double rest = __builtin_fma(-m, width, Ssum);  // exact when bound == 0: m * width has at most 41 bits
+    m = fmax(floor(Ssum * __builtin_amdgcn_rcp(width)), 0.0);  // (NaN from non-finite input becomes 0)
+    double rest = __builtin_fma(-m, width, Ssum);  // exact when bound == 0: m * width has at most 41 bits
     if (rest > bound && width - rest > bound) return true;
-    if (bound != 0.0) return false;
-    // exact sums, exact rest: the rounding of the quotient can have put m one off
-    if (rest < 0.0) m -= 1.0;
-    else if (rest >= width) m += 1.0;
-    m = fmax(m, 0.0);
-    return true;
+    if (rest < 0.0) {
+        m = fmax(m - 1.0, 0.0);
+        rest = __builtin_fma(-m, width, Ssum);
+    } else if (rest >= width) {
+        m += 1.0;
+        rest = __builtin_fma(-m, width, Ssum);
+    }
+    if (bound == 0.0) return true;  // exact sums, exact rest: 0 <= rest < width now
+    return rest > bound && width - rest > bound;
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
