@@ -65,14 +65,24 @@ __device__ __forceinline__ uint32_t writelane(uint32_t dst, uint32_t value, int 
     return ogq_llvm_writelane(value, (uint32_t)lane, dst);
 }
 
-// Wave-wide sum; the result is wave-uniform.
+// Wave-wide sum; the result is wave-uniform.  Four butterfly steps leave every row's sum in all of its lanes; two row
+// broadcasts (DPP row_bcast:15 into rows 1 and 3, row_bcast:31 into rows 2 and 3) then add them up as (r0 + r1) + (r2 + r3)
+// in the last row, from which one lane is read.
 __device__ __forceinline__ double wave_sum(double x)
 {
     x += dpp_f64<kDppXor1>(x);
     x += dpp_f64<kDppXor2>(x);
     x += dpp_f64<kDppHalfMirror>(x);
     x += dpp_f64<kDppMirror>(x);
-    return (readlane_f64(x, 0) + readlane_f64(x, 16)) + (readlane_f64(x, 32) + readlane_f64(x, 48));
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo15 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, 0x142, 0xA, 0xF, false);
+    const uint32_t hi15 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), 0x142, 0xA, 0xF, false);
+    x += __longlong_as_double((long long)(((uint64_t)hi15 << 32) | lo15));  // rows 0 and 2 add +0.0
+    const uint64_t w = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo31 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)w, 0x143, 0xC, 0xF, false);
+    const uint32_t hi31 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(w >> 32), 0x143, 0xC, 0xF, false);
+    x += __longlong_as_double((long long)(((uint64_t)hi31 << 32) | lo31));
+    return readlane_f64(x, 63);
 }
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
