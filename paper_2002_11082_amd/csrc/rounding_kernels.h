@@ -703,10 +703,11 @@ __device__ __forceinline__ void orq_encode(const float (&v)[C][4], const float (
 // Whether the bucket holds a non-zero element more than safe_binades(capacity) binades below its largest magnitude
 // (mag_max = its bit pattern), i.e. whether its fp64 sums may round.  Such elements sit in the bins next to zero: the
 // two centre bins, which take everything below the binned range, and above 4096 elements also the lowest regular bins.
-// Called by one whole wavefront once the bucket is grouped; the result is wave-uniform.
+// Called by `threads` threads (thread = 0 .. threads - 1) once the bucket is grouped; every thread looks at its share
+// of those bins and returns what it saw: the caller combines the answers.
 template <int HALF, int SHIFT, class Lds>
 __device__ __forceinline__ bool any_tiny_element(const Lds& lds, uint32_t capacity, uint32_t mag_max, uint32_t t_low,
-                                                 uint32_t lane)
+                                                 uint32_t thread, uint32_t threads)
 {
     const uint32_t safe = safe_binades(capacity);
     const uint32_t biased = mag_max >> 23;
@@ -718,11 +719,11 @@ __device__ __forceinline__ bool any_tiny_element(const Lds& lds, uint32_t capaci
     const uint32_t first = uniform_u32(lds.bin_start[(uint32_t)HALF - bins]);
     const uint32_t last = uniform_u32(lds.bin_start[(uint32_t)HALF + bins]);
     bool tiny = false;
-    for (uint32_t i = first + lane; i < last; i += kWave) {
+    for (uint32_t i = first + thread; i < last; i += threads) {
         const uint32_t magnitude = lds.grouped[skewed(i)] & 0x7FFFFFFFu;
         tiny = tiny || (magnitude != 0u && magnitude < mag_safe);
     }
-    return __ballot(tiny) != 0;
+    return tiny;
 }
 
 // Where the levels come from; all rules share the random-rounding encoder.
@@ -1279,7 +1280,7 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         __builtin_amdgcn_wave_barrier();
 
         if constexpr (RULE == kOptimal && S > 2) {
-            const bool tiny = any_tiny_element<HALF, SHIFT>(lds, (uint32_t)D, mag_max, t_low, lane);
+            const bool tiny = __ballot(any_tiny_element<HALF, SHIFT>(lds, (uint32_t)D, mag_max, t_low, lane, kWave)) != 0;
             if (lane == 0u) lds.sum_error_bound = tiny ? sum_error_bound_of(mag_max, (uint32_t)D) : 0.0;
             wave_lds_sync();
         }
@@ -1873,6 +1874,7 @@ struct OrqTeamLds {
     uint32_t lvl_count_le[10];
     uint32_t lvl_rank[10];
     double sum_error_bound;  // 0 when every fp64 sum of the bucket is exact (see floor_t_from_sums)
+    uint32_t tiny_flag;      // set by any thread that met an element too small for exact sums
     unsigned long long exact_limb[2][kExactLimbs];  // workspace of exact_floor_t, one per solving wavefront
     TeamSlot slots[2][W];
 };
@@ -1966,6 +1968,7 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
     if constexpr ((S > 2 && RULE != kEven) || PB) {
         // ---- histogram: the returning LDS add hands every element its position inside its bin ------------
         for (uint32_t i = tid; i < (uint32_t)B; i += THREADS) lds.bin_start[i] = 0u;
+        if (tid == 0u) lds.tiny_flag = 0u;
         __syncthreads();
         uint32_t slot[C][4];  // bin | position inside the bin << 16
         for_each_chunk<C, FULL>(my_len, [&](int c, auto all) {
@@ -2019,6 +2022,12 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
         }
         __syncthreads();
 
+        // ---- may the fp64 sums round?  (all threads look; combined before the records below are written) ----
+        if constexpr (RULE == kOptimal && S > 2) {
+            if (any_tiny_element<HALF, SHIFT>(lds, (uint32_t)OrqTeamLds<W, C>::D, mag_max, t_low, tid, THREADS))
+                atomicOr(&lds.tiny_flag, 1u);
+        }
+
         // ---- fp64 prefix of the grouped values per block of 4C positions (thread t sums block t) ----------
         // Skipped, but for the bucket's total, by the rules whose solves read no picked level's counts or sums.
         constexpr bool SUMS = (RULE == kOptimal && S > 3) || PB;
@@ -2064,18 +2073,13 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
                 lds.lvl_sum_le[S - 1] = total;
                 lds.lvl_count_lt[S - 1] = len;
                 lds.lvl_sum_lt[S - 1] = total;
+                // (every thread's look at the small elements lies before the barrier of the exchange above)
+                if constexpr (RULE == kOptimal && S > 2)
+                    lds.sum_error_bound = lds.tiny_flag != 0u ? sum_error_bound_of(mag_max, (uint32_t)OrqTeamLds<W, C>::D) : 0.0;
             }
             if (tid < (uint32_t)S) {
                 lds.lvl_value[tid] = key_to_float(tid == (uint32_t)(S - 1) ? key_max : key_min);
                 lds.lvl_rank[tid] = 0u;
-            }
-        }
-        if constexpr (RULE == kOptimal && S > 2) {
-            // (the grouped values and the bin starts have been complete since the barrier after the scatter)
-            if (wave == 0u) {
-                const bool tiny = any_tiny_element<HALF, SHIFT>(lds, (uint32_t)OrqTeamLds<W, C>::D, mag_max, t_low, lane);
-                if (lane == 0u)
-                    lds.sum_error_bound = tiny ? sum_error_bound_of(mag_max, (uint32_t)OrqTeamLds<W, C>::D) : 0.0;
             }
         }
         __syncthreads();
@@ -2120,8 +2124,11 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
     orq_encode<C, S, BITS, FULL>(v, lv, my_len, begin + first, seed, index_offset, codes32);
 }
 
+// C = 8 (2048 elements per wavefront): the LDS of a CU holds the buckets of 16 wavefronts, so the kernel is held to the
+// 128 registers that let four wavefronts share a SIMD (one register more costs d = 8192 a quarter of its wavefronts);
+// BinGrad-pb would spill.
 template <int W, int C, int S, int BITS, int RULE>
-__global__ __launch_bounds__(W* kWave) void orq_team_kernel(const float* __restrict__ grad, size_t n,
+__global__ __launch_bounds__(W* kWave) __attribute__((amdgpu_waves_per_eu(C == 8 && RULE != kPb ? 4 : 1))) void orq_team_kernel(const float* __restrict__ grad, size_t n,
                                                             uint32_t bucket_size, uint32_t sweeps, float clip,
                                                             uint32_t num_buckets, uint64_t seed, uint64_t index_offset,
                                                             float* __restrict__ levels, uint32_t* __restrict__ codes32)
