@@ -424,12 +424,13 @@ __device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t r
 //
 // Fast path.  The sums a solve reads are fp64 sums of fp32 values.  They are exact, whatever their order, when every
 // non-zero element of the bucket is at most safe_binades(len) binades below the largest magnitude M < 2^(E+1): every
-// element is then a multiple of q = 2^(E - safe - 23), every intermediate value (prefix sums below len * M, S and
-// m (R - L) below 4 len M) is a multiple of q below 2^53 q, so no addition, difference or product ever rounds.  With
+// element is then a multiple of q = 2^(E - safe - 23), every intermediate value (prefix sums below len * M; their
+// differences, S and m (R - L) below 2 len M < len * 2^(E+2)) is a multiple of q below 2^53 q, so no addition,
+// difference or product ever rounds.  With
 // S exact, floor(S / (R - L)) is corrected by at most one through the sign of the exact rest S - m (R - L).  A bucket
 // with smaller non-zero elements ("tiny" ones: they sit in the two centre bins of the grouping) keeps the same
 // arithmetic, but a rest within sum_error_bound of 0 or of R - L does not decide; the bound covers 256 roundings of
-// half a unit in the last place of a value below 4 len M, more than any prefix sum here goes through.
+// half a unit in the last place of a value below 2 len M, more than any prefix sum here goes through.
 //
 // Exact path (undecided solves only).  Every fp32 value is an integer multiple of 2^-149: the elements in [L, R] are
 // added up as signed fixed-point numbers in 11 limbs of 32 payload bits (64-bit LDS atomics; a limb takes at most
@@ -445,7 +446,7 @@ __host__ __device__ constexpr uint32_t ceil_log2(uint32_t n)
 }
 
 // How many binades below the largest magnitude a non-zero element may lie for all fp64 sums of a bucket of at most
-// `capacity` elements to be exact: capacity * 4 M / q <= 2^53 with q = 2^(E - safe - 23) and M < 2^(E+1).
+// `capacity` elements to be exact: capacity * 2 M / q < 2^53 with q = 2^(E - safe - 23) and M < 2^(E+1).
 __host__ __device__ constexpr uint32_t safe_binades(uint32_t capacity) { return 28u - ceil_log2(capacity); }
 
 // What the fp64 sums of a bucket with tiny elements can be off by: 2^(ceil_log2(capacity) + E - 44), E the

@@ -455,6 +455,10 @@ def test_symmetric_buckets_where_t_is_exactly_an_integer(d):
         rng.integers(1, 40, d // 2).astype(np.float64),                           # many equal values
         np.concatenate([rng.normal(0, 1e-40, d // 4), rng.normal(0, 1e-3, d // 2 - d // 4)]),  # subnormals
     ]
+    # magnitudes spread over just as many binades as the fp64 sums of a bucket of this size hold exactly, and two more
+    safe = 28 - int(np.ceil(np.log2(max(d, 64))))
+    for span in (safe, safe + 2):
+        halves.append(rng.uniform(1, 2, d // 2) * 2.0 ** (-rng.integers(0, span + 1, d // 2).astype(np.float64)))
     buckets = []
     for h in halves:
         h = np.abs(h).astype(np.float32)
