@@ -88,9 +88,10 @@ constexpr GreedyOrder greedy_order()
     return o;
 }
 
-// Limbs of the exact sums behind floor(T) (exact_floor_t below): value = sum_i limb[i] * 2^(32 i - 149); |v| < 2^129
-// and |coefficient| < 2^20 fit.
-constexpr int kExactLimbs = 11;
+// Limbs of the exact sums behind floor(T) (exact_floor_t below): value = sum_i limb[i] * 2^(32 i - 149).  An fp32 value
+// starts in limb 7 at the latest and touches three limbs; what the 64 bits of the top limb hold beyond 32 is headroom
+// for the sum and the coefficients, and the carry out of it gives the sign.
+constexpr int kExactLimbs = 10;
 
 // LDS of one bucket: D = element capacity, B = number of bins.
 template <int D_, int B_, int S_>
@@ -100,7 +101,7 @@ struct OrqLds {
     // fp32 bit patterns grouped by bin (-0 lies with +0), unsorted inside a bin.  Position i lives at
     // word i + i/64, so that the 64 lanes reading consecutive blocks of D/64 positions hit distinct banks.
     uint32_t grouped[D + D / 64];
-    uint32_t bin_start[B + 4];  // histogram, then first position of each bin; [B] = bucket length
+    uint32_t bin_start[B + 1];  // histogram, then first position of each bin; [B] = bucket length
     double block_prefix[64];    // fp64 sum of all positions before block l (block = D/64 positions)
     // per level k: value; #{v < value}; #{v <= value}; sum{v < value}; sum{v <= value}; the rank it
     // was picked at (0 = not picked by rank)
@@ -433,7 +434,7 @@ __device__ __forceinline__ Picked pick_rank_by_lookup(const Lds& lds, uint32_t r
 // half a unit in the last place of a value below 2 len M, more than any prefix sum here goes through.
 //
 // Exact path (undecided solves only).  Every fp32 value is an integer multiple of 2^-149: the elements in [L, R] are
-// added up as signed fixed-point numbers in 11 limbs of 32 payload bits (64-bit LDS atomics; a limb takes at most
+// added up as signed fixed-point numbers in 10 limbs of 32 payload bits (64-bit LDS atomics; a limb takes at most
 // 32768 pieces below 2^32 before the carries are propagated), and m is searched with the sign of
 // sum - (c - m) L - m R, c the number of elements in [L, R], which does not grow with m.
 // ----------------------------------------------------------------------------------------------
