@@ -117,6 +117,41 @@ struct OrqLds {
 
 __device__ __forceinline__ uint32_t skewed(uint32_t position) { return position + (position >> 6); }
 
+// Byte offset of a skewed position in the grouped array, as one shift and one add-and-shift (v_add_lshl_u32; written
+// in plain C++ the compiler distributes the shift over the sum and needs three instructions).
+__device__ __forceinline__ uint32_t skewed_byte_offset(uint32_t position)
+{
+    uint32_t offset;
+    asm("v_add_lshl_u32 %0, %1, %2, 2" : "=v"(offset) : "v"(position), "v"(position >> 6));
+    return offset;
+}
+
+// A zero the compiler cannot see through.  x + this turns -0 into +0 like x + 0.0f does, and, unlike that, is not
+// recognised as the same value in a later phase: what is derived from the register-resident bucket is computed again
+// where it is needed instead of being kept in registers (and no copy of x is made to hide it).
+__device__ __forceinline__ float opaque_zero()
+{
+    float zero = 0.0f;
+    asm volatile("" : "+v"(zero));
+    return zero;
+}
+
+// What the histogram keeps per element: the element's position inside its bin in the upper half, and in the lower half
+// the byte offset of its bin's counter from the middle of the bin table (signed, at most +-4096: the low half of the
+// very register that addressed the returning add; one byte permute packs the two).
+__device__ __forceinline__ uint32_t pack_slot(uint32_t position_in_bin, uint32_t bin, uint32_t half)
+{
+    return __builtin_amdgcn_perm(position_in_bin, (bin - half) * 4u, 0x05040100u);
+}
+
+// First position of the slot's bin: table = the middle of the bin-start table (one sign-extending bit-field extract).
+template <class T>
+__device__ __forceinline__ uint32_t slot_bin_start(const T* table_middle, uint32_t slot)
+{
+    const int32_t byte_offset = (int32_t)(int16_t)(slot & 0xFFFFu);
+    return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(table_middle) + byte_offset);
+}
+
 __device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __device__ __forceinline__ uint32_t umax32(uint32_t a, uint32_t b) { return a > b ? a : b; }
 
@@ -610,14 +645,6 @@ __device__ __forceinline__ void for_each_chunk(uint32_t len, F f)
         if (FULL || 256u * (uint32_t)(c + 1) <= len) f(c, std::true_type{});
         else if (256u * (uint32_t)c < len) f(c, std::false_type{});
     }
-}
-
-// Returns x unchanged but hides it from common-subexpression elimination, so that values derived
-// from the register-resident bucket are recomputed in each phase instead of being kept alive.
-__device__ __forceinline__ float recompute_from(float x)
-{
-    asm volatile("" : "+v"(x));
-    return x;
 }
 
 // ---- encode (random rounding, Section 3.1) + pack ------------------------------------------------
@@ -1168,14 +1195,15 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
         for (int t = 0; t < PER; ++t) lds.bin_start[lane * PER + t] = 0u;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        uint32_t slot[C][4];  // bin | position inside the bin << 16
+        uint32_t slot[C][4];  // bin | position inside the bin << 16 (pack_slot)
+        const float zero = opaque_zero();
         for_each_chunk<C, FULL>(len, [&](int c, auto all) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < len);
-                const uint32_t bin = value_bin<HALF, SHIFT>(recompute_from(v[c][k]) + 0.0f, t_low);
+                const uint32_t bin = value_bin<HALF, SHIFT>(v[c][k] + zero, t_low);
                 slot[c][k] = 0u;
-                if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
+                if (valid) slot[c][k] = pack_slot(atomicAdd(&lds.bin_start[bin], 1u), bin, (uint32_t)HALF);
             }
         });
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1213,14 +1241,16 @@ __device__ __forceinline__ void orq_bucket(OrqLds<OrqShape<C>::D, OrqShape<C>::B
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < len);
-                    if (valid) slot[c][k] = lds.bin_start[slot[c][k] & 0xFFFFu] + (slot[c][k] >> 16);
+                    if (valid) slot[c][k] = slot_bin_start(&lds.bin_start[HALF], slot[c][k]) + (slot[c][k] >> 16);
                 }
 #pragma unroll
             for (int c = c0; c < c0 + GROUP; ++c)
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < len);
-                    if (valid) lds.grouped[skewed(slot[c][k])] = __float_as_uint(v[c][k]);
+                    if (valid)
+                        *reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(lds.grouped) + skewed_byte_offset(slot[c][k])) =
+                            __float_as_uint(v[c][k]);
                 }
         };
 #pragma unroll
@@ -1972,14 +2002,15 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
         for (uint32_t i = tid; i < (uint32_t)B; i += THREADS) lds.bin_start[i] = 0u;
         if (tid == 0u) lds.tiny_flag = 0u;
         __syncthreads();
-        uint32_t slot[C][4];  // bin | position inside the bin << 16
+        uint32_t slot[C][4];  // bin | position inside the bin << 16 (pack_slot)
+        const float zero = opaque_zero();
         for_each_chunk<C, FULL>(my_len, [&](int c, auto all) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < my_len);
-                const uint32_t bin = value_bin<HALF, SHIFT>(recompute_from(v[c][k]) + 0.0f, t_low);
+                const uint32_t bin = value_bin<HALF, SHIFT>(v[c][k] + zero, t_low);
                 slot[c][k] = 0u;
-                if (valid) slot[c][k] = bin | (atomicAdd(&lds.bin_start[bin], 1u) << 16);
+                if (valid) slot[c][k] = pack_slot(atomicAdd(&lds.bin_start[bin], 1u), bin, (uint32_t)HALF);
             }
         });
         __syncthreads();
@@ -2007,14 +2038,16 @@ __device__ __forceinline__ void orq_team_bucket(OrqTeamLds<W, C>& lds, const flo
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < my_len);
-                    if (valid) slot[c][k] = lds.bin_start[slot[c][k] & 0xFFFFu] + (slot[c][k] >> 16);
+                    if (valid) slot[c][k] = slot_bin_start(&lds.bin_start[HALF], slot[c][k]) + (slot[c][k] >> 16);
                 }
 #pragma unroll
             for (int c = c0; c < c0 + GROUP; ++c)
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const bool valid = decltype(all)::value || (256u * c + 4u * lane + k < my_len);
-                    if (valid) lds.grouped[skewed(slot[c][k])] = __float_as_uint(v[c][k]);
+                    if (valid)
+                        *reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(lds.grouped) + skewed_byte_offset(slot[c][k])) =
+                            __float_as_uint(v[c][k]);
                 }
         };
 #pragma unroll
