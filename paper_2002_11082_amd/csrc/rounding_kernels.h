@@ -888,61 +888,34 @@ constexpr TeamGreedy team_greedy()
     return g;
 }
 
-// One wavefront's greedy steps packed for a run-time loop: 12 bits (k | l << 4 | r << 8) per step, five steps per word.
-struct TeamSteps {
-    uint64_t packed[2][2];  // [wavefront][word]
-};
-
-template <int S>
-constexpr TeamSteps team_steps(bool with_sweeps)
-{
-    const TeamGreedy g = team_greedy<S>();
-    TeamSteps t{{{0, 0}, {0, 0}}};
-    for (int w = 0; w < 2; ++w)
-        for (int step = 0; step < g.steps; ++step) {
-            uint64_t e = g.entry[w][step];
-            if (w == 0 && with_sweeps) {  // head start of the first sweep
-                if (g.head_step[0] == step) e = 1u | (0u << 4) | (2u << 8);
-                if (g.head_step[1] == step) e = 2u | (1u << 4) | (3u << 8);
-            }
-            t.packed[w][step / 5] |= e << (12 * (step % 5));
-        }
-    return t;
-}
-
-// The solves run in one loop over the steps, so that the kernel holds the solve routine (with its selection in crowded
-// bins and its exact sums) once: unrolled, an eight-level kernel no longer fits the instruction cache.
+// The greedy steps are unrolled (their level indices are compile-time constants: measured 3-4 % faster on 8 levels
+// than one loop over a packed table, at equal register counts).
 template <int S, class Lds, class PickFn>
 __device__ __forceinline__ void orq_team_solve(Lds& lds, PickFn pick, uint32_t wave, uint32_t len, uint32_t sweeps,
                                                uint32_t lane)
 {
     constexpr TeamGreedy greedy = team_greedy<S>();
-    constexpr TeamSteps plain = team_steps<S>(false), ahead = team_steps<S>(true);
     constexpr uint32_t INTERIOR = S - 2;
-    static_assert(greedy.steps <= 10, "two words of five steps");
-    const uint32_t mine = wave < 2u ? wave : 0u;
-    const uint64_t word0 = sweeps > 0u ? ahead.packed[mine][0] : plain.packed[mine][0];
-    const uint64_t word1 = sweeps > 0u ? ahead.packed[mine][1] : plain.packed[mine][1];
-    // steps of the sweeps: two sweeps at a time take INTERIOR + 2 steps, a last single one INTERIOR; the first pair
-    // starts greedy.head steps in (those solves ran beside the greedy ones)
-    const uint32_t pairs = sweeps / 2u, single = sweeps & 1u;
-    const uint32_t sweep_steps = pairs * (INTERIOR + 2u) + single * INTERIOR;
-    const uint32_t head = sweeps > 0u ? (uint32_t)greedy.head : 0u;
-    const uint32_t total = (uint32_t)greedy.steps + (sweep_steps > head ? sweep_steps - head : 0u);
-    for (uint32_t step = 0; step < total; ++step) {
-        uint32_t e = 0u;
-        if (step < (uint32_t)greedy.steps) {
-            e = (uint32_t)((step < 5u ? word0 >> (12u * step) : word1 >> (12u * (step - 5u))) & 0xFFFu);
-        } else {
-            const uint32_t u = step - (uint32_t)greedy.steps + head;  // step among all sweep steps
-            const uint32_t pair_index = u / (INTERIOR + 2u);
-            const bool in_pair = pair_index < pairs;
-            const uint32_t t = in_pair ? u - pair_index * (INTERIOR + 2u) : u - pairs * (INTERIOR + 2u);
-            if (wave == 0u && t < INTERIOR) e = (t + 1u) | (t << 4) | ((t + 2u) << 8);
-            if (wave == 1u && in_pair && t >= 2u) e = (t - 1u) | ((t - 2u) << 4) | (t << 8);
+#pragma unroll
+    for (int step = 0; step < greedy.steps; ++step) {
+        if (wave < 2u) {
+            const uint32_t e = wave == 0u ? greedy.entry[0][step] : greedy.entry[1][step];
+            if (e != 0u) orq_solve_one(lds, pick, e & 15u, (e >> 4) & 15u, (e >> 8) & 15u, len, lane);
+            if (wave == 0u && sweeps > 0u) {  // head start of the first sweep
+                if (greedy.head_step[0] == step) orq_solve_one(lds, pick, 1u, 0u, 2u, len, lane);
+                if (greedy.head_step[1] == step) orq_solve_one(lds, pick, 2u, 1u, 3u, len, lane);
+            }
         }
-        if (wave < 2u && e != 0u) orq_solve_one(lds, pick, e & 15u, (e >> 4) & 15u, (e >> 8) & 15u, len, lane);
         __syncthreads();
+    }
+    for (uint32_t s = 0; s < sweeps; s += 2u) {
+        const bool pair = s + 1u < sweeps;
+        const uint32_t steps = INTERIOR + (pair ? 2u : 0u);
+        for (uint32_t t = (s == 0u ? (uint32_t)greedy.head : 0u); t < steps; ++t) {
+            if (wave == 0u && t < INTERIOR) orq_solve_one(lds, pick, t + 1u, t, t + 2u, len, lane);
+            if (wave == 1u && pair && t >= 2u) orq_solve_one(lds, pick, t - 1u, t - 2u, t, len, lane);
+            __syncthreads();
+        }
     }
 }
 
