@@ -775,7 +775,7 @@ __device__ __forceinline__ double lane_entry_f64(double x, uint32_t at)
 // levels l and r, whose records (and k's) are in lds.lvl_*.  Run by one whole wavefront.
 template <class Lds, class PickFn>
 __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k, uint32_t l, uint32_t r, uint32_t len,
-                                              uint32_t lane)
+                                              double bound, uint32_t lane)
 {
     const float L = uniform_f32(lds.lvl_value[l]);
     const float R = uniform_f32(lds.lvl_value[r]);
@@ -793,7 +793,7 @@ __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k,
         const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)count_in;
         const double width = (double)R - (double)L;
         double m;
-        if (!floor_t_from_sums(Ssum, width, uniform_f64(lds.sum_error_bound), m)) {
+        if (!floor_t_from_sums(Ssum, width, bound, m)) {
             // the fp64 sums do not decide floor(T): exact sums of the elements in [L, R] (rare)
             m = (double)exact_floor_t_grouped(
                 lds.exact_limb[(threadIdx.x >> 6) & (sizeof(lds.exact_limb) / sizeof(lds.exact_limb[0]) - 1u)], lds.grouped, len,
@@ -896,14 +896,15 @@ __device__ __forceinline__ void orq_team_solve(Lds& lds, PickFn pick, uint32_t w
 {
     constexpr TeamGreedy greedy = team_greedy<S>();
     constexpr uint32_t INTERIOR = S - 2;
+    const double bound = uniform_f64(lds.sum_error_bound);  // (see floor_t_from_sums)
 #pragma unroll
     for (int step = 0; step < greedy.steps; ++step) {
         if (wave < 2u) {
             const uint32_t e = wave == 0u ? greedy.entry[0][step] : greedy.entry[1][step];
-            if (e != 0u) orq_solve_one(lds, pick, e & 15u, (e >> 4) & 15u, (e >> 8) & 15u, len, lane);
+            if (e != 0u) orq_solve_one(lds, pick, e & 15u, (e >> 4) & 15u, (e >> 8) & 15u, len, bound, lane);
             if (wave == 0u && sweeps > 0u) {  // head start of the first sweep
-                if (greedy.head_step[0] == step) orq_solve_one(lds, pick, 1u, 0u, 2u, len, lane);
-                if (greedy.head_step[1] == step) orq_solve_one(lds, pick, 2u, 1u, 3u, len, lane);
+                if (greedy.head_step[0] == step) orq_solve_one(lds, pick, 1u, 0u, 2u, len, bound, lane);
+                if (greedy.head_step[1] == step) orq_solve_one(lds, pick, 2u, 1u, 3u, len, bound, lane);
             }
         }
         __syncthreads();
@@ -912,8 +913,8 @@ __device__ __forceinline__ void orq_team_solve(Lds& lds, PickFn pick, uint32_t w
         const bool pair = s + 1u < sweeps;
         const uint32_t steps = INTERIOR + (pair ? 2u : 0u);
         for (uint32_t t = (s == 0u ? (uint32_t)greedy.head : 0u); t < steps; ++t) {
-            if (wave == 0u && t < INTERIOR) orq_solve_one(lds, pick, t + 1u, t, t + 2u, len, lane);
-            if (wave == 1u && pair && t >= 2u) orq_solve_one(lds, pick, t - 1u, t - 2u, t, len, lane);
+            if (wave == 0u && t < INTERIOR) orq_solve_one(lds, pick, t + 1u, t, t + 2u, len, bound, lane);
+            if (wave == 1u && pair && t >= 2u) orq_solve_one(lds, pick, t - 1u, t - 2u, t, len, bound, lane);
             __syncthreads();
         }
     }
@@ -929,6 +930,29 @@ __device__ __forceinline__ double sum_before_position(const Lds& lds, uint32_t p
     const uint32_t block_first = block * BLOCK;
     const float head = lane < position - block_first ? __uint_as_float(lds.grouped[skewed(block_first + lane)]) : 0.0f;
     return uniform_f64(lds.block_prefix[block]) + wave_sum((double)head);
+}
+
+// Run solve(k, l, r) with compile-time level indices: the greedy order of Algorithm 1, and one re-solve sweep.
+template <int S, int STEP, class Solve>
+__device__ __forceinline__ void for_greedy_steps(Solve&& solve)
+{
+    constexpr GreedyOrder order = greedy_order<S>();
+    if constexpr (STEP < order.count) {
+        constexpr uint32_t e =
+            STEP < 5 ? (uint32_t)(order.packed[0] >> (12 * STEP)) : (uint32_t)(order.packed[1] >> (12 * (STEP - 5)));
+        solve(std::integral_constant<int, (int)(e & 15u)>{}, std::integral_constant<int, (int)((e >> 4) & 15u)>{},
+              std::integral_constant<int, (int)((e >> 8) & 15u)>{});
+        for_greedy_steps<S, STEP + 1>(solve);
+    }
+}
+
+template <int S, int K, class Solve>
+__device__ __forceinline__ void for_sweep_levels(Solve&& solve)
+{
+    if constexpr (K + 1 < S) {
+        solve(std::integral_constant<int, K>{}, std::integral_constant<int, K - 1>{}, std::integral_constant<int, K + 1>{});
+        for_sweep_levels<S, K + 1>(solve);
+    }
 }
 
 // The level solves of one bucket, run by one wavefront once the bucket is grouped in LDS and the level
@@ -1064,7 +1088,16 @@ __device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, EdgeFn 
     }
 
     // ---- level solves: greedy recursion (Algorithm 1), then re-solve sweeps ------------------
-    if constexpr (S > 2 && RULE == kOptimal) {
+    [[maybe_unused]] const double bound = RULE == kOptimal ? uniform_f64(lds.sum_error_bound) : 0.0;  // (see floor_t_from_sums)
+    if constexpr (S > 2 && S <= 5 && RULE == kOptimal) {
+        // few levels: every solve with compile-time level indices (S - 2 + greedy copies of the routine)
+        auto solve = [&](auto kc, auto lc, auto rc) {
+            orq_solve_one(lds, pick, (uint32_t)decltype(kc)::value, (uint32_t)decltype(lc)::value, (uint32_t)decltype(rc)::value,
+                          len, bound, lane);
+        };
+        for_greedy_steps<S, 0>(solve);
+        for (uint32_t sweep = 0; sweep < sweeps; ++sweep) for_sweep_levels<S, 1>(solve);
+    } else if constexpr (S > 2 && RULE == kOptimal) {
     constexpr GreedyOrder order = greedy_order<S>();
     const uint32_t steps = order.count + sweeps * (S - 2);
     for (uint32_t step = 0; step < steps; ++step) {
@@ -1077,7 +1110,7 @@ __device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, EdgeFn 
             k = 1u + (step - order.count) % (S - 2);
             l = k - 1u; r = k + 1u;
         }
-        orq_solve_one(lds, pick, k, l, r, len, lane);
+        orq_solve_one(lds, pick, k, l, r, len, bound, lane);
     }
     }
     return pb_level;
@@ -1580,28 +1613,6 @@ struct RowLevels {
     uint32_t count_lt[S], count_le[S], rank[S];
     double sum_lt[S], sum_le[S];
 };
-
-template <int S, int STEP, class Solve>
-__device__ __forceinline__ void for_greedy_steps(Solve&& solve)
-{
-    constexpr GreedyOrder order = greedy_order<S>();
-    if constexpr (STEP < order.count) {
-        constexpr uint32_t e =
-            STEP < 5 ? (uint32_t)(order.packed[0] >> (12 * STEP)) : (uint32_t)(order.packed[1] >> (12 * (STEP - 5)));
-        solve(std::integral_constant<int, (int)(e & 15u)>{}, std::integral_constant<int, (int)((e >> 4) & 15u)>{},
-              std::integral_constant<int, (int)((e >> 8) & 15u)>{});
-        for_greedy_steps<S, STEP + 1>(solve);
-    }
-}
-
-template <int S, int K, class Solve>
-__device__ __forceinline__ void for_sweep_levels(Solve&& solve)
-{
-    if constexpr (K + 1 < S) {
-        solve(std::integral_constant<int, K>{}, std::integral_constant<int, K - 1>{}, std::integral_constant<int, K + 1>{});
-        for_sweep_levels<S, K + 1>(solve);
-    }
-}
 
 template <int S, int BITS, int NB, bool FULL, int RULE>
 __device__ __forceinline__ void sorted_small_span(const float* __restrict__ g, uint32_t len, size_t begin, uint32_t first_bucket,
