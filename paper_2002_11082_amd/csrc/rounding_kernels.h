@@ -828,6 +828,64 @@ __device__ __forceinline__ void orq_solve_one(Lds& lds, PickFn pick, uint32_t k,
     __builtin_amdgcn_wave_barrier();
 }
 
+// The level records of a bucket held by the wavefront itself (wave-uniform values in registers): what lds.lvl_* keeps,
+// for the kernels whose solves all have compile-time level indices.
+template <int S>
+struct LevelRecords {
+    float value[S];
+    uint32_t count_lt[S], count_le[S], rank[S];
+    double sum_lt[S], sum_le[S];
+};
+
+// orq_solve_one on such records: level K between the levels L_ and R_.
+template <int K, int L_, int R_, int S, class Lds, class PickFn>
+__device__ __forceinline__ void orq_solve_one_in_registers(LevelRecords<S>& st, Lds& lds, PickFn pick, uint32_t len,
+                                                           double bound, uint32_t lane)
+{
+    const float L = st.value[L_], R = st.value[R_];
+    const uint32_t cnt_lt_L = st.count_lt[L_], cnt_le_R = st.count_le[R_];
+    const double sum_lt_L = st.sum_lt[L_], sum_le_R = st.sum_le[R_];
+    if (!(L < R)) {
+        // the level coincides with both ends
+        st.value[K] = L;
+        st.count_lt[K] = cnt_lt_L;
+        st.sum_lt[K] = sum_lt_L;
+        st.count_le[K] = cnt_le_R;
+        st.sum_le[K] = sum_le_R;
+        st.rank[K] = 0u;
+        return;
+    }
+    // S = sum_{L<=v<=R} (v - L),  T = S / (R - L),  level = element of rank #{v<=R} - floor(T)
+    const uint32_t count_in = cnt_le_R - cnt_lt_L;
+    const double Ssum = (sum_le_R - sum_lt_L) - (double)L * (double)count_in;
+    const double width = (double)R - (double)L;
+    double m;
+    if (!floor_t_from_sums(Ssum, width, bound, m)) {
+        // the fp64 sums do not decide floor(T): exact sums of the elements in [L, R] (rare)
+        m = (double)exact_floor_t_grouped(lds.exact_limb[0], lds.grouped, len, lane, kWave, L, R, count_in, (uint32_t)m);
+    }
+    uint32_t rank = (m >= (double)cnt_le_R) ? 1u : cnt_le_R - (uint32_t)m;
+    rank = rank < 1u ? 1u : (rank > len ? len : rank);
+    if (rank == st.rank[K]) return;  // same element as last time
+    const Picked p = pick(rank);
+    if (key_to_float(p.key) < L) {
+        // rounding put the level below L: it coincides with the left end
+        st.value[K] = L;
+        st.count_lt[K] = cnt_lt_L;
+        st.sum_lt[K] = sum_lt_L;
+        st.count_le[K] = st.count_le[L_];
+        st.sum_le[K] = st.sum_le[L_];
+        st.rank[K] = 0u;
+    } else {
+        st.value[K] = key_to_float(p.key);
+        st.count_lt[K] = p.count_lt;
+        st.count_le[K] = p.count_le;
+        st.sum_lt[K] = p.sum_lt;
+        st.sum_le[K] = p.sum_le;
+        st.rank[K] = rank;
+    }
+}
+
 // Schedule of the level solves over the first two wavefronts of a team (Algorithm 1 and the re-solve sweeps;
 // the results are those of the serial order).  Greedy: after the root, the solves of the left half only touch levels
 // up to the root and those of the right half only levels from the root on, so wavefront 0 takes the left and
@@ -1089,8 +1147,30 @@ __device__ __forceinline__ float orq_solve_levels(Lds& lds, PickFn pick, EdgeFn 
 
     // ---- level solves: greedy recursion (Algorithm 1), then re-solve sweeps ------------------
     [[maybe_unused]] const double bound = RULE == kOptimal ? uniform_f64(lds.sum_error_bound) : 0.0;  // (see floor_t_from_sums)
-    if constexpr (S > 2 && S <= 5 && RULE == kOptimal) {
-        // few levels: every solve with compile-time level indices (S - 2 + greedy copies of the routine)
+    if constexpr (S > 2 && S <= 4 && RULE == kOptimal && std::is_same_v<decltype(lds.exact_limb), unsigned long long[1][kExactLimbs]>) {
+        // One wavefront, three or four levels: every solve with compile-time level indices and the level records in the
+        // wavefront's registers instead of LDS (greedy + S - 2 copies of the routine; with five levels the records no
+        // longer fit the 128 registers).
+        LevelRecords<S> st;
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+            st.value[k] = uniform_f32(lds.lvl_value[k]);
+            st.rank[k] = 0u;
+            st.count_lt[k] = st.count_le[k] = k == S - 1 ? len : 0u;
+            st.sum_lt[k] = st.sum_le[k] = k == S - 1 ? uniform_f64(lds.lvl_sum_le[S - 1]) : 0.0;
+        }
+        auto solve = [&](auto kc, auto lc, auto rc) {
+            orq_solve_one_in_registers<decltype(kc)::value, decltype(lc)::value, decltype(rc)::value>(st, lds, pick, len, bound, lane);
+        };
+        for_greedy_steps<S, 0>(solve);
+        for (uint32_t sweep = 0; sweep < sweeps; ++sweep) for_sweep_levels<S, 1>(solve);
+        if (lane == 0u) {
+#pragma unroll
+            for (int k = 1; k < S - 1; ++k) lds.lvl_value[k] = st.value[k];
+        }
+        wave_lds_sync();
+    } else if constexpr (S > 2 && S <= 5 && RULE == kOptimal) {
+        // few levels: every solve with compile-time level indices
         auto solve = [&](auto kc, auto lc, auto rc) {
             orq_solve_one(lds, pick, (uint32_t)decltype(kc)::value, (uint32_t)decltype(lc)::value, (uint32_t)decltype(rc)::value,
                           len, bound, lane);
