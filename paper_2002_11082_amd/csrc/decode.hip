@@ -158,7 +158,9 @@ __device__ __forceinline__ void for_each_group(const uint32_t (&turned)[R], F&& 
 // 1, 2, 4 or 8 = bucket_size 64 .. 512, the span holds 16 / WPB buckets whose level tables are
 // consecutive in memory.  Each table is fetched once per span and worker.  WPB = 0: any other bucket
 // size, the table is looked up per word group.
-template <int BITS, int S, int WPB>
+// ONE: the launch has a single worker (its own instantiation: without the fp64 sums of the general case the kernel
+// needs half the registers, and twice the wavefronts are in flight to hide the first trip to HBM).
+template <int BITS, int S, int WPB, bool ONE>
 __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs ptrs, uint32_t num_workers, size_t n,
                                                                     uint32_t words_per_bucket, uint32_t total_words,
                                                                     double inv_workers, float* __restrict__ out)
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
         const uint32_t first_bucket = WPB == kSpanWords ? word0 / words_per_bucket : word0 / (uint32_t)kWpb;
         const uint32_t wave = uniform_u32(threadIdx.x >> 6);
         bool combined = false;
-        if constexpr (kTables <= 2) {
+        if constexpr (kTables <= 2 && !ONE) {
           if (num_workers > 1u) {
             combined = true;
             // Several workers per look-up: K workers' indices of an element form one index of K * BITS bits into a
@@ -296,7 +298,7 @@ __global__ __launch_bounds__(kBlock) void dequantize_average_kernel(WorkerPtrs p
             constexpr uint32_t BATCH = R + LR > 2 ? 4 : 8;    // workers whose loads are in flight together
             __shared__ float level_tables[kWavesPerBlock][BATCH * kTables * S];
             float* my_tables = level_tables[wave];
-            const bool one_worker = num_workers == 1u;
+            constexpr bool one_worker = ONE;
             for (uint32_t w0 = 0; w0 < num_workers; w0 += BATCH) {
                 uint32_t code_reg[BATCH][R];
                 float level_reg[BATCH][LR];
@@ -442,9 +444,15 @@ void launch_decode(const void* const* d_codes, const float* const* d_levels, uin
     const uint32_t wpb = d / 64;
     const uint32_t span_elements = kSpanWords * 64;
     const uint32_t fixed_wpb = d % span_elements == 0 ? (uint32_t)kSpanWords : (span_elements % d == 0 ? wpb : 0u);
-#define OGQ_LAUNCH_DEQUANT_WPB(BITS, S, WPB)                                                                      \
-    launch_kernel((dequantize_average_kernel<BITS, S, WPB>), grid, block, st, ptrs, num_workers, n, wpb, \
-                       total_words, inv, d_out)
+#define OGQ_LAUNCH_DEQUANT_WPB(BITS, S, WPB)                                                                              \
+    do {                                                                                                                 \
+        if (num_workers == 1u)                                                                                           \
+            launch_kernel((dequantize_average_kernel<BITS, S, WPB, true>), grid, block, st, ptrs, num_workers, n, wpb,   \
+                          total_words, inv, d_out);                                                                      \
+        else                                                                                                             \
+            launch_kernel((dequantize_average_kernel<BITS, S, WPB, false>), grid, block, st, ptrs, num_workers, n, wpb,  \
+                          total_words, inv, d_out);                                                                      \
+    } while (0)
 #define OGQ_LAUNCH_DEQUANT(BITS, S)                                \
     do {                                                           \
         switch (fixed_wpb) {                                       \
