@@ -10,8 +10,9 @@
 //                          Section 3.1), BinGrad-pb and the evenly spaced / Linear-s comparison rules: every
 //                          level solve is a range sum plus an exact rank selection over the bucket grouped in
 //                          LDS; Philox4x32-10 draws keyed by (seed, global element index).
-//   decode.hip             decode-average (server step of Algorithm 2): the packed 64-bit words are used
-//                          directly as lane masks of v_cndmask selects over the bucket's level table.
+//   decode.hip             decode-average (server step of Algorithm 2): a bit-matrix transpose across the lanes turns
+//                          the packed words into per-element level indices, which address level tables in LDS
+//                          (several workers per look-up through tables of pre-summed level combinations).
 // This file validates the arguments and picks the launcher (launch.h).
 //
 // Compile with -ffp-contract=off: the rounding decision of ORQ is specified op by op in fp32.

@@ -8,9 +8,10 @@
 namespace ogq {
 
 // ----------------------------------------------------------------------------------------------
-// Decode + average.  One wavefront decodes a segment of up to 16 packed words (1024 elements)
-// that lies inside one bucket; lane l owns element 64*j + l of word j, so the packed words are
-// the lane masks of the level selects.
+// Decode + average.  One wavefront decodes a span of up to 16 packed word groups (1024 elements); lane l owns
+// element 64*j + l of word group j.  Complete spans of bucket sizes with a fixed layout turn the code bits into
+// per-lane level indices and look the levels up in LDS (below); the ragged last span and the other bucket sizes use
+// the packed words directly as the lane masks of a tree of selects.
 // ----------------------------------------------------------------------------------------------
 struct WorkerPtrs {
     const uint64_t* codes[OGQ_MAX_WORKERS];
